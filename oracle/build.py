@@ -1,0 +1,24 @@
+"""Compile the CPU oracle (plain C, gcc) into oracle/libznni_ref.so.
+
+Test infrastructure only: building the checker is not using it.  No -march flag is given, so the
+library built in one container also runs on a host with a different CPU.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "znni_ref.c")
+LIB = os.path.join(HERE, "libznni_ref.so")
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-O3", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", LIB, SRC]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())
