@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned-FFT 3D convolutional layer on one MI355X.
+
+A step is one whole layer call (kernel prep, three forward passes, multiply-accumulate, three inverse passes)
+on inputs already resident in HBM with a pre-allocated workspace.  The timed steps go through the profiling
+entry point, which records a HIP event on the launch stream between stages, so the per-stage durations behind
+the roofline figures come from the same timed region as the throughput.  One JSON line is printed.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3    # dense fp32 matrix, published
+# Plain-VALU fp32 without packed instructions (this build switches them off):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz.
+VALU_FP32_UNPACKED_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+
+
+def algorithmic_work(L, N):
+    """Bytes / flops the method itself has to move / do per stage of one layer call."""
+    S, f, fo, n, k = L.S, L.f, L.fo, L.n, L.k
+    no = n - k + 1
+    zc = N // 2 + 1
+    bins = zc * N * N
+    c = 8  # bytes per complex
+    nimg, nimgo = S * f, S * fo
+    return {
+        "fwd_z": ("bytes", nimg * (4 * n ** 3 + c * n * n * zc)),
+        "fwd_y": ("bytes", nimg * (c * n * n * zc + c * n * N * zc)),
+        "fwd_x": ("bytes", nimg * (c * n * N * zc + c * bins)),
+        "kernel_prep": ("bytes", 4 * fo * f * k ** 3 + c * zc * N * fo * f * k),
+        # complex multiply-add = 8 flops; the last kernel-transform stage is a k-term sum per bin
+        "mac": ("flops", (8 * S + 8 * (k - 1)) * f * fo * bins),
+        "inv_x": ("bytes", nimgo * (c * bins + c * zc * no * N)),
+        "inv_y": ("bytes", nimgo * (c * zc * no * N + c * no * no * zc)),
+        "inv_z": ("bytes", nimgo * (c * no * no * zc + 4 * no ** 3)),
+    }
+
+
+def cpu_baseline(layer, workloads):
+    """The oracle, as it stands, on a bounded sample: a cubic crop of the layer's input, as many output
+    images as there are host threads (the oracle parallelises over (s, j) pairs)."""
+    import numpy as np
+    from oracle import ref
+    threads = ref.max_threads()
+    fo_s = min(layer.fo, threads)
+    # crop edge so the sample costs roughly 2e11 multiply-adds (tens of seconds on a many-core host)
+    budget = 2.0e11
+    n_s = layer.n
+    while n_s > layer.k and layer.S * fo_s * layer.f * layer.k ** 3 * (n_s - layer.k + 1) ** 3 > budget:
+        n_s -= 1
+    rng = np.random.default_rng(0)
+    inp = rng.uniform(-1, 1, (layer.S, layer.f, n_s, n_s, n_s)).astype(np.float32)
+    w = (rng.standard_normal((fo_s, layer.f, layer.k, layer.k, layer.k))
+         * (layer.f * layer.k ** 3) ** -0.5).astype(np.float32)
+    b = (rng.standard_normal(fo_s) * np.sqrt(0.1)).astype(np.float32)
+    t0 = time.perf_counter()
+    out = ref.conv3d(inp, w, b, relu=layer.relu)
+    dt = time.perf_counter() - t0
+    return {
+        "value": out.size / dt, "unit": "output voxels/s", "cores": min(threads, layer.S * fo_s),
+        "kind": "oracle",
+        "sample": f"fp64 direct convolution of a {n_s}^3 crop, S={layer.S}, f={layer.f}, {fo_s} of {layer.fo} "
+                  f"output images, k={layer.k} ({out.size} output voxels in {dt:.1f} s; cost per output voxel "
+                  f"is uniform: f*k^3 multiply-adds)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_1606_05688_amd import binding as B
+    from paper_1606_05688_amd import workloads as W
+
+    layer = W.CONFIGS[args.config - 1]
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
+    # synthetic inputs of the layer's distribution, drawn on the device (values do not affect timing)
+    inp = torch.rand((S, f, n, n, n), device=dev, generator=g) * 2 - 1
+    w = torch.randn((fo, f, k, k, k), device=dev, generator=g) * (f * k ** 3) ** -0.5
+    bias = torch.randn((fo,), device=dev, generator=g) * 0.1 ** 0.5 if layer.bias else None
+    out = torch.empty((S, fo, n - k + 1, n - k + 1, n - k + 1), device=dev)
+    ws = B.alloc_workspace(S, f, fo, n, k, dev)
+    N = B.znni_fft_size(n)
+
+    for _ in range(args.warmup):
+        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+    torch.cuda.synchronize()
+
+    stage_sum = {s: 0.0 for s in B.STAGES}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        _, ms = B.znni_conv3d_fft_profile(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+        for s_, v in ms.items():
+            stage_sum[s_] += v
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    stage_ms = {s_: v / args.steps for s_, v in stage_sum.items()}
+
+    # the same steps through the plain asynchronous entry point, for reference
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    ms_plain = 1e3 * (time.perf_counter() - t1) / args.steps
+
+    work = algorithmic_work(layer, N)
+    stages = {}
+    for s_, (kind, amount) in work.items():
+        t = stage_ms[s_] * 1e-3
+        if kind == "bytes":
+            ach = amount / t / 1e9 if t > 0 else 0.0
+            stages[s_] = {"ms": stage_ms[s_], "GB": amount / 1e9, "GB/s": ach, "frac_hbm": ach / HBM_PEAK_GBS}
+        else:
+            ach = amount / t / 1e12 if t > 0 else 0.0
+            stages[s_] = {"ms": stage_ms[s_], "GFLOP": amount / 1e9, "TFLOP/s": ach,
+                          "frac_peak": ach / MFMA_FP32_PEAK_TFLOPS}
+    dom = max(B.STAGES, key=lambda s_: stage_ms[s_])
+    kind, amount = work[dom]
+    t = stage_ms[dom] * 1e-3
+    if kind == "bytes":
+        roof = {"kernel": dom, "bound": "hbm", "achieved": amount / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"kernel": dom, "bound": "mfma", "achieved": amount / t / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["avg_launch_ms"] = stage_ms[dom]
+    fft_bytes = sum(work[s_][1] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
+    fft_ms = sum(stage_ms[s_] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
+
+    rec = {
+        "metric": "output voxels/sec per conv layer at 1 GPU",
+        "value": layer.out_voxels / (ms_per_step * 1e-3),
+        "unit": "output voxels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "ms_per_step_async_entry": ms_plain,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": layer.name, "S": S, "f": f, "f_out": fo, "n": n, "k": k,
+                   "fft_size": N, "out_voxels": layer.out_voxels, "relu": layer.relu, "bias": layer.bias},
+        "roofline": roof,
+        "fft_passes": {"GB": fft_bytes / 1e9, "ms": fft_ms, "GB/s": fft_bytes / (fft_ms * 1e-3) / 1e9,
+                       "frac_hbm": fft_bytes / (fft_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(layer, W)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

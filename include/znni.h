@@ -1,0 +1,115 @@
+/*
+ * znni.h -- C ABI of the pruned-FFT 3D convolutional layer for AMD MI355X (gfx950).
+ *
+ * The layer (paper Section IV): a batch of S inputs, each a tuple of f images of n^3 voxels, is turned into
+ * S tuples of f' images of n'^3 voxels, n' = n - k + 1, by
+ *
+ *     O[s][j] = act( bias[j] + sum_{i<f} w[j][i] * I[s][i] )          (* = valid convolution, kernel flipped)
+ *
+ * computed with the convolution theorem (Section III-A) in three stages, as in the GPU algorithm of
+ * Section IV-B-2 (Algorithm 3): forward transforms of the S*f images, a multiply-accumulate over the input
+ * images in every frequency bin, inverse transforms of the S*f' accumulated spectra.  Kernel transforms are
+ * pruned as in Section III-A (k^2, then k*n~, then n~^2 one-dimensional transforms) and their last stage is
+ * evaluated inside the multiply-accumulate kernel, so no full-size kernel spectrum is ever stored.  Bias and
+ * transfer function are applied where the inverse transform finishes an output image (Section IV-A-3).
+ *
+ * Conventions for every function below
+ *   - Returns a znni_status; never throws, aborts or prints.
+ *   - Every argument is validated on the host BEFORE the first HIP call, so argument errors are reported the
+ *     same way on a machine without a GPU.
+ *   - Pointers named in/w/bias/out/workspace are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or reallocates device memory and keeps no device state between calls.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns without synchronising, except znni_conv3d_fft_profile, which synchronises the stream.
+ *   - Results are deterministic: no floating-point atomics, fixed summation order.
+ *   - Tensors are dense, row-major, last index fastest; all arithmetic is fp32.
+ */
+#ifndef ZNNI_H
+#define ZNNI_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZNNI_OK = 0,
+    ZNNI_ERR_NULL = -1,             /* a required pointer is NULL                                         */
+    ZNNI_ERR_SHAPE = -2,            /* S, f, f' < 1, k < 1, k > n, or a count too large for the launch grid */
+    ZNNI_ERR_UNSUPPORTED_SIZE = -3, /* no supported transform size n~ >= n                                 */
+    ZNNI_ERR_WORKSPACE = -4,        /* workspace smaller than znni_conv3d_fft_workspace reports            */
+    ZNNI_ERR_FLAGS = -5,            /* unknown flag bit                                                    */
+    ZNNI_ERR_HIP = -6,              /* a HIP call or kernel launch failed                                  */
+    ZNNI_ERR_ALIGN = -7             /* a device pointer is not 16-byte aligned (workspace: 256-byte)       */
+} znni_status;
+
+/* flags */
+enum {
+    ZNNI_RELU = 1u                  /* transfer function max(0, .) (Section V); without it: identity       */
+};
+
+/* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */
+enum {
+    ZNNI_STAGE_KERNEL_PREP = 0,     /* pruned kernel transform, first two axes (Section III-A)             */
+    ZNNI_STAGE_FWD_Z = 1,           /* image transform, real-to-complex along z (Section III-C)            */
+    ZNNI_STAGE_FWD_Y = 2,
+    ZNNI_STAGE_FWD_X = 3,
+    ZNNI_STAGE_MAC = 4,             /* last kernel-transform stage + per-bin multiply-accumulate           */
+    ZNNI_STAGE_INV_X = 5,           /* inverse transforms, pruned to the valid outputs (Section III-B)     */
+    ZNNI_STAGE_INV_Y = 6,
+    ZNNI_STAGE_INV_Z = 7,           /* complex-to-real along z + bias + transfer function                  */
+    ZNNI_NUM_STAGES = 8
+};
+
+/* Library version, major*10000 + minor*100 + patch. */
+int znni_version(void);
+
+/* Static string for a status code (never NULL). */
+const char* znni_status_string(znni_status st);
+
+/*
+ * Transform size n~ used for an image edge n: the smallest supported size >= n.  Supported sizes are the
+ * products 2^a 3^b 5^c 7^d (the family Section III-D names for GPU transforms) up to ZNNI_MAX_FFT.
+ * Because the valid outputs of a circular convolution of length n~ >= n never wrap, n~ = n is used whenever
+ * n itself is supported.  Returns 0 if there is none.  Host only; touches no GPU.
+ */
+#define ZNNI_MAX_FFT 1024
+int znni_fft_size(int n);
+
+/*
+ * Bytes of device workspace znni_conv3d_fft needs for this layer shape (Table II's GPU-FFT row plays the
+ * same role in the paper: spectra of the inputs and outputs plus per-call scratch).  Host only.
+ *   S, f, fo (= f'), n, k : layer shape as in Section IV.        bytes : out, host pointer.
+ */
+znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t* bytes);
+
+/*
+ * The layer (Section IV equation; Algorithm 3).  Asynchronous on `stream`.
+ *   in        [S][f][n][n][n]          device, read-only
+ *   w         [fo][f][k][k][k]         device, read-only
+ *   bias      [fo] device, read-only, or NULL for zero bias
+ *   out       [S][fo][n-k+1]^3         device, written (every element)
+ *   flags     ZNNI_RELU or 0
+ *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
+ *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
+ *             not overlap in time.
+ */
+znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k,
+                            const float* in, const float* w, const float* bias, float* out,
+                            unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same computation, with a HIP event recorded on `stream` between stages; synchronises `stream` before
+ * returning and writes the elapsed milliseconds of each stage to stage_ms[ZNNI_NUM_STAGES] (HOST pointer).
+ * Meant for measurement: creates and destroys its events on every call.
+ */
+znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
+                                    const float* in, const float* w, const float* bias, float* out,
+                                    unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
+                                    float* stage_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZNNI_H */

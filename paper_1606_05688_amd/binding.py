@@ -1,0 +1,119 @@
+"""Thin ctypes binding of libznni.so (declared in include/znni.h): argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the layer runs in the library's HIP kernels.
+There is no fallback: if the compiled library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch  # imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libznni.so")
+
+OK = 0
+RELU = 1
+STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
+EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
+           "znni_conv3d_fft", "znni_conv3d_fft_profile")
+
+_lib = None
+
+
+class ZnniError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"znni status {status}: {message}")
+        self.status = status
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1606_05688_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        i, u, vp, sz = ctypes.c_int, ctypes.c_uint, ctypes.c_void_p, ctypes.c_size_t
+        L.znni_version.restype = i
+        L.znni_status_string.restype = ctypes.c_char_p
+        L.znni_status_string.argtypes = [i]
+        L.znni_fft_size.restype = i
+        L.znni_fft_size.argtypes = [i]
+        L.znni_conv3d_fft_workspace.restype = i
+        L.znni_conv3d_fft_workspace.argtypes = [i, i, i, i, i, ctypes.POINTER(sz)]
+        L.znni_conv3d_fft.restype = i
+        L.znni_conv3d_fft.argtypes = [i, i, i, i, i, vp, vp, vp, vp, u, vp, sz, vp]
+        L.znni_conv3d_fft_profile.restype = i
+        L.znni_conv3d_fft_profile.argtypes = [i, i, i, i, i, vp, vp, vp, vp, u, vp, sz, vp,
+                                              ctypes.POINTER(ctypes.c_float)]
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != OK:
+        raise ZnniError(status, lib().znni_status_string(status).decode())
+
+
+def znni_version():
+    return int(lib().znni_version())
+
+
+def znni_fft_size(n):
+    return int(lib().znni_fft_size(int(n)))
+
+
+def znni_conv3d_fft_workspace(S, f, fo, n, k):
+    b = ctypes.c_size_t(0)
+    _check(lib().znni_conv3d_fft_workspace(int(S), int(f), int(fo), int(n), int(k), ctypes.byref(b)))
+    return int(b.value)
+
+
+def alloc_workspace(S, f, fo, n, k, device="cuda"):
+    """A torch byte tensor large enough for the layer (torch allocations are at least 256-byte aligned)."""
+    return torch.empty(znni_conv3d_fft_workspace(S, f, fo, n, k), dtype=torch.uint8, device=device)
+
+
+def _marshal(inp, w, bias, out, workspace):
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
+    assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 5
+    S, f, n = inp.shape[0], inp.shape[1], inp.shape[2]
+    assert inp.shape[3] == n and inp.shape[4] == n, "cubic images only"
+    fo, k = w.shape[0], w.shape[2]
+    assert w.shape[1] == f and w.shape[3] == k and w.shape[4] == k, "kernel bank must be [f', f, k, k, k]"
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and bias.shape == (fo,)
+    if out is None:
+        out = torch.empty((S, fo, n - k + 1, n - k + 1, n - k + 1), dtype=torch.float32, device=inp.device)
+    else:
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (S, fo, n - k + 1, n - k + 1, n - k + 1)
+    if workspace is None:
+        workspace = alloc_workspace(S, f, fo, n, k, inp.device)
+    assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+    return S, f, fo, n, k, out, workspace
+
+
+def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None):
+    """out[S,f',n-k+1,...] = act(bias + valid 3D convolution of inp[S,f,n,n,n] with w[f',f,k,k,k]).
+
+    Asynchronous on `stream` (a torch.cuda.Stream; default: torch's current stream)."""
+    S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(lib().znni_conv3d_fft(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
+                                 bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                                 RELU if relu else 0, workspace.data_ptr(), workspace.numel(),
+                                 st.cuda_stream))
+    return out
+
+
+def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None):
+    """Same call with per-stage HIP-event timing; returns (out, {stage: milliseconds}).  Synchronises."""
+    S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    ms = (ctypes.c_float * len(STAGES))()
+    _check(lib().znni_conv3d_fft_profile(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
+                                         bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                                         RELU if relu else 0, workspace.data_ptr(), workspace.numel(),
+                                         st.cuda_stream, ms))
+    return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}

@@ -1,0 +1,328 @@
+// passes.hip -- the six transform passes of the layer, for any supported transform length.
+//
+// Forward (Section III-C order: the contiguous axis z first, real-to-complex, then y, then x) and inverse
+// (the same steps in reverse, Section III-B/C).  Where the paper permutes the 4-D tensor between
+// library calls, each pass here reads TL whole lines that are contiguous along the axis being transformed,
+// transforms them in LDS, and writes them back with the NEXT axis contiguous, so every pass both reads and
+// writes HBM in contiguous runs and the tensor is touched exactly once per pass.  Like the paper's GPU
+// transform, the result is left in permuted order because only bin-wise work follows.
+//
+// Pruning (Section III-A): lines that are zero padding are never read or transformed (they only exist when
+// n~ > n); on the inverse side only the n' = n-k+1 valid outputs of a line are stored, so the later passes
+// run n'/n~ (y) and (n'/n~)^2 (z) of the lines.
+//
+// Layouts (N = n~, zc = N/2+1, no = n', img = s*f + i, imgo = s*f' + j; all complex interleaved fp32):
+//   in  [img][x<n][y<n][z<n]              real
+//   X1  [img][x<n][oz<zc][y<n]            after z
+//   X2  [img][oz][oy<N][x<n]              after y
+//   Xt  [oz][oy][img][ox<N]               after x   ("pencil" order: one (oz,oy) pair holds all images)
+//   Yt  [oz][oy][imgo][ox<N]              accumulated output spectra
+//   Y2  [imgo][oz][xo<no][oy<N]           after inverse x, cropped to valid x
+//   Y1  [imgo][xo][yo<no][oz<zc (ldz)]    after inverse y, cropped to valid y
+//   out [imgo][xo][yo][zo<no]             real, after inverse z + bias + transfer function
+#include "znni_internal.h"
+
+namespace znni {
+
+__global__ void k_twiddles(float2* tw, int N)
+{
+    int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < N) {
+        double s, c;
+        sincospi(2.0 * (double)q / (double)N, &s, &c);
+        tw[q] = make_float2((float)c, (float)(-s));
+    }
+}
+
+struct Lds {
+    float2* tw;
+    float2* a;
+    float2* b;
+    int ld;
+};
+
+__device__ __forceinline__ Lds carve(float2* base, int N, int nlines, const float2* __restrict__ twg)
+{
+    Lds L;
+    L.ld = N | 1;
+    L.tw = base;
+    L.a = base + N;
+    L.b = L.a + nlines * L.ld;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) L.tw[q] = twg[q];
+    return L;
+}
+
+// ---- forward, axis z: real -> complex.  Two real lines ride through one complex transform.
+__global__ void k_fwd_z(const float* __restrict__ in, float2* __restrict__ X1, const float2* __restrict__ twg,
+                        FftPlan P, int n, int zc, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N, nl = TL >> 1;
+    Lds L = carve(lds, N, nl, twg);
+    const int y0 = blockIdx.x * TL, x = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, n - y0);
+    const float* src = in + ((size_t)(img * n + x) * n + y0) * n;
+    for (int e = threadIdx.x; e < nl * N; e += blockDim.x) {
+        const int p = e / N, z = e - p * N;
+        float re = 0.f, im = 0.f;
+        if (z < n) {
+            if (2 * p < nvalid) re = src[(2 * p) * n + z];
+            if (2 * p + 1 < nvalid) im = src[(2 * p + 1) * n + z];
+        }
+        L.a[p * L.ld + z] = make_float2(re, im);
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, nl, L.ld, P);
+    float2* dst = X1 + (size_t)(img * n + x) * zc * n + y0;
+    for (int e = threadIdx.x; e < zc * TL; e += blockDim.x) {
+        const int l = e & (TL - 1), oz = e / TL;
+        if (l >= nvalid) continue;
+        const float2* row = r + (l >> 1) * L.ld;
+        const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
+        const float2 v = (l & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f) : cscale(cadd(z1, z2), 0.5f);
+        dst[(size_t)oz * n + l] = v;
+    }
+}
+
+// ---- forward, axis y
+__global__ void k_fwd_y(const float2* __restrict__ X1, float2* __restrict__ X2, const float2* __restrict__ twg,
+                        FftPlan P, int n, int zc, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N;
+    Lds L = carve(lds, N, TL, twg);
+    const int x0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, n - x0);
+    for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
+        const int l = e / N, y = e - l * N;
+        float2 v = make_float2(0.f, 0.f);
+        if (l < nvalid && y < n) v = X1[((size_t)(img * n + x0 + l) * zc + oz) * n + y];
+        L.a[l * L.ld + y] = v;
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
+    float2* dst = X2 + ((size_t)img * zc + oz) * N * n + x0;
+    for (int e = threadIdx.x; e < N * TL; e += blockDim.x) {
+        const int l = e & (TL - 1), oy = e / TL;
+        if (l < nvalid) dst[(size_t)oy * n + l] = r[l * L.ld + oy];
+    }
+}
+
+// ---- forward, axis x; writes pencil order
+__global__ void k_fwd_x(const float2* __restrict__ X2, float2* __restrict__ Xt, const float2* __restrict__ twg,
+                        FftPlan P, int n, int zc, int nimg, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N;
+    Lds L = carve(lds, N, TL, twg);
+    const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, N - oy0);
+    const float2* src = X2 + (((size_t)img * zc + oz) * N + oy0) * n;
+    for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
+        const int l = e / N, x = e - l * N;
+        float2 v = make_float2(0.f, 0.f);
+        if (l < nvalid && x < n) v = src[(size_t)l * n + x];
+        L.a[l * L.ld + x] = v;
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
+    for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
+        const int l = e / N, ox = e - l * N;
+        if (l < nvalid) Xt[(((size_t)oz * N + oy0 + l) * nimg + img) * N + ox] = r[l * L.ld + ox];
+    }
+}
+
+// The inverse transform of a line is conj(forward(conj(line))); the 1/N^3 factor is folded into the
+// kernel spectra.
+
+// ---- inverse, axis x; keeps x in [k-1, n-1]
+__global__ void k_inv_x(const float2* __restrict__ Yt, float2* __restrict__ Y2, const float2* __restrict__ twg,
+                        FftPlan P, int zc, int nimgo, int no, int k, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N;
+    Lds L = carve(lds, N, TL, twg);
+    const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, N - oy0);
+    for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
+        const int l = e / N, ox = e - l * N;
+        float2 v = make_float2(0.f, 0.f);
+        if (l < nvalid) v = cconj(Yt[(((size_t)oz * N + oy0 + l) * nimgo + img) * N + ox]);
+        L.a[l * L.ld + ox] = v;
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
+    float2* dst = Y2 + ((size_t)img * zc + oz) * no * N + oy0;
+    for (int e = threadIdx.x; e < no * TL; e += blockDim.x) {
+        const int l = e & (TL - 1), xo = e / TL;
+        if (l < nvalid) dst[(size_t)xo * N + l] = cconj(r[l * L.ld + xo + k - 1]);
+    }
+}
+
+// ---- inverse, axis y; keeps y in [k-1, n-1]; only lines with valid x exist
+__global__ void k_inv_y(const float2* __restrict__ Y2, float2* __restrict__ Y1, const float2* __restrict__ twg,
+                        FftPlan P, int zc, int ldz, int no, int k, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N;
+    Lds L = carve(lds, N, TL, twg);
+    const int oz0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, zc - oz0);
+    for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
+        const int l = e / N, oy = e - l * N;
+        float2 v = make_float2(0.f, 0.f);
+        if (l < nvalid) v = cconj(Y2[(((size_t)img * zc + oz0 + l) * no + xo) * N + oy]);
+        L.a[l * L.ld + oy] = v;
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
+    float2* dst = Y1 + ((size_t)img * no + xo) * no * ldz + oz0;
+    for (int e = threadIdx.x; e < no * TL; e += blockDim.x) {
+        const int l = e & (TL - 1), yo = e / TL;
+        if (l < nvalid) dst[(size_t)yo * ldz + l] = cconj(r[l * L.ld + yo + k - 1]);
+    }
+}
+
+// ---- inverse, axis z: complex -> real for two lines at once; keeps z in [k-1, n-1]; bias + transfer
+__global__ void k_inv_z(const float2* __restrict__ Y1, float* __restrict__ out, const float* __restrict__ bias,
+                        const float2* __restrict__ twg, FftPlan P, int zc, int ldz, int fo, int no, int k,
+                        int relu, int TL)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N, nl = TL >> 1;
+    Lds L = carve(lds, N, nl, twg);
+    const int yo0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
+    const int nvalid = min(TL, no - yo0);
+    const float2* src = Y1 + (((size_t)img * no + xo) * no + yo0) * ldz;
+    for (int e = threadIdx.x; e < nl * N; e += blockDim.x) {
+        const int p = e / N, o = e - p * N;
+        const bool direct = o < zc;
+        const int oo = direct ? o : N - o;
+        float2 A = make_float2(0.f, 0.f), B = A;
+        if (2 * p < nvalid) A = src[(size_t)(2 * p) * ldz + oo];
+        if (2 * p + 1 < nvalid) B = src[(size_t)(2 * p + 1) * ldz + oo];
+        if (!direct) { A = cconj(A); B = cconj(B); }
+        // Z = A + iB carries line 2p in its real part and line 2p+1 in its imaginary part after the
+        // inverse transform; stored conjugated for the forward-transform route.
+        L.a[p * L.ld + o] = cconj(cadd(A, mul_pi(B)));
+    }
+    __syncthreads();
+    const float2* r = fft_lines(L.a, L.b, L.tw, nl, L.ld, P);
+    const float bj = bias ? bias[img % fo] : 0.f;
+    float* dst = out + (((size_t)img * no + xo) * no + yo0) * no;
+    for (int e = threadIdx.x; e < TL * no; e += blockDim.x) {
+        const int l = e / no, zo = e - l * no;
+        if (l >= nvalid) continue;
+        const float2 t = r[(l >> 1) * L.ld + zo + k - 1];
+        float v = ((l & 1) ? -t.y : t.x) + bj;
+        if (relu) v = fmaxf(v, 0.f);
+        dst[(size_t)l * no + zo] = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------- host side
+static size_t pass_lds_bytes(int N, int nlines) { return sizeof(float2) * ((size_t)N + 2 * (size_t)nlines * (N | 1)); }
+
+int lines_per_tile(int N)
+{
+    // largest power of two <= 16 whose two LDS buffers stay within ~72 KB, so several tiles share a CU
+    int TL = 16;
+    while (TL > 2 && pass_lds_bytes(N, TL) > 72 * 1024) TL >>= 1;
+    return TL;
+}
+
+#define ZNNI_LAUNCH_CHECK()                         \
+    do {                                            \
+        if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP; \
+    } while (0)
+
+static znni_status allow_lds(const void* fn, size_t bytes)
+{
+    if (bytes > 48 * 1024) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+            return ZNNI_ERR_HIP;
+    }
+    return ZNNI_OK;
+}
+
+znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
+{
+    k_twiddles<<<dim3((L.N + 255) / 256), dim3(256), 0, st>>>(L.tw, L.N);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL / 2);
+    znni_status rc = allow_lds((const void*)k_fwd_z, lds);
+    if (rc) return rc;
+    dim3 grid((L.n + TL - 1) / TL, L.n, L.nimg);
+    k_fwd_z<<<grid, dim3(256), lds, st>>>(in, L.buf0, L.tw, L.fft, L.n, L.zc, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL);
+    znni_status rc = allow_lds((const void*)k_fwd_y, lds);
+    if (rc) return rc;
+    dim3 grid((L.n + TL - 1) / TL, L.zc, L.nimg);
+    k_fwd_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.tw, L.fft, L.n, L.zc, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL);
+    znni_status rc = allow_lds((const void*)k_fwd_x, lds);
+    if (rc) return rc;
+    dim3 grid((L.N + TL - 1) / TL, L.zc, L.nimg);
+    k_fwd_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.tw, L.fft, L.n, L.zc, L.nimg, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL);
+    znni_status rc = allow_lds((const void*)k_inv_x, lds);
+    if (rc) return rc;
+    dim3 grid((L.N + TL - 1) / TL, L.zc, L.nimgo);
+    k_inv_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.tw, L.fft, L.zc, L.nimgo, L.no, L.k, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL);
+    znni_status rc = allow_lds((const void*)k_inv_y, lds);
+    if (rc) return rc;
+    dim3 grid((L.zc + TL - 1) / TL, L.no, L.nimgo);
+    k_inv_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.tw, L.fft, L.zc, L.ldz, L.no, L.k, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
+{
+    const int TL = L.TL;
+    const size_t lds = pass_lds_bytes(L.N, TL / 2);
+    znni_status rc = allow_lds((const void*)k_inv_z, lds);
+    if (rc) return rc;
+    dim3 grid((L.no + TL - 1) / TL, L.no, L.nimgo);
+    k_inv_z<<<grid, dim3(256), lds, st>>>(L.buf1, out, bias, L.tw, L.fft, L.zc, L.ldz, L.fo, L.no, L.k,
+                                          (flags & ZNNI_RELU) ? 1 : 0, TL);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
+}
+
+}  // namespace znni

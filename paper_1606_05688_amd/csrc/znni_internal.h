@@ -1,0 +1,49 @@
+// znni_internal.h -- host-side plan of one layer call and the launchers of its stages (library-internal).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+#include "../../include/znni.h"
+#include "fft_core.h"
+
+namespace znni {
+
+// Everything one call needs: sizes, the radix schedule, and where each buffer lives in the workspace.
+// Buffers buf0/buf1 are reused in turn by the stages (X1 -> X2 -> Xt, then Yt -> Y2 -> Y1), the way the
+// paper reuses its transform scratch (Section III-D, last paragraphs).
+struct LayerPlan {
+    int S, f, fo, n, k;
+    int N;        // transform size n~
+    int zc;       // N/2 + 1 bins along the halved axis
+    int no;       // n - k + 1
+    int ldz;      // row stride of Y1 (zc rounded up to even)
+    int nimg;     // S * f
+    int nimgo;    // S * fo
+    int TL;       // lines per tile in the transform passes
+    FftPlan fft;
+    // workspace carving (device pointers)
+    float2* tw;   // [N] exp(-2 pi i q / N)
+    float2* A1;   // [zc][fo*f*k][k]     kernel transform after the z stage
+    float2* A;    // [zc][N][fo][f][k]   kernel transform after the z and y stages, scaled by 1/N^3
+    float2* buf0;
+    float2* buf1;
+    size_t bytes; // total workspace bytes
+};
+
+// Host-only: validate the shape and fill every field; pointers are offsets from `base` (may be NULL when
+// only the size is wanted).
+znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan* out);
+
+int lines_per_tile(int N);
+
+znni_status launch_twiddles(const LayerPlan& L, hipStream_t st);
+znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st);
+znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st);
+znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st);
+znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st);
+znni_status launch_mac(const LayerPlan& L, hipStream_t st);
+znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
+znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
+znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
+
+}  // namespace znni

@@ -1,0 +1,93 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/znni.h declares, sizes its workspace
+sensibly, and turns every argument error into a status code before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1606_05688_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "znni.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(znni_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for name in names:
+        assert hasattr(L, name), f"{name} is declared in include/znni.h but not exported"
+    assert B.znni_version() >= 100
+
+
+def test_status_strings():
+    L = B.lib()
+    seen = set()
+    for st in range(0, -8, -1):
+        s = L.znni_status_string(st)
+        assert s and s not in seen
+        seen.add(s)
+    assert L.znni_status_string(-99) == b"unknown status"
+
+
+def test_fft_size_is_smallest_7_smooth():
+    def smooth(m):
+        for p in (2, 3, 5, 7):
+            while m % p == 0:
+                m //= p
+        return m == 1
+    for n in range(1, 1025):
+        m = B.znni_fft_size(n)
+        assert m >= n and smooth(m)
+        assert all(not smooth(t) for t in range(n, m))
+    for n in (16, 64, 128, 320):
+        assert B.znni_fft_size(n) == n          # the benchmark layers transform at their own size
+    assert B.znni_fft_size(0) == 0 and B.znni_fft_size(-3) == 0 and B.znni_fft_size(1025) == 0
+
+
+def test_workspace_holds_both_spectra_and_partial_kernel_transforms():
+    for (S, f, fo, n, k) in [(1, 2, 3, 16, 3), (1, 8, 8, 64, 5), (8, 32, 32, 64, 7), (1, 48, 48, 320, 5)]:
+        N = B.znni_fft_size(n)
+        zc = N // 2 + 1
+        need = 8 * zc * N * N * S * (f + fo) + 8 * zc * N * fo * f * k
+        got = B.znni_conv3d_fft_workspace(S, f, fo, n, k)
+        assert need <= got <= 1.1 * need + (1 << 20)
+    # the largest benchmark layer: far below the 304 GB a stored kernel-spectrum bank would take
+    assert B.znni_conv3d_fft_workspace(1, 48, 48, 320, 5) < 20e9
+
+
+@pytest.mark.parametrize("args,status", [
+    ((0, 1, 1, 8, 3), -2), ((1, 0, 1, 8, 3), -2), ((1, 1, 0, 8, 3), -2), ((1, 1, 1, 8, 0), -2),
+    ((1, 1, 1, 8, 9), -2), ((1, 1, 1, 0, 1), -2), ((70000, 1, 1, 8, 3), -2), ((1, 1, 1, 1025, 3), -3),
+])
+def test_workspace_query_rejects_bad_shapes(args, status):
+    b = ctypes.c_size_t(0)
+    assert B.lib().znni_conv3d_fft_workspace(*args, ctypes.byref(b)) == status
+    assert B.lib().znni_conv3d_fft_workspace(1, 1, 1, 8, 3, None) == -1
+
+
+def test_layer_call_validates_before_any_gpu_work():
+    """Fake (never dereferenced) device addresses: each call must fail in validation."""
+    L = B.lib()
+    p, ws = 0x1000, 0x100000
+    big = 1 << 40
+
+    def call(S=1, f=1, fo=1, n=8, k=3, inp=p, w=p, bias=None, out=p, flags=0, wsp=ws, wsb=big):
+        return L.znni_conv3d_fft(S, f, fo, n, k, inp, w, bias, out, flags, wsp, wsb, None)
+    assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
+    assert call(k=9) == -2 and call(S=0) == -2
+    assert call(n=1025, k=1) == -3
+    assert call(flags=2) == -5 and call(flags=0x80000001) == -5
+    assert call(inp=p + 4) == -7 and call(out=p + 8) == -7 and call(wsp=ws + 128) == -7
+    assert call(wsb=1024) == -4
+    need = B.znni_conv3d_fft_workspace(1, 1, 1, 8, 3)
+    assert call(wsb=need - 1) == -4
+    ms = (ctypes.c_float * 8)()
+    assert L.znni_conv3d_fft_profile(1, 1, 1, 8, 9, p, p, None, p, 0, ws, big, None, ms) == -2
+    assert L.znni_conv3d_fft_profile(1, 1, 1, 8, 3, p, p, None, p, 0, ws, big, None, None) == -1

@@ -1,0 +1,149 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle on the same seeded inputs.
+
+Bar (per output voxel of output image j):  |gpu - oracle| <= 1e-4 * max|x| * sum_{i,a,b,c} |w[j,i,a,b,c]|.
+Small layers are compared element by element; the layers too large for a full direct convolution on the host
+are compared on sampled voxels (all corner blocks and face centres of every output image plus uniformly random
+positions), each computed by the oracle one voxel at a time.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1606_05688_amd import binding as B
+from paper_1606_05688_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _run_gpu(inp, w, bias, relu, **kw):
+    d = torch.device("cuda:0")
+    ti = torch.from_numpy(inp).to(d)
+    tw = torch.from_numpy(w).to(d)
+    tb = torch.from_numpy(bias).to(d) if bias is not None else None
+    out = B.znni_conv3d_fft(ti, tw, tb, relu=relu, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check_full(oracle, inp, w, bias, relu, label):
+    _say(f"[parity/full] {label} inp={inp.shape} w={w.shape} relu={relu} bias={'yes' if bias is not None else 'no'}")
+    got = _run_gpu(inp, w, bias, relu).cpu().numpy().astype(np.float64)
+    exp = oracle.conv3d(inp, w, bias, relu=relu)
+    assert got.shape == exp.shape
+    tol = oracle.tolerance(inp, w)
+    err = np.abs(got - exp).max(axis=(0, 2, 3, 4))
+    _say(f"    max err/tol per output image: {np.max(err / tol):.3e} (worst abs {err.max():.3e})")
+    assert np.all(np.isfinite(got))
+    assert np.all(err <= tol), f"{label}: err {err} > tol {tol}"
+
+
+def _rand(seed, S, f, fo, n, k):
+    r = np.random.default_rng(seed)
+    inp = r.uniform(-1, 1, (S, f, n, n, n)).astype(np.float32)
+    w = (r.standard_normal((fo, f, k, k, k)) * (f * k ** 3) ** -0.5).astype(np.float32)
+    b = (r.standard_normal(fo) * np.sqrt(0.1)).astype(np.float32)
+    return inp, w, b
+
+
+# (S, f, fo, n, k): transform sizes with every supported radix, tiles with ragged tails, n~ > n padding,
+# odd sizes, k = 1 and k = n, single and many images.
+SMALL = [
+    (1, 1, 1, 8, 3),       # one radix-8 stage
+    (2, 3, 2, 20, 3),      # 20 = 5*4, two tiles of lines with a ragged second one
+    (1, 2, 2, 17, 4),      # 17 -> n~ = 18 = 3*3*2, padded lines
+    (1, 1, 2, 33, 5),      # 33 -> 35 = 7*5
+    (1, 3, 5, 24, 7),      # 24 = 3*8
+    (2, 2, 2, 48, 2),      # even kernel
+    (1, 4, 4, 40, 5),      # 40 = 5*8
+    (1, 2, 3, 21, 1),      # k = 1: per-voxel matrix product, odd transform size 21 = 7*3
+    (1, 2, 2, 6, 6),       # k = n: one output voxel per image
+    (3, 1, 1, 1, 1),       # a single voxel
+    (1, 5, 3, 50, 3),      # 50 = 5*5*2
+    (1, 2, 2, 96, 3),      # 96 = 3*4*8, three stages
+    (1, 1, 1, 125, 4),     # 125 -> 126 = 7*3*3*2
+]
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_small_layers_full_compare(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand(100 + n + k, S, f, fo, n, k)
+    _check_full(oracle, inp, w, b, True, f"small {shape}")
+    _check_full(oracle, inp, w, None, False, f"small {shape} linear")
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_benchmark_layers_full_compare(oracle, idx):
+    L = W.CONFIGS[idx]
+    inp, w, b = W.make_inputs(L)
+    _check_full(oracle, inp, w, b, L.relu, L.name)
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_benchmark_layers_sampled_compare(oracle, idx):
+    L = W.CONFIGS[idx]
+    _say(f"[parity/sampled] {L.name}: drawing inputs")
+    inp, w, b = W.make_inputs(L)
+    pts = W.sample_points(L, n_random=200_000 if idx < 4 else 100_000)
+    _say(f"    {len(pts)} sampled voxels; running GPU layer")
+    out = _run_gpu(inp, w, b, L.relu)
+    assert bool(torch.isfinite(out).all())
+    tp = torch.from_numpy(pts.astype(np.int64)).to(out.device)
+    got = out[tp[:, 0], tp[:, 1], tp[:, 2], tp[:, 3], tp[:, 4]].cpu().numpy().astype(np.float64)
+    del out
+    torch.cuda.empty_cache()
+    _say("    running oracle on the sampled voxels")
+    exp = oracle.conv3d_points(inp, w, b, pts, relu=L.relu)
+    tol = oracle.tolerance(inp, w)[pts[:, 1]]
+    ratio = np.abs(got - exp) / tol
+    _say(f"    max err/tol {ratio.max():.3e}; mean |out| {np.abs(exp).mean():.3e}")
+    assert np.all(ratio <= 1.0)
+    assert np.count_nonzero(exp) > 0.2 * len(exp)        # the sample is not all rectified to zero
+
+
+def test_results_are_bitwise_reproducible_and_workspace_reusable():
+    S, f, fo, n, k = 2, 3, 4, 40, 5
+    inp, w, b = _rand(7, S, f, fo, n, k)
+    d = torch.device("cuda:0")
+    ws = B.alloc_workspace(S, f, fo, n, k, d)
+    ws.fill_(0xFF)          # NaN bit patterns: the layer must not depend on workspace contents
+    a = _run_gpu(inp, w, b, True, workspace=ws).clone()
+    c = _run_gpu(inp, w, b, True, workspace=ws)
+    assert torch.equal(a, c)
+    e = _run_gpu(inp, w, b, True)
+    assert torch.equal(a, e)
+
+
+def test_runs_on_a_side_stream_and_profile_matches():
+    S, f, fo, n, k = 1, 4, 4, 32, 3
+    inp, w, b = _rand(9, S, f, fo, n, k)
+    d = torch.device("cuda:0")
+    ti, tw, tb = (torch.from_numpy(t).to(d) for t in (inp, w, b))
+    ref_out = B.znni_conv3d_fft(ti, tw, tb, relu=True)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream(device=d)
+    with torch.cuda.stream(st):
+        o2 = B.znni_conv3d_fft(ti, tw, tb, relu=True, stream=st)
+    st.synchronize()
+    assert torch.equal(ref_out, o2)
+    o3, ms = B.znni_conv3d_fft_profile(ti, tw, tb, relu=True)
+    assert torch.equal(ref_out, o3)
+    assert set(ms) == set(B.STAGES) and all(v >= 0 for v in ms.values())
+
+
+def test_relu_flag_and_null_bias(oracle):
+    S, f, fo, n, k = 1, 2, 2, 16, 3
+    inp, w, b = _rand(11, S, f, fo, n, k)
+    lin = _run_gpu(inp, w, None, False)
+    pre = _run_gpu(inp, w, b, False)
+    act = _run_gpu(inp, w, b, True)
+    assert torch.equal(act, torch.clamp_min(pre, 0))
+    tb = torch.from_numpy(b).to(lin.device)
+    assert torch.allclose(pre, lin + tb[None, :, None, None, None], atol=1e-6)
