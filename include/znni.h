@@ -46,7 +46,10 @@ typedef enum {
 
 /* flags */
 enum {
-    ZNNI_RELU = 1u                  /* transfer function max(0, .) (Section V); without it: identity       */
+    ZNNI_RELU = 1u,                 /* transfer function max(0, .) (Section V); without it: identity       */
+    ZNNI_MAC_REFERENCE = 2u         /* diagnostic: run the multiply-accumulate stage with the plain one-thread- */
+                                    /* per-bin kernel instead of the matrix-core kernel (same result up to     */
+                                    /* rounding, much slower)                                                   */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */
@@ -90,7 +93,7 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
  *   w         [fo][f][k][k][k]         device, read-only
  *   bias      [fo] device, read-only, or NULL for zero bias
  *   out       [S][fo][n-k+1]^3         device, written (every element)
- *   flags     ZNNI_RELU or 0
+ *   flags     bitwise OR of ZNNI_RELU / ZNNI_MAC_REFERENCE, or 0
  *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
  *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
  *             not overlap in time.

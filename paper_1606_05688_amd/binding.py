@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libznni.so")
 
 OK = 0
 RELU = 1
+MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile")
@@ -74,6 +75,10 @@ def alloc_workspace(S, f, fo, n, k, device="cuda"):
     return torch.empty(znni_conv3d_fft_workspace(S, f, fo, n, k), dtype=torch.uint8, device=device)
 
 
+def _flags(relu, mac_reference):
+    return (RELU if relu else 0) | (MAC_REFERENCE if mac_reference else 0)
+
+
 def _marshal(inp, w, bias, out, workspace):
     assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
     assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 5
@@ -94,7 +99,8 @@ def _marshal(inp, w, bias, out, workspace):
     return S, f, fo, n, k, out, workspace
 
 
-def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None):
+def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
+                    mac_reference=False):
     """out[S,f',n-k+1,...] = act(bias + valid 3D convolution of inp[S,f,n,n,n] with w[f',f,k,k,k]).
 
     Asynchronous on `stream` (a torch.cuda.Stream; default: torch's current stream)."""
@@ -102,18 +108,19 @@ def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, str
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
     _check(lib().znni_conv3d_fft(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
                                  bias.data_ptr() if bias is not None else None, out.data_ptr(),
-                                 RELU if relu else 0, workspace.data_ptr(), workspace.numel(),
+                                 _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
                                  st.cuda_stream))
     return out
 
 
-def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None):
+def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
+                            mac_reference=False):
     """Same call with per-stage HIP-event timing; returns (out, {stage: milliseconds}).  Synchronises."""
     S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
     ms = (ctypes.c_float * len(STAGES))()
     _check(lib().znni_conv3d_fft_profile(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
                                          bias.data_ptr() if bias is not None else None, out.data_ptr(),
-                                         RELU if relu else 0, workspace.data_ptr(), workspace.numel(),
+                                         _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
                                          st.cuda_stream, ms))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}

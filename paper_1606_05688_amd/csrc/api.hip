@@ -57,13 +57,16 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     L->nimg = S * f;
     L->nimgo = S * fo;
     L->TL = lines_per_tile(N);
+    L->fp = (f + 3) & ~3;
+    L->Mp = (fo + 15) & ~15;
+    plan_mac(L);
     make_fft_plan(N, &L->fft);
 
     const size_t c = sizeof(float2);
     const size_t zc = L->zc, no = L->no, nn = n, NN = N;
     const size_t sz_tw = NN * c;
     const size_t sz_A1 = zc * fo * f * k * k * c;
-    const size_t sz_A = zc * NN * fo * f * k * c;
+    const size_t sz_A = zc * NN * k * L->fp * L->Mp * c;
     size_t b0 = (size_t)L->nimg * nn * zc * nn;                    // X1
     size_t t = zc * NN * L->nimg * NN; if (t > b0) b0 = t;         // Xt
     t = (size_t)L->nimgo * zc * no * NN; if (t > b0) b0 = t;       // Y2
@@ -85,7 +88,7 @@ static znni_status validate(int S, int f, int fo, int n, int k, const float* in,
                             unsigned flags, void* workspace, size_t workspace_bytes, LayerPlan* L)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (flags & ~(unsigned)ZNNI_RELU) return ZNNI_ERR_FLAGS;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE)) return ZNNI_ERR_FLAGS;
     znni_status rc = make_plan(S, f, fo, n, k, workspace, L);
     if (rc) return rc;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u) return ZNNI_ERR_ALIGN;
@@ -118,7 +121,7 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_MARK(ZNNI_STAGE_FWD_X);
     ZNNI_DO(launch_fwd_x(L, st));
     ZNNI_MARK(ZNNI_STAGE_MAC);
-    ZNNI_DO(launch_mac(L, st));
+    ZNNI_DO(launch_mac(L, flags, st));
     ZNNI_MARK(ZNNI_STAGE_INV_X);
     ZNNI_DO(launch_inv_x(L, st));
     ZNNI_MARK(ZNNI_STAGE_INV_Y);

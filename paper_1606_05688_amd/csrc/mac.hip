@@ -7,14 +7,25 @@
 // instead of N*N*zc); the third is evaluated where it is consumed, inside the multiply-accumulate
 //
 //     Yt[s][j](ox,oy,oz) = sum_i  Wt[j][i](ox,oy,oz) * Xt[s][i](ox,oy,oz),
-//     Wt[j][i](ox,oy,oz) = sum_{a<k} A[oz][oy][j][i][a] * exp(-2 pi i a ox / N)
+//     Wt[j][i](ox,oy,oz) = sum_{a<k} A[oz][oy][a][i][j] * exp(-2 pi i a ox / N)
 //
 // which is the second stage of Algorithm 3 (multiply the f image spectra by the f kernel spectra of output
 // image j, accumulate over the f products) without a stored kernel spectrum.  The 1/N^3 of the unnormalised
 // transforms is folded into A.
+//
+// For one (oz,oy) pencil the two sums commute:
+//
+//     Yt[j][col] = sum_a T[a*ox(col)] * P_a[j][col],     P_a = A_a (Mp x fp)  *  X (fp x columns)
+//
+// with col = s*N + ox running over all images of the batch: k dense complex matrix products per pencil whose
+// left operand does not depend on the column.  That is a contraction, so it runs on the matrix cores
+// (v_mfma_f32_16x16x4_f32), each complex product done as three real ones:
+//     P1 = Ar Xr, P2 = Ai Xi, P3 = (Ar+Ai)(Xr+Xi);  Re = P1 - P2, Im = P3 - P1 - P2.
 #include "znni_internal.h"
 
 namespace znni {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // A1[oz][row][.] with row = ((j*f+i)*k + a)*k + b :  sum_c w[row][c] exp(-2 pi i oz c / N)
 __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, const float2* __restrict__ tw,
@@ -29,40 +40,164 @@ __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, 
     A1[(size_t)oz * nrows + row] = acc;
 }
 
-// A[oz][oy][jia] = scale * sum_b A1[oz][jia][b] exp(-2 pi i oy b / N),   jia = (j*f+i)*k + a
+// A[oz][oy][a][i<fp][j<Mp] = scale * sum_b A1[oz][((j*f+i)*k+a)][b] exp(-2 pi i oy b / N); zero where i >= f
+// or j >= fo (fp, Mp: f and fo rounded up to the matrix-core tile, 4 and 16).
 __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
-                          int N, int njia, int k, float scale)
+                          int N, int f, int fo, int k, int fp, int Mp, float scale)
 {
-    const int jia = blockIdx.x * blockDim.x + threadIdx.x;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int oy = blockIdx.y, oz = blockIdx.z;
-    if (jia >= njia) return;
-    const float2* a1 = A1 + ((size_t)oz * njia + jia) * k;
+    const int per = k * fp * Mp;
+    if (idx >= per) return;
+    const int j = idx % Mp;
+    const int i = (idx / Mp) % fp;
+    const int a = idx / (Mp * fp);
     float2 acc = make_float2(0.f, 0.f);
-    for (int b = 0; b < k; ++b) acc = cadd(acc, cmul(a1[b], tw[(oy * b) % N]));
-    A[((size_t)oz * N + oy) * njia + jia] = cscale(acc, scale);
+    if (i < f && j < fo) {
+        const float2* a1 = A1 + ((size_t)oz * fo * f * k + (size_t)(j * f + i) * k + a) * k;
+        for (int b = 0; b < k; ++b) acc = cadd(acc, cmul(a1[b], tw[(oy * b) % N]));
+        acc = cscale(acc, scale);
+    }
+    A[((size_t)oz * N + oy) * per + idx] = acc;
 }
 
-// Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple: it is
-// the fallback for shapes the tiled kernel does not take, and the form the tiled kernel is checked against.
+// Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
+// a diagnostic path (flag ZNNI_MAC_REFERENCE) the matrix-core kernel can be compared with.
 __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
-                             const float2* __restrict__ tw, int N, int S, int f, int fo, int k)
+                             const float2* __restrict__ tw, int N, int S, int f, int fo, int k, int fp, int Mp)
 {
     const size_t pencil = (size_t)blockIdx.y * N + blockIdx.x;
     const float2* Xp = Xt + pencil * S * f * N;
-    const float2* Ap = A + pencil * fo * f * k;
+    const float2* Ap = A + pencil * k * fp * Mp;
     float2* Yp = Yt + pencil * S * fo * N;
     for (int ox = threadIdx.x; ox < N; ox += blockDim.x) {
         for (int s = 0; s < S; ++s)
             for (int j = 0; j < fo; ++j) {
                 float2 acc = make_float2(0.f, 0.f);
                 for (int i = 0; i < f; ++i) {
-                    const float2* aji = Ap + (size_t)(j * f + i) * k;
                     float2 W = make_float2(0.f, 0.f);
-                    for (int a = 0; a < k; ++a) W = cadd(W, cmul(aji[a], tw[(a * ox) % N]));
+                    for (int a = 0; a < k; ++a)
+                        W = cadd(W, cmul(Ap[(size_t)(a * fp + i) * Mp + j], tw[(a * ox) % N]));
                     acc = cadd(acc, cmul(W, Xp[(size_t)(s * f + i) * N + ox]));
                 }
                 Yp[(size_t)(s * fo + j) * N + ox] = acc;
             }
+    }
+}
+
+// Matrix-core multiply-accumulate.
+//
+// One workgroup = one pencil x one block of NW = 16*NT*CG columns x one block of 16*RG output rows.
+// Wave (rg, cg) owns a 16 x (16*NT) tile of Yt.  The fp x NW block of image spectra stays in LDS for the
+// whole call (in chunks of FC input images if it does not fit); A is streamed from global memory straight
+// into the matrix-core operand layout (lane l supplies A[row l%16][k-index l/16]), every wave of a row
+// group reading the same values, which the vector L1 serves.
+//
+// blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
+// row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
+// so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
+template <int NT>
+__global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
+                                                  float2* __restrict__ Yt, const float2* __restrict__ twg,
+                                                  int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
+                                                  int RG, int CG, int ncolblk, int nmblk, int npencils)
+{
+    extern __shared__ float2 lds[];
+    const int NW = 16 * NT * CG;
+    float2* tws = lds;              // [N]
+    float2* Xs = lds + N;           // [FC][NW]
+
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per_pencil = ncolblk * nmblk;
+    const int pencil = (slot / per_pencil) * 8 + xcd;
+    if (pencil >= npencils) return;
+    const int sub = slot % per_pencil;
+    const int colblk = sub % ncolblk, mblk = sub / ncolblk;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int rg = wave % RG, cg = wave / RG;
+    const int l16 = lane & 15, kk = lane >> 4;
+    const int Ct = S * N;                           // columns of the pencil
+    const int m0 = (mblk * RG + rg) * 16;           // first output row of this wave (may be >= Mp: idle)
+    const bool active = m0 < Mp;
+    const int cw0 = cg * NT * 16;                   // first column of this wave inside the block
+    const int colbase = colblk * NW;
+
+    const float2* Xp = Xt + (size_t)pencil * S * f * N;
+    const float2* Ap = A + (size_t)pencil * k * fp * Mp;
+    float2* Yp = Yt + (size_t)pencil * S * fo * N;
+
+    for (int q = threadIdx.x; q < N; q += blockDim.x) tws[q] = twg[q];
+
+    int oxs[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) oxs[t] = (colbase + cw0 + t * 16 + l16) % N;
+
+    floatx4 yr[NT], yi[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) { yr[t] = floatx4{0.f, 0.f, 0.f, 0.f}; yi[t] = yr[t]; }
+
+    for (int ic0 = 0; ic0 < fp; ic0 += FC) {
+        const int fc = min(FC, fp - ic0);           // multiple of 4
+        __syncthreads();
+        for (int i = wave; i < fc; i += nwaves) {
+            const int gi = ic0 + i;
+            for (int c = lane; c < NW; c += 64) {
+                const int col = colbase + c;
+                float2 v = make_float2(0.f, 0.f);
+                if (gi < f && col < Ct) {
+                    const int s = col / N, ox = col - s * N;
+                    v = Xp[(size_t)(s * f + gi) * N + ox];
+                }
+                Xs[i * NW + c] = v;
+            }
+        }
+        __syncthreads();
+        if (!active) continue;
+        for (int a = 0; a < k; ++a) {
+            floatx4 p1[NT], p2[NT], p3[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) { p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t]; }
+            const float2* Aa = Ap + ((size_t)(a * fp + ic0 + kk)) * Mp + m0 + l16;
+            const float2* Xw = Xs + kk * NW + cw0 + l16;
+            float2 av = Aa[0];
+            for (int i4 = 0; i4 < fc; i4 += 4) {
+                const float2 ac = av;
+                if (i4 + 4 < fc) av = Aa[(size_t)(i4 + 4) * Mp];
+                const float as = ac.x + ac.y;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const float2 xv = Xw[i4 * NW + t * 16];
+                    p1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.x, xv.x, p1[t], 0, 0, 0);
+                    p2[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.y, xv.y, p2[t], 0, 0, 0);
+                    p3[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, xv.x + xv.y, p3[t], 0, 0, 0);
+                }
+            }
+            // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element r of lane l is row 4*(l/16)+r, column l%16
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const float2 T = tws[(a * oxs[t]) % N];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pr = p1[t][r] - p2[t][r];
+                    const float pi = p3[t][r] - p1[t][r] - p2[t][r];
+                    yr[t][r] += T.x * pr - T.y * pi;
+                    yi[t][r] += T.x * pi + T.y * pr;
+                }
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int col = colbase + cw0 + t * 16 + l16;
+        if (col >= Ct) continue;
+        const int s = col / N, ox = col - s * N;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = m0 + 4 * kk + r;
+            if (row < fo) Yp[(size_t)(s * fo + row) * N + ox] = make_float2(yr[t][r], yi[t][r]);
+        }
     }
 }
 
@@ -73,21 +208,77 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 
 znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st)
 {
-    const int njia = L.fo * L.f * L.k;
-    const int nrows = njia * L.k;
+    const int nrows = L.fo * L.f * L.k * L.k;
     k_kprep_z<<<dim3((nrows + 255) / 256, L.zc), dim3(256), 0, st>>>(w, L.A1, L.tw, L.N, nrows, L.k);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
-    k_kprep_y<<<dim3((njia + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, njia, L.k, scale);
+    const int per = L.k * L.fp * L.Mp;
+    k_kprep_y<<<dim3((per + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, L.f, L.fo, L.k,
+                                                                       L.fp, L.Mp, scale);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
-znni_status launch_mac(const LayerPlan& L, hipStream_t st)
+// Tiling of the matrix-core kernel for a layer shape (host only).
+void plan_mac(LayerPlan* L)
 {
-    k_mac_simple<<<dim3(L.N, L.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k);
+    const int Ct = L->S * L->N;
+    static const int cand[6][2] = {{5, 2}, {4, 2}, {5, 1}, {4, 1}, {2, 1}, {1, 1}};   // (NT, CG), widest first
+    int best = 0;
+    long best_waste = -1;
+    for (int c = 0; c < 6; ++c) {
+        const int NW = 16 * cand[c][0] * cand[c][1];
+        const long waste = (long)((Ct + NW - 1) / NW) * NW - Ct;
+        if (best_waste < 0 || waste < best_waste) { best = c; best_waste = waste; }
+    }
+    L->mac_NT = cand[best][0];
+    L->mac_CG = cand[best][1];
+    const int NW = 16 * L->mac_NT * L->mac_CG;
+    L->mac_ncolblk = (Ct + NW - 1) / NW;
+    const int rt = L->Mp / 16;
+    const int rgmax = 12 / L->mac_CG;
+    L->mac_RG = rt < rgmax ? rt : rgmax;
+    L->mac_nmblk = (rt + L->mac_RG - 1) / L->mac_RG;
+    // image-spectrum block kept in LDS: at most ~64 KB so two workgroups share a CU
+    int FC = (64 * 1024) / (NW * (int)sizeof(float2));
+    FC &= ~3;
+    if (FC < 4) FC = 4;
+    if (FC > L->fp) FC = L->fp;
+    L->mac_FC = FC;
+    L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)FC * NW);
+}
+
+template <int NT>
+static znni_status launch_mac_nt(const LayerPlan& L, hipStream_t st)
+{
+    const void* fn = (const void*)k_mac_mfma<NT>;
+    if (L.mac_lds > 48 * 1024 &&
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.mac_lds) != hipSuccess)
+        return ZNNI_ERR_HIP;
+    const int npencils = L.zc * L.N;
+    const int per_pencil = L.mac_ncolblk * L.mac_nmblk;
+    const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
+    k_mac_mfma<NT><<<dim3((unsigned)blocks), dim3(64 * L.mac_RG * L.mac_CG), L.mac_lds, st>>>(
+        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_RG, L.mac_CG,
+        L.mac_ncolblk, L.mac_nmblk, npencils);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
+}
+
+znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
+{
+    if (flags & ZNNI_MAC_REFERENCE) {
+        k_mac_simple<<<dim3(L.N, L.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k,
+                                                            L.fp, L.Mp);
+        ZNNI_LAUNCH_CHECK();
+        return ZNNI_OK;
+    }
+    switch (L.mac_NT) {
+        case 5: return launch_mac_nt<5>(L, st);
+        case 4: return launch_mac_nt<4>(L, st);
+        case 2: return launch_mac_nt<2>(L, st);
+        default: return launch_mac_nt<1>(L, st);
+    }
 }
 
 }  // namespace znni

@@ -20,11 +20,16 @@ struct LayerPlan {
     int nimg;     // S * f
     int nimgo;    // S * fo
     int TL;       // lines per tile in the transform passes
+    int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
+    int Mp;       // fo rounded up to a multiple of 16 (matrix-core tile rows)
+    // tiling of the matrix-core multiply-accumulate (see mac.hip)
+    int mac_NT, mac_CG, mac_RG, mac_FC, mac_ncolblk, mac_nmblk;
+    size_t mac_lds;
     FftPlan fft;
     // workspace carving (device pointers)
     float2* tw;   // [N] exp(-2 pi i q / N)
     float2* A1;   // [zc][fo*f*k][k]     kernel transform after the z stage
-    float2* A;    // [zc][N][fo][f][k]   kernel transform after the z and y stages, scaled by 1/N^3
+    float2* A;    // [zc][N][k][fp][Mp]  kernel transform after the z and y stages, scaled by 1/N^3
     float2* buf0;
     float2* buf1;
     size_t bytes; // total workspace bytes
@@ -41,7 +46,8 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
 znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st);
 znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st);
-znni_status launch_mac(const LayerPlan& L, hipStream_t st);
+void plan_mac(LayerPlan* L);
+znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st);
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);

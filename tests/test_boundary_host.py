@@ -55,7 +55,8 @@ def test_workspace_holds_both_spectra_and_partial_kernel_transforms():
     for (S, f, fo, n, k) in [(1, 2, 3, 16, 3), (1, 8, 8, 64, 5), (8, 32, 32, 64, 7), (1, 48, 48, 320, 5)]:
         N = B.znni_fft_size(n)
         zc = N // 2 + 1
-        need = 8 * zc * N * N * S * (f + fo) + 8 * zc * N * fo * f * k
+        fp, Mp = (f + 3) // 4 * 4, (fo + 15) // 16 * 16     # kernel transforms are stored padded to matrix-core tiles
+        need = 8 * zc * N * N * S * (f + fo) + 8 * zc * N * fp * Mp * k
         got = B.znni_conv3d_fft_workspace(S, f, fo, n, k)
         assert need <= got <= 1.1 * need + (1 << 20)
     # the largest benchmark layer: far below the 304 GB a stored kernel-spectrum bank would take
@@ -83,7 +84,7 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
-    assert call(flags=2) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=4) == -5 and call(flags=0x80000001) == -5
     assert call(inp=p + 4) == -7 and call(out=p + 8) == -7 and call(wsp=ws + 128) == -7
     assert call(wsb=1024) == -4
     need = B.znni_conv3d_fft_workspace(1, 1, 1, 8, 3)

@@ -138,6 +138,24 @@ def test_runs_on_a_side_stream_and_profile_matches():
     assert set(ms) == set(B.STAGES) and all(v >= 0 for v in ms.values())
 
 
+@pytest.mark.parametrize("shape", [(1, 2, 3, 16, 3), (2, 5, 7, 24, 5), (1, 48, 48, 40, 5), (3, 6, 20, 20, 2),
+                                   (1, 80, 100, 16, 3)],
+                         ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_matrix_core_mac_agrees_with_plain_mac(oracle, shape):
+    """The tiled matrix-core multiply-accumulate and the one-thread-per-bin kernel must agree to rounding,
+    and both must meet the oracle bar (row/column padding, several row blocks, channel chunks)."""
+    S, f, fo, n, k = shape
+    inp, w, b = _rand(21 + f, S, f, fo, n, k)
+    _say(f"[mac] {shape}")
+    fast = _run_gpu(inp, w, b, False).cpu().numpy().astype(np.float64)
+    plain = _run_gpu(inp, w, b, False, mac_reference=True).cpu().numpy().astype(np.float64)
+    exp = oracle.conv3d(inp, w, b, relu=False)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    assert np.all(np.abs(fast - exp) <= tol)
+    assert np.all(np.abs(plain - exp) <= tol)
+    assert np.all(np.abs(fast - plain) <= 0.1 * tol)
+
+
 def test_relu_flag_and_null_bias(oracle):
     S, f, fo, n, k = 1, 2, 2, 16, 3
     inp, w, b = _rand(11, S, f, fo, n, k)
