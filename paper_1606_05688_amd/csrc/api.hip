@@ -47,7 +47,7 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     if (N == 0) return ZNNI_ERR_UNSUPPORTED_SIZE;
     // launch-grid limits (grid y/z <= 65535) and 32-bit index products used inside the kernels
     if ((long long)S * f > 65535 || (long long)S * fo > 65535) return ZNNI_ERR_SHAPE;
-    if ((long long)fo * f * k * k > (1ll << 30)) return ZNNI_ERR_SHAPE;
+    if (((long long)fo + 15) * (f + 3) * k * k > (1ll << 30)) return ZNNI_ERR_SHAPE;
     if ((long long)S * (f > fo ? f : fo) * n > (1ll << 30)) return ZNNI_ERR_SHAPE;
     L->S = S; L->f = f; L->fo = fo; L->n = n; L->k = k;
     L->N = N;
@@ -65,7 +65,7 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     const size_t c = sizeof(float2);
     const size_t zc = L->zc, no = L->no, nn = n, NN = N;
     const size_t sz_tw = NN * c;
-    const size_t sz_A1 = zc * fo * f * k * k * c;
+    const size_t sz_A1 = zc * k * k * L->fp * L->Mp * c;
     const size_t sz_A = zc * NN * k * L->fp * L->Mp * c;
     size_t b0 = (size_t)L->nimg * nn * zc * nn;                    // X1
     size_t t = zc * NN * L->nimg * NN; if (t > b0) b0 = t;         // Xt

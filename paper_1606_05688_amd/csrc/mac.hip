@@ -27,38 +27,39 @@ namespace znni {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// A1[oz][row][.] with row = ((j*f+i)*k + a)*k + b :  sum_c w[row][c] exp(-2 pi i oz c / N)
+// A1[oz][b][a][i<fp][j<Mp] = sum_c w[j][i][a][b][c] exp(-2 pi i oz c / N); zero where i >= f or j >= fo.
+// (j fastest, so the y stage below reads and writes contiguous runs.)
 __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, const float2* __restrict__ tw,
-                          int N, int nrows, int k)
-{
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    const int oz = blockIdx.y;
-    if (row >= nrows) return;
-    const float* wr = w + (size_t)row * k;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int c = 0; c < k; ++c) acc = caxpy(acc, wr[c], tw[(oz * c) % N]);
-    A1[(size_t)oz * nrows + row] = acc;
-}
-
-// A[oz][oy][a][i<fp][j<Mp] = scale * sum_b A1[oz][((j*f+i)*k+a)][b] exp(-2 pi i oy b / N); zero where i >= f
-// or j >= fo (fp, Mp: f and fo rounded up to the matrix-core tile, 4 and 16).
-__global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
-                          int N, int f, int fo, int k, int fp, int Mp, float scale)
+                          int N, int f, int fo, int k, int fp, int Mp)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    const int oy = blockIdx.y, oz = blockIdx.z;
-    const int per = k * fp * Mp;
+    const int oz = blockIdx.y;
+    const int per = k * k * fp * Mp;
     if (idx >= per) return;
     const int j = idx % Mp;
     const int i = (idx / Mp) % fp;
-    const int a = idx / (Mp * fp);
+    const int ba = idx / (Mp * fp);
+    const int a = ba % k, b = ba / k;
     float2 acc = make_float2(0.f, 0.f);
     if (i < f && j < fo) {
-        const float2* a1 = A1 + ((size_t)oz * fo * f * k + (size_t)(j * f + i) * k + a) * k;
-        for (int b = 0; b < k; ++b) acc = cadd(acc, cmul(a1[b], tw[(oy * b) % N]));
-        acc = cscale(acc, scale);
+        const float* wr = w + ((((size_t)j * f + i) * k + a) * k + b) * k;
+        for (int c = 0; c < k; ++c) acc = caxpy(acc, wr[c], tw[(oz * c) % N]);
     }
-    A[((size_t)oz * N + oy) * per + idx] = acc;
+    A1[(size_t)oz * per + idx] = acc;
+}
+
+// A[oz][oy][a][i<fp][j<Mp] = scale * sum_b A1[oz][b][a][i][j] exp(-2 pi i oy b / N)
+// (fp, Mp: f and fo rounded up to the matrix-core tile, 4 and 16; the padding holds zeros).
+__global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
+                          int N, int k, int per, float scale)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j)
+    const int oy = blockIdx.y, oz = blockIdx.z;
+    if (idx >= per) return;
+    const float2* a1 = A1 + (size_t)oz * k * per + idx;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int b = 0; b < k; ++b) acc = cadd(acc, cmul(a1[(size_t)b * per], tw[(oy * b) % N]));
+    A[((size_t)oz * N + oy) * per + idx] = cscale(acc, scale);
 }
 
 // Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
@@ -208,13 +209,13 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
 
 znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st)
 {
-    const int nrows = L.fo * L.f * L.k * L.k;
-    k_kprep_z<<<dim3((nrows + 255) / 256, L.zc), dim3(256), 0, st>>>(w, L.A1, L.tw, L.N, nrows, L.k);
+    const int per = L.k * L.fp * L.Mp;
+    const int per1 = per * L.k;
+    k_kprep_z<<<dim3((per1 + 255) / 256, L.zc), dim3(256), 0, st>>>(w, L.A1, L.tw, L.N, L.f, L.fo, L.k, L.fp,
+                                                                    L.Mp);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
-    const int per = L.k * L.fp * L.Mp;
-    k_kprep_y<<<dim3((per + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, L.f, L.fo, L.k,
-                                                                       L.fp, L.Mp, scale);
+    k_kprep_y<<<dim3((per + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, L.k, per, scale);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }

@@ -28,7 +28,7 @@ struct LayerPlan {
     FftPlan fft;
     // workspace carving (device pointers)
     float2* tw;   // [N] exp(-2 pi i q / N)
-    float2* A1;   // [zc][fo*f*k][k]     kernel transform after the z stage
+    float2* A1;   // [zc][k(b)][k(a)][fp][Mp]  kernel transform after the z stage
     float2* A;    // [zc][N][k][fp][Mp]  kernel transform after the z and y stages, scaled by 1/N^3
     float2* buf0;
     float2* buf1;
