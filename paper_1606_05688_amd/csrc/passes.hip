@@ -254,6 +254,7 @@ znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
 
 znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_fwd_z(L, in, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL / 2);
     znni_status rc = allow_lds((const void*)k_fwd_z, lds);
@@ -266,6 +267,7 @@ znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 
 znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_fwd_y(L, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL);
     znni_status rc = allow_lds((const void*)k_fwd_y, lds);
@@ -278,6 +280,7 @@ znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
 
 znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_fwd_x(L, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL);
     znni_status rc = allow_lds((const void*)k_fwd_x, lds);
@@ -290,6 +293,7 @@ znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
 
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_inv_x(L, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL);
     znni_status rc = allow_lds((const void*)k_inv_x, lds);
@@ -302,6 +306,7 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
 
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_inv_y(L, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL);
     znni_status rc = allow_lds((const void*)k_inv_y, lds);
@@ -314,6 +319,7 @@ znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
 
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {
+    if (fast_pass_available(L.N)) return launch_fast_inv_z(L, bias, out, flags, st);
     const int TL = L.TL;
     const size_t lds = pass_lds_bytes(L.N, TL / 2);
     znni_status rc = allow_lds((const void*)k_inv_z, lds);

@@ -1,0 +1,295 @@
+// passes_fast.hip -- the six transform passes for transform lengths N = R1*R2 with both factors small enough
+// for an in-register DFT (16, 64, 128, 256, 320).  Same layouts, pruning and results as passes.hip.
+//
+// One workgroup transforms a tile of 16 lines (passes along z: 16 pairs of real lines).  Each line is done in
+// two steps.  Step A: thread (line, j < R2) loads the R1 samples j, j+R2, j+2R2, ... straight from HBM into
+// registers (16 consecutive j of a line make a 128-byte run), does a length-R1 DFT, multiplies by the
+// twiddles w_N^(j q) and parks the result in LDS.  Step B: thread (q < R1, line) picks up the R2 values of
+// its q, does a length-R2 DFT and holds outputs q, q+R1, q+2R1, ...; with the line index fastest across
+// lanes, the 16 lines of the tile form one 128-byte run per output index, so passes whose output has the next
+// axis contiguous store straight from registers.  Passes whose output is contiguous along the transformed
+// axis, and the real<->complex passes, go through LDS once more.  Every byte of a tensor is read once and
+// written once per pass; LDS sees one exchange per element.
+#include "fft_regs.h"
+#include "znni_internal.h"
+
+namespace znni {
+
+enum PassKind { P_FWD_Z, P_FWD_Y, P_FWD_X, P_INV_X, P_INV_Y, P_INV_Z };
+
+struct PassArgs {
+    const void* src;
+    void* dst;
+    const float2* tw;      // [N]
+    const float* bias;     // inv_z only
+    int n, zc, no, k, ldz, nimg, fo, relu;
+};
+
+template <int R1, int R2> struct TwoStep {
+    static constexpr int N = R1 * R2;
+    static constexpr int T = R1 > R2 ? R1 : R2;      // threads per line
+    static constexpr int NTH = 16 * T;               // threads per workgroup
+    static constexpr int P = N + 2;                  // LDS line pitch (complex); even, so 16-byte reads stay aligned
+    static constexpr int LDS_BYTES = (int)sizeof(float2) * (N + 16 * P);
+
+    // Step A on the R1 samples in v (sample m is element j + R2*m of the line), result to LDS.
+    static __device__ __forceinline__ void step_a(float2* v, int line, int j, const float2* tws, float2* buf)
+    {
+        Dft<R1>::run(v);
+#pragma unroll
+        for (int q = 1; q < R1; ++q) v[q] = cmul(v[q], tws[j * q]);
+#pragma unroll
+        for (int q = 0; q < R1; ++q) buf[line * P + q * R2 + j] = v[q];
+    }
+    // Step B for (line, q): u[r] becomes element q + R1*r of the transformed line.
+    static __device__ __forceinline__ void step_b(float2* u, int line, int q, const float2* buf)
+    {
+        const float4* p = reinterpret_cast<const float4*>(buf + line * P + q * R2);
+#pragma unroll
+        for (int h = 0; h < R2 / 2; ++h) {
+            const float4 t = p[h];
+            u[2 * h] = make_float2(t.x, t.y);
+            u[2 * h + 1] = make_float2(t.z, t.w);
+        }
+        Dft<R2>::run(u);
+    }
+};
+
+template <int R1, int R2, int KIND>
+__global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
+{
+    using TS = TwoStep<R1, R2>;
+    constexpr int N = TS::N, P = TS::P, NTH = TS::NTH;
+    extern __shared__ float2 lds[];
+    float2* tws = lds;
+    float2* buf = lds + N;
+    const int t = threadIdx.x;
+    for (int q = t; q < N; q += NTH) tws[q] = a.tw[q];
+
+    const int tile = blockIdx.x, mid = blockIdx.y, img = blockIdx.z;
+    const int n = a.n, zc = a.zc, no = a.no;
+
+    // ---- where the 16 lines of this tile start, how far apart they are, how many exist, how long they are
+    const float2* src = nullptr;      // complex passes
+    size_t lpitch = 0;
+    int nvalid = 0, lin = N;
+    if constexpr (KIND == P_FWD_Y) {          // tile: 16 x of one (img, oz); lines along y in X1
+        const int x0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + ((size_t)(img * n + x0) * zc + oz) * n;
+        lpitch = (size_t)zc * n; nvalid = min(16, n - x0); lin = n;
+    } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
+        const int oy0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + (((size_t)img * zc + oz) * N + oy0) * n;
+        lpitch = n; nvalid = min(16, N - oy0); lin = n;
+    } else if constexpr (KIND == P_INV_X) {   // tile: 16 oy of one (oz, imgo); lines along ox in Yt
+        const int oy0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + (((size_t)oz * N + oy0) * a.nimg + img) * N;
+        lpitch = (size_t)a.nimg * N; nvalid = min(16, N - oy0);
+    } else if constexpr (KIND == P_INV_Y) {   // tile: 16 oz of one (imgo, xo); lines along oy in Y2
+        const int oz0 = tile * 16, xo = mid;
+        src = (const float2*)a.src + (((size_t)img * zc + oz0) * no + xo) * N;
+        lpitch = (size_t)no * N; nvalid = min(16, zc - oz0);
+    }
+
+    // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
+    const int ja = t % R2, la = t / R2;       // la < 16 only for t < 16*R2
+    const bool in_a = t < 16 * R2;
+    float2 v[R1];
+    if (in_a) {
+        if constexpr (KIND == P_FWD_Z) {
+            // two real lines y0+2*la, y0+2*la+1 of one (img, x) ride as real and imaginary part
+            const int y0 = tile * 32, x = mid;
+            const int ya = y0 + 2 * la;
+            const float* ra = (const float*)a.src + ((size_t)(img * n + x) * n + ya) * n;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const int e = ja + R2 * m;
+                float re = 0.f, im = 0.f;
+                if (e < n) {
+                    if (ya < n) re = ra[e];
+                    if (ya + 1 < n) im = ra[n + e];
+                }
+                v[m] = make_float2(re, im);
+            }
+        } else if constexpr (KIND == P_INV_Z) {
+            // lines yo0+2*la (A) and yo0+2*la+1 (B) of one (imgo, xo): Z = A + iB extended by Hermitian
+            // symmetry, conjugated for the inverse-by-forward route
+            const int yo0 = tile * 32, xo = mid;
+            const int ya = yo0 + 2 * la;
+            const float2* pa = (const float2*)a.src + (((size_t)img * no + xo) * no + ya) * a.ldz;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const int e = ja + R2 * m;
+                const bool direct = e < zc;
+                const int ee = direct ? e : N - e;
+                float2 A = make_float2(0.f, 0.f), B = A;
+                if (ya < no) A = pa[ee];
+                if (ya + 1 < no) B = pa[a.ldz + ee];
+                if (!direct) { A = cconj(A); B = cconj(B); }
+                v[m] = cconj(cadd(A, mul_pi(B)));
+            }
+        } else {
+            const float2* ls = src + (size_t)la * lpitch;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const int e = ja + R2 * m;
+                float2 x = make_float2(0.f, 0.f);
+                if (la < nvalid && e < lin) x = ls[e];
+                if constexpr (KIND == P_INV_X || KIND == P_INV_Y) x = cconj(x);
+                v[m] = x;
+            }
+        }
+    }
+    __syncthreads();                          // twiddle table is in LDS
+    if (in_a) TS::step_a(v, la, ja, tws, buf);
+    __syncthreads();
+
+    // ---- step B
+    const int lb = t & 15, q = t >> 4;        // q < T; only q < R1 has work
+    float2 u[R2];
+    if (q < R1) TS::step_b(u, lb, q, buf);
+
+    if constexpr (KIND == P_FWD_Y) {
+        // X2[img][oz][oy][x0 + lb]
+        if (q < R1 && lb < nvalid) {
+            float2* d = (float2*)a.dst + ((size_t)img * zc + mid) * N * n + tile * 16 + lb;
+#pragma unroll
+            for (int r = 0; r < R2; ++r) d[(size_t)(q + R1 * r) * n] = u[r];
+        }
+    } else if constexpr (KIND == P_INV_X) {
+        // Y2[imgo][oz][xo][oy0 + lb], xo = element - (k-1) in [0, no)
+        if (q < R1 && lb < nvalid) {
+            float2* d = (float2*)a.dst + ((size_t)img * zc + mid) * no * N + tile * 16 + lb;
+#pragma unroll
+            for (int r = 0; r < R2; ++r) {
+                const int xo = q + R1 * r - (a.k - 1);
+                if (xo >= 0 && xo < no) d[(size_t)xo * N] = cconj(u[r]);
+            }
+        }
+    } else if constexpr (KIND == P_INV_Y) {
+        // Y1[imgo][xo][yo][oz0 + lb]
+        if (q < R1 && lb < nvalid) {
+            float2* d = (float2*)a.dst + ((size_t)img * no + mid) * no * a.ldz + tile * 16 + lb;
+#pragma unroll
+            for (int r = 0; r < R2; ++r) {
+                const int yo = q + R1 * r - (a.k - 1);
+                if (yo >= 0 && yo < no) d[(size_t)yo * a.ldz] = cconj(u[r]);
+            }
+        }
+    } else {
+        // second trip through LDS: natural order per line
+        __syncthreads();
+        if (q < R1) {
+#pragma unroll
+            for (int r = 0; r < R2; ++r) buf[lb * P + q + R1 * r] = u[r];
+        }
+        __syncthreads();
+        if constexpr (KIND == P_FWD_X) {
+            // Xt[oz][oy0 + l][img][ox]: whole lines, contiguous
+            const int oy0 = tile * 16;
+            for (int l = t / 64; l < nvalid; l += NTH / 64) {
+                float2* d = (float2*)a.dst + (((size_t)mid * N + oy0 + l) * a.nimg + img) * N;
+                for (int e = t % 64; e < N; e += 64) d[e] = buf[l * P + e];
+            }
+        } else if constexpr (KIND == P_FWD_Z) {
+            // untangle the two real lines and store X1[img][x][oz][y0 + ll], ll < 32 fastest across lanes
+            const int y0 = tile * 32;
+            float2* d = (float2*)a.dst + (size_t)(img * n + mid) * zc * n + y0;
+            const int ll = t & 31;
+            if (y0 + ll < n) {
+                const float2* row = buf + (ll >> 1) * P;
+                for (int oz = t >> 5; oz < zc; oz += NTH / 32) {
+                    const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
+                    d[(size_t)oz * n + ll] = (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
+                                                      : cscale(cadd(z1, z2), 0.5f);
+                }
+            }
+        } else {   // P_INV_Z: real part -> line 2l, minus imaginary part -> line 2l+1; crop, bias, transfer
+            const int yo0 = tile * 32;
+            const float bj = a.bias ? a.bias[img % a.fo] : 0.f;
+            float* d = (float*)a.dst + (((size_t)img * no + mid) * no + yo0) * no;
+            const int rows = min(32, no - yo0);
+            for (int ll = t / 64; ll < rows; ll += NTH / 64) {
+                const float2* row = buf + (ll >> 1) * P + (a.k - 1);
+                for (int zo = t % 64; zo < no; zo += 64) {
+                    const float2 c = row[zo];
+                    float v = ((ll & 1) ? -c.y : c.x) + bj;
+                    if (a.relu) v = fmaxf(v, 0.f);
+                    d[(size_t)ll * no + zo] = v;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------- host side
+template <int R1, int R2, int KIND>
+static znni_status launch_one(const PassArgs& a, dim3 grid, hipStream_t st)
+{
+    using TS = TwoStep<R1, R2>;
+    const void* fn = (const void*)k_pass<R1, R2, KIND>;
+    if (TS::LDS_BYTES > 48 * 1024 &&
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TS::LDS_BYTES) != hipSuccess)
+        return ZNNI_ERR_HIP;
+    k_pass<R1, R2, KIND><<<grid, dim3(TS::NTH), TS::LDS_BYTES, st>>>(a);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
+}
+
+template <int KIND>
+static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t st)
+{
+    switch (N) {
+        case 16: return launch_one<4, 4, KIND>(a, grid, st);
+        case 64: return launch_one<8, 8, KIND>(a, grid, st);
+        case 128: return launch_one<8, 16, KIND>(a, grid, st);
+        case 256: return launch_one<16, 16, KIND>(a, grid, st);
+        case 320: return launch_one<20, 16, KIND>(a, grid, st);
+    }
+    return ZNNI_ERR_UNSUPPORTED_SIZE;
+}
+
+bool fast_pass_available(int N) { return N == 16 || N == 64 || N == 128 || N == 256 || N == 320; }
+
+static PassArgs base_args(const LayerPlan& L, const void* src, void* dst)
+{
+    PassArgs a;
+    a.src = src; a.dst = dst; a.tw = L.tw; a.bias = nullptr;
+    a.n = L.n; a.zc = L.zc; a.no = L.no; a.k = L.k; a.ldz = L.ldz; a.nimg = L.nimg; a.fo = L.fo; a.relu = 0;
+    return a;
+}
+
+znni_status launch_fast_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
+{
+    return launch_kind<P_FWD_Z>(L.N, base_args(L, in, L.buf0), dim3((L.n + 31) / 32, L.n, L.nimg), st);
+}
+znni_status launch_fast_fwd_y(const LayerPlan& L, hipStream_t st)
+{
+    return launch_kind<P_FWD_Y>(L.N, base_args(L, L.buf0, L.buf1), dim3((L.n + 15) / 16, L.zc, L.nimg), st);
+}
+znni_status launch_fast_fwd_x(const LayerPlan& L, hipStream_t st)
+{
+    return launch_kind<P_FWD_X>(L.N, base_args(L, L.buf1, L.buf0), dim3((L.N + 15) / 16, L.zc, L.nimg), st);
+}
+znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
+{
+    PassArgs a = base_args(L, L.buf1, L.buf0);
+    a.nimg = L.nimgo;
+    return launch_kind<P_INV_X>(L.N, a, dim3((L.N + 15) / 16, L.zc, L.nimgo), st);
+}
+znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)
+{
+    PassArgs a = base_args(L, L.buf0, L.buf1);
+    a.nimg = L.nimgo;
+    return launch_kind<P_INV_Y>(L.N, a, dim3((L.zc + 15) / 16, L.no, L.nimgo), st);
+}
+znni_status launch_fast_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
+{
+    PassArgs a = base_args(L, L.buf1, out);
+    a.nimg = L.nimgo;
+    a.bias = bias;
+    a.relu = (flags & ZNNI_RELU) ? 1 : 0;
+    return launch_kind<P_INV_Z>(L.N, a, dim3((L.no + 31) / 32, L.no, L.nimgo), st);
+}
+
+}  // namespace znni

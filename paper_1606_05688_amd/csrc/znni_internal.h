@@ -52,4 +52,13 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
 
+// Two-step in-register passes for selected transform lengths (passes_fast.hip).
+bool fast_pass_available(int N);
+znni_status launch_fast_fwd_z(const LayerPlan& L, const float* in, hipStream_t st);
+znni_status launch_fast_fwd_y(const LayerPlan& L, hipStream_t st);
+znni_status launch_fast_fwd_x(const LayerPlan& L, hipStream_t st);
+znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st);
+znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st);
+znni_status launch_fast_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
+
 }  // namespace znni

@@ -79,6 +79,19 @@ def test_small_layers_full_compare(oracle, shape):
     _check_full(oracle, inp, w, None, False, f"small {shape} linear")
 
 
+# Transform lengths served by the two-step in-register passes (16, 64, 128, 256, 320), at the length itself
+# and just below it (zero-padded lines, ragged tiles of lines).
+TWO_STEP = [(2, 2, 3, 16, 3), (1, 2, 2, 15, 2), (1, 3, 2, 64, 5), (2, 1, 2, 61, 4), (1, 2, 1, 128, 3),
+            (1, 1, 2, 127, 6), (1, 1, 1, 256, 3), (1, 1, 1, 250, 2), (1, 1, 2, 320, 5), (1, 2, 1, 317, 3)]
+
+
+@pytest.mark.parametrize("shape", TWO_STEP, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_two_step_pass_lengths_full_compare(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand(300 + n + k, S, f, fo, n, k)
+    _check_full(oracle, inp, w, b, True, f"two-step {shape}")
+
+
 @pytest.mark.parametrize("idx", [0, 1])
 def test_benchmark_layers_full_compare(oracle, idx):
     L = W.CONFIGS[idx]
