@@ -53,7 +53,7 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     L->N = N;
     L->zc = N / 2 + 1;
     L->no = n - k + 1;
-    L->ldz = (L->zc + 1) & ~1;
+    L->ldz = (L->zc + 15) & ~15;     // Y1 rows start on 128-byte boundaries
     L->nimg = S * f;
     L->nimgo = S * fo;
     L->TL = lines_per_tile(N);

@@ -95,48 +95,51 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     const int ja = t % R2, la = t / R2;       // la < 16 only for t < 16*R2
     const bool in_a = t < 16 * R2;
     float2 v[R1];
+    // Every load is issued unconditionally from a clamped (always valid, so finite) address and multiplied by
+    // a 0/1 mask afterwards: a select would be turned back into a branch around each load, which fences the
+    // R1 loads of a thread one by one instead of keeping them all in flight.
     if (in_a) {
         if constexpr (KIND == P_FWD_Z) {
             // two real lines y0+2*la, y0+2*la+1 of one (img, x) ride as real and imaginary part
             const int y0 = tile * 32, x = mid;
             const int ya = y0 + 2 * la;
-            const float* ra = (const float*)a.src + ((size_t)(img * n + x) * n + ya) * n;
+            const float ma = ya < n ? 1.f : 0.f, mb = ya + 1 < n ? 1.f : 0.f;
+            const float* ra = (const float*)a.src + ((size_t)(img * n + x) * n + min(ya, n - 1)) * n;
+            const float* rb = (const float*)a.src + ((size_t)(img * n + x) * n + min(ya + 1, n - 1)) * n;
 #pragma unroll
             for (int m = 0; m < R1; ++m) {
-                const int e = ja + R2 * m;
-                float re = 0.f, im = 0.f;
-                if (e < n) {
-                    if (ya < n) re = ra[e];
-                    if (ya + 1 < n) im = ra[n + e];
-                }
-                v[m] = make_float2(re, im);
+                const int e = ja + R2 * m, ec = min(e, n - 1);
+                const float me = e < n ? 1.f : 0.f;
+                v[m] = make_float2(ra[ec] * (me * ma), rb[ec] * (me * mb));
             }
         } else if constexpr (KIND == P_INV_Z) {
             // lines yo0+2*la (A) and yo0+2*la+1 (B) of one (imgo, xo): Z = A + iB extended by Hermitian
             // symmetry, conjugated for the inverse-by-forward route
             const int yo0 = tile * 32, xo = mid;
             const int ya = yo0 + 2 * la;
-            const float2* pa = (const float2*)a.src + (((size_t)img * no + xo) * no + ya) * a.ldz;
+            const float ma = ya < no ? 1.f : 0.f, mb = ya + 1 < no ? 1.f : 0.f;
+            const float2* pa = (const float2*)a.src + (((size_t)img * no + xo) * no + min(ya, no - 1)) * a.ldz;
+            const float2* pb = (const float2*)a.src + (((size_t)img * no + xo) * no + min(ya + 1, no - 1)) * a.ldz;
 #pragma unroll
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
                 const bool direct = e < zc;
                 const int ee = direct ? e : N - e;
-                float2 A = make_float2(0.f, 0.f), B = A;
-                if (ya < no) A = pa[ee];
-                if (ya + 1 < no) B = pa[a.ldz + ee];
-                if (!direct) { A = cconj(A); B = cconj(B); }
+                const float sg = direct ? 1.f : -1.f;                    // mirrored half: conjugate
+                float2 A = pa[ee], B = pb[ee];
+                A = make_float2(A.x * ma, A.y * (ma * sg));
+                B = make_float2(B.x * mb, B.y * (mb * sg));
                 v[m] = cconj(cadd(A, mul_pi(B)));
             }
         } else {
-            const float2* ls = src + (size_t)la * lpitch;
+            const float ml = la < nvalid ? 1.f : 0.f;
+            const float2* ls = src + (size_t)min(la, nvalid - 1) * lpitch;
 #pragma unroll
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
-                float2 x = make_float2(0.f, 0.f);
-                if (la < nvalid && e < lin) x = ls[e];
-                if constexpr (KIND == P_INV_X || KIND == P_INV_Y) x = cconj(x);
-                v[m] = x;
+                const float mk = e < lin ? ml : 0.f;
+                const float2 x = ls[min(e, lin - 1)];
+                v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y) ? -(x.y * mk) : x.y * mk);
             }
         }
     }

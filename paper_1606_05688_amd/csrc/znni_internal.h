@@ -16,7 +16,7 @@ struct LayerPlan {
     int N;        // transform size n~
     int zc;       // N/2 + 1 bins along the halved axis
     int no;       // n - k + 1
-    int ldz;      // row stride of Y1 (zc rounded up to even)
+    int ldz;      // row stride of Y1 (zc rounded up to a multiple of 16 complex = 128 bytes)
     int nimg;     // S * f
     int nimgo;    // S * fo
     int TL;       // lines per tile in the transform passes
