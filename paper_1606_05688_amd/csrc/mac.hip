@@ -97,14 +97,14 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 // blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
 // row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
 // so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
-template <int NT>
+template <int NT, int CG>
 __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
                                                   int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
-                                                  int RG, int CG, int ncolblk, int nmblk, int npencils)
+                                                  int RG, int ncolblk, int nmblk, int npencils)
 {
     extern __shared__ float2 lds[];
-    const int NW = 16 * NT * CG;
+    constexpr int NW = 16 * NT * CG;
     float2* tws = lds;              // [N]
     float2* Xs = lds + N;           // [FC][NW]
 
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
     const int sub = slot % per_pencil;
     const int colblk = sub % ncolblk, mblk = sub / ncolblk;
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rg = wave % RG, cg = wave / RG;
     const int l16 = lane & 15, kk = lane >> 4;
     const int Ct = S * N;                           // columns of the pencil
@@ -141,49 +141,94 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
     for (int ic0 = 0; ic0 < fp; ic0 += FC) {
         const int fc = min(FC, fp - ic0);           // multiple of 4
         __syncthreads();
-        for (int i = wave; i < fc; i += nwaves) {
-            const int gi = ic0 + i;
-            for (int c = lane; c < NW; c += 64) {
-                const int col = colbase + c;
+        // ---- stage the fc x NW block of image spectra (rows beyond f and columns beyond Ct hold zeros).
+        // Loads come from clamped, always valid addresses and are masked by a multiply, so the compiler keeps
+        // several of them in flight instead of branching around each one.
+        if ((N & 1) == 0) {
+            constexpr int HW = NW / 2;              // 16-byte units per row
+#pragma unroll 4
+            for (int e = threadIdx.x; e < fc * HW; e += blockDim.x) {
+                const int i = e / HW, c = (e - i * HW) * 2;
+                const int gi = ic0 + i, col = colbase + c;
+                const float mk = (gi < f && col < Ct) ? 1.f : 0.f;
+                const int colc = min(col, Ct - 2), gic = min(gi, f - 1);
+                const int sI = colc / N, ox = colc - sI * N;
+                const float4 v = *reinterpret_cast<const float4*>(Xp + (size_t)(sI * f + gic) * N + ox);
+                *reinterpret_cast<float4*>(Xs + i * NW + c) = make_float4(v.x * mk, v.y * mk, v.z * mk, v.w * mk);
+            }
+        } else {
+            for (int e = threadIdx.x; e < fc * NW; e += blockDim.x) {
+                const int i = e / NW, c = e - i * NW;
+                const int gi = ic0 + i, col = colbase + c;
                 float2 v = make_float2(0.f, 0.f);
                 if (gi < f && col < Ct) {
-                    const int s = col / N, ox = col - s * N;
-                    v = Xp[(size_t)(s * f + gi) * N + ox];
+                    const int sI = col / N, ox = col - sI * N;
+                    v = Xp[(size_t)(sI * f + gi) * N + ox];
                 }
                 Xs[i * NW + c] = v;
             }
         }
         __syncthreads();
         if (!active) continue;
-        for (int a = 0; a < k; ++a) {
-            floatx4 p1[NT], p2[NT], p3[NT];
+
+        // ---- k * fc/4 matrix-core steps; step (a, j) uses A[a][ic0 + 4j + kk][m0 + l16].  The A operand of
+        // step s+4 is requested while step s computes (ring of 4), far enough ahead to cover an HBM miss.
+        const int nst = fc >> 2, ST = k * nst;
+        const size_t jstride = (size_t)4 * Mp;
+        const size_t awrap = (size_t)fp * Mp - (size_t)nst * jstride;      // from the end of one a to the next
+        const float2* pp = Ap + (size_t)(ic0 + kk) * Mp + m0 + l16;        // prefetch cursor
+        int pj = 0, sp = 0;
+        float2 ring[4];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) { p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t]; }
-            const float2* Aa = Ap + ((size_t)(a * fp + ic0 + kk)) * Mp + m0 + l16;
-            const float2* Xw = Xs + kk * NW + cw0 + l16;
-            float2 av = Aa[0];
-            for (int i4 = 0; i4 < fc; i4 += 4) {
-                const float2 ac = av;
-                if (i4 + 4 < fc) av = Aa[(size_t)(i4 + 4) * Mp];
-                const float as = ac.x + ac.y;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float2 xv = Xw[i4 * NW + t * 16];
-                    p1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.x, xv.x, p1[t], 0, 0, 0);
-                    p2[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.y, xv.y, p2[t], 0, 0, 0);
-                    p3[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, xv.x + xv.y, p3[t], 0, 0, 0);
-                }
+        for (int d = 0; d < 4; ++d) {
+            ring[d] = make_float2(0.f, 0.f);
+            if (sp < ST) {
+                ring[d] = *pp;
+                pp += jstride; ++sp;
+                if (++pj == nst) { pj = 0; pp += awrap; }
             }
-            // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element r of lane l is row 4*(l/16)+r, column l%16
+        }
+        floatx4 p1[NT], p2[NT], p3[NT];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float2 T = tws[(a * oxs[t]) % N];
+        for (int t = 0; t < NT; ++t) { p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t]; }
+        const float2* Xw = Xs + kk * NW + cw0 + l16;
+        int cj = 0, ca = 0;
+        for (int s0 = 0; s0 < ST; s0 += 4) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pr = p1[t][r] - p2[t][r];
-                    const float pi = p3[t][r] - p1[t][r] - p2[t][r];
-                    yr[t][r] += T.x * pr - T.y * pi;
-                    yi[t][r] += T.x * pi + T.y * pr;
+            for (int d = 0; d < 4; ++d) {
+                if (s0 + d < ST) {
+                    const float2 ac = ring[d];
+                    if (sp < ST) {
+                        ring[d] = *pp;
+                        pp += jstride; ++sp;
+                        if (++pj == nst) { pj = 0; pp += awrap; }
+                    }
+                    const float as = ac.x + ac.y;
+                    const float2* xr = Xw + cj * 4 * NW;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const float2 xv = xr[t * 16];
+                        p1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.x, xv.x, p1[t], 0, 0, 0);
+                        p2[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.y, xv.y, p2[t], 0, 0, 0);
+                        p3[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, xv.x + xv.y, p3[t], 0, 0, 0);
+                    }
+                    if (++cj == nst) {
+                        // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element r of lane l is row 4*(l/16)+r,
+                        // column l%16
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            const float2 T = tws[(ca * oxs[t]) % N];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float pr = p1[t][r] - p2[t][r];
+                                const float pi = p3[t][r] - p1[t][r] - p2[t][r];
+                                yr[t][r] += T.x * pr - T.y * pi;
+                                yi[t][r] += T.x * pi + T.y * pr;
+                            }
+                            p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t];
+                        }
+                        cj = 0; ++ca;
+                    }
                 }
             }
         }
@@ -249,18 +294,18 @@ void plan_mac(LayerPlan* L)
     L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)FC * NW);
 }
 
-template <int NT>
+template <int NT, int CG>
 static znni_status launch_mac_nt(const LayerPlan& L, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma<NT>;
+    const void* fn = (const void*)k_mac_mfma<NT, CG>;
     if (L.mac_lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.mac_lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.zc * L.N;
     const int per_pencil = L.mac_ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma<NT><<<dim3((unsigned)blocks), dim3(64 * L.mac_RG * L.mac_CG), L.mac_lds, st>>>(
-        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_RG, L.mac_CG,
+    k_mac_mfma<NT, CG><<<dim3((unsigned)blocks), dim3(64 * L.mac_RG * CG), L.mac_lds, st>>>(
+        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_RG,
         L.mac_ncolblk, L.mac_nmblk, npencils);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
@@ -274,11 +319,13 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
-    switch (L.mac_NT) {
-        case 5: return launch_mac_nt<5>(L, st);
-        case 4: return launch_mac_nt<4>(L, st);
-        case 2: return launch_mac_nt<2>(L, st);
-        default: return launch_mac_nt<1>(L, st);
+    switch (L.mac_NT * 10 + L.mac_CG) {
+        case 52: return launch_mac_nt<5, 2>(L, st);
+        case 42: return launch_mac_nt<4, 2>(L, st);
+        case 51: return launch_mac_nt<5, 1>(L, st);
+        case 41: return launch_mac_nt<4, 1>(L, st);
+        case 21: return launch_mac_nt<2, 1>(L, st);
+        default: return launch_mac_nt<1, 1>(L, st);
     }
 }
 
