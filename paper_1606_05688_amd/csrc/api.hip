@@ -58,8 +58,7 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     L->nimgo = S * fo;
     L->TL = lines_per_tile(N);
     L->fp = (f + 3) & ~3;
-    L->Mp = (fo + 15) & ~15;
-    plan_mac(L);
+    plan_mac(L);        // also sets Mp
     make_fft_plan(N, &L->fft);
 
     const size_t c = sizeof(float2);

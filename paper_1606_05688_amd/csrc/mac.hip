@@ -88,23 +88,25 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 
 // Matrix-core multiply-accumulate.
 //
-// One workgroup = one pencil x one block of NW = 16*NT*CG columns x one block of 16*RG output rows.
-// Wave (rg, cg) owns a 16 x (16*NT) tile of Yt.  The fp x NW block of image spectra stays in LDS for the
-// whole call (in chunks of FC input images if it does not fit); A is streamed from global memory straight
-// into the matrix-core operand layout (lane l supplies A[row l%16][k-index l/16]), every wave of a row
-// group reading the same values, which the vector L1 serves.
+// One workgroup = 4 waves = one pencil x one block of NW = 64*CTW columns x one block of 16*RTW output rows.
+// Four waves per workgroup put exactly one wave on each of the CU's four SIMDs, which keeps the four matrix
+// cores evenly loaded however many workgroups share the CU.  Wave w owns the RTW x CTW tiles (16x16 each) of
+// all RTW row tiles in its own 16*CTW columns.  The fp x NW block of image spectra stays in LDS for the whole
+// call (in chunks of FC input images if it does not fit); A is streamed from global memory straight into the
+// matrix-core operand layout (lane l supplies A[row l%16][k-index l/16]); the four waves of a workgroup read
+// the same A values, which the vector L1 serves.
 //
 // blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
 // row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
 // so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
-template <int NT, int CG>
-__global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
+template <int RTW, int CTW>
+__global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
                                                   int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
-                                                  int RG, int ncolblk, int nmblk, int npencils)
+                                                  int ncolblk, int nmblk, int npencils)
 {
     extern __shared__ float2 lds[];
-    constexpr int NW = 16 * NT * CG;
+    constexpr int NW = 64 * CTW;
     float2* tws = lds;              // [N]
     float2* Xs = lds + N;           // [FC][NW]
 
@@ -116,27 +118,27 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
     const int colblk = sub % ncolblk, mblk = sub / ncolblk;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rg = wave % RG, cg = wave / RG;
     const int l16 = lane & 15, kk = lane >> 4;
     const int Ct = S * N;                           // columns of the pencil
-    const int m0 = (mblk * RG + rg) * 16;           // first output row of this wave (may be >= Mp: idle)
-    const bool active = m0 < Mp;
-    const int cw0 = cg * NT * 16;                   // first column of this wave inside the block
+    const int m0 = mblk * RTW * 16;                 // first output row of this block (Mp is a multiple of 16*RTW)
+    const int cw0 = wave * CTW * 16;                // first column of this wave inside the block
     const int colbase = colblk * NW;
 
     const float2* Xp = Xt + (size_t)pencil * S * f * N;
     const float2* Ap = A + (size_t)pencil * k * fp * Mp;
     float2* Yp = Yt + (size_t)pencil * S * fo * N;
 
-    for (int q = threadIdx.x; q < N; q += blockDim.x) tws[q] = twg[q];
+    for (int q = threadIdx.x; q < N; q += 256) tws[q] = twg[q];
 
-    int oxs[NT];
+    int oxs[CTW];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) oxs[t] = (colbase + cw0 + t * 16 + l16) % N;
+    for (int c = 0; c < CTW; ++c) oxs[c] = (colbase + cw0 + c * 16 + l16) % N;
 
-    floatx4 yr[NT], yi[NT];
+    floatx4 yr[RTW][CTW], yi[RTW][CTW];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) { yr[t] = floatx4{0.f, 0.f, 0.f, 0.f}; yi[t] = yr[t]; }
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) { yr[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; yi[r][c] = yr[r][c]; }
 
     for (int ic0 = 0; ic0 < fp; ic0 += FC) {
         const int fc = min(FC, fp - ic0);           // multiple of 4
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
         if ((N & 1) == 0) {
             constexpr int HW = NW / 2;              // 16-byte units per row
 #pragma unroll 4
-            for (int e = threadIdx.x; e < fc * HW; e += blockDim.x) {
+            for (int e = threadIdx.x; e < fc * HW; e += 256) {
                 const int i = e / HW, c = (e - i * HW) * 2;
                 const int gi = ic0 + i, col = colbase + c;
                 const float mk = (gi < f && col < Ct) ? 1.f : 0.f;
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
                 *reinterpret_cast<float4*>(Xs + i * NW + c) = make_float4(v.x * mk, v.y * mk, v.z * mk, v.w * mk);
             }
         } else {
-            for (int e = threadIdx.x; e < fc * NW; e += blockDim.x) {
+            for (int e = threadIdx.x; e < fc * NW; e += 256) {
                 const int i = e / NW, c = e - i * NW;
                 const int gi = ic0 + i, col = colbase + c;
                 float2 v = make_float2(0.f, 0.f);
@@ -169,81 +171,92 @@ __global__ __launch_bounds__(768) void k_mac_mfma(const float2* __restrict__ Xt,
             }
         }
         __syncthreads();
-        if (!active) continue;
 
-        // ---- k * fc/4 matrix-core steps; step (a, j) uses A[a][ic0 + 4j + kk][m0 + l16].  The A operand of
-        // step s+4 is requested while step s computes (ring of 4), far enough ahead to cover an HBM miss.
-        const int nst = fc >> 2, ST = k * nst;
+        // ---- k * fc/4 matrix-core steps; step (a, j) uses A[a][ic0 + 4j + kk][m0 + 16r + l16] and rows
+        // 4j..4j+3 of the staged block.  The loop body is branch-free and unrolled by four so that operands
+        // are fetched ahead of use without register copies: each of four sets of A registers is reloaded for
+        // step j+4 right after step j has consumed it, and the image fragments of step j+1 are read from LDS
+        // while step j computes.  The step count is rounded up to a multiple of four; surplus steps fetch
+        // from the last valid position and multiply A by zero.
+        const int nst = fc >> 2, nst4 = (nst + 3) & ~3;
         const size_t jstride = (size_t)4 * Mp;
-        const size_t awrap = (size_t)fp * Mp - (size_t)nst * jstride;      // from the end of one a to the next
-        const float2* pp = Ap + (size_t)(ic0 + kk) * Mp + m0 + l16;        // prefetch cursor
-        int pj = 0, sp = 0;
-        float2 ring[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            ring[d] = make_float2(0.f, 0.f);
-            if (sp < ST) {
-                ring[d] = *pp;
-                pp += jstride; ++sp;
-                if (++pj == nst) { pj = 0; pp += awrap; }
-            }
-        }
-        floatx4 p1[NT], p2[NT], p3[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) { p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t]; }
         const float2* Xw = Xs + kk * NW + cw0 + l16;
-        int cj = 0, ca = 0;
-        for (int s0 = 0; s0 < ST; s0 += 4) {
+#define ZNNI_MAC_STEP(AR, XA, XB, J)                                                                      \
+    {                                                                                                     \
+        const float2* xr_ = Xw + min((J) + 1, nst - 1) * 4 * NW;                                          \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XB[c] = xr_[c * 16];                              \
+        const float mk_ = (J) < nst ? 1.f : 0.f;                                                          \
+        float ax_[RTW], ay_[RTW], as_[RTW];                                                               \
+        const float2* an_ = Aa + (size_t)min((J) + 4, nst - 1) * jstride;                                 \
+        _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                                 \
+            ax_[r] = AR[r].x * mk_; ay_[r] = AR[r].y * mk_; as_[r] = ax_[r] + ay_[r];                     \
+            AR[r] = an_[r * 16];                                                                          \
+        }                                                                                                 \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                                 \
+            const float xs_ = XA[c].x + XA[c].y;                                                          \
+            _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                             \
+                p1[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ax_[r], XA[c].x, p1[r][c], 0, 0, 0);      \
+                p2[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ay_[r], XA[c].y, p2[r][c], 0, 0, 0);      \
+                p3[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as_[r], xs_, p3[r][c], 0, 0, 0);          \
+            }                                                                                             \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0); /* keep this step's fetches inside this step */                \
+    }
+        for (int a = 0; a < k; ++a) {
+            const float2* Aa = Ap + ((size_t)a * fp + ic0 + kk) * Mp + m0 + l16;
+            floatx4 p1[RTW][CTW], p2[RTW][CTW], p3[RTW][CTW];
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                if (s0 + d < ST) {
-                    const float2 ac = ring[d];
-                    if (sp < ST) {
-                        ring[d] = *pp;
-                        pp += jstride; ++sp;
-                        if (++pj == nst) { pj = 0; pp += awrap; }
-                    }
-                    const float as = ac.x + ac.y;
-                    const float2* xr = Xw + cj * 4 * NW;
+            for (int r = 0; r < RTW; ++r)
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const float2 xv = xr[t * 16];
-                        p1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.x, xv.x, p1[t], 0, 0, 0);
-                        p2[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ac.y, xv.y, p2[t], 0, 0, 0);
-                        p3[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, xv.x + xv.y, p3[t], 0, 0, 0);
-                    }
-                    if (++cj == nst) {
-                        // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element r of lane l is row 4*(l/16)+r,
-                        // column l%16
-#pragma unroll
-                        for (int t = 0; t < NT; ++t) {
-                            const float2 T = tws[(ca * oxs[t]) % N];
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const float pr = p1[t][r] - p2[t][r];
-                                const float pi = p3[t][r] - p1[t][r] - p2[t][r];
-                                yr[t][r] += T.x * pr - T.y * pi;
-                                yi[t][r] += T.x * pi + T.y * pr;
-                            }
-                            p1[t] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[t] = p1[t]; p3[t] = p1[t];
-                        }
-                        cj = 0; ++ca;
-                    }
+                for (int c = 0; c < CTW; ++c) {
+                    p1[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[r][c] = p1[r][c]; p3[r][c] = p1[r][c];
                 }
+            float2 r0[RTW], r1[RTW], r2[RTW], r3[RTW];
+#pragma unroll
+            for (int r = 0; r < RTW; ++r) {
+                r0[r] = Aa[r * 16];
+                r1[r] = Aa[(size_t)min(1, nst - 1) * jstride + r * 16];
+                r2[r] = Aa[(size_t)min(2, nst - 1) * jstride + r * 16];
+                r3[r] = Aa[(size_t)min(3, nst - 1) * jstride + r * 16];
+            }
+            float2 xa[CTW], xb[CTW];
+#pragma unroll
+            for (int c = 0; c < CTW; ++c) xa[c] = Xw[c * 16];
+            for (int j = 0; j < nst4; j += 4) {
+                ZNNI_MAC_STEP(r0, xa, xb, j)
+                ZNNI_MAC_STEP(r1, xb, xa, j + 1)
+                ZNNI_MAC_STEP(r2, xa, xb, j + 2)
+                ZNNI_MAC_STEP(r3, xb, xa, j + 3)
+            }
+#undef ZNNI_MAC_STEP
+            // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element e of lane l is row 4*(l/16)+e, column l%16
+#pragma unroll
+            for (int c = 0; c < CTW; ++c) {
+                const float2 T = tws[(a * oxs[c]) % N];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float pr = p1[r][c][e] - p2[r][c][e];
+                        const float pi = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
+                        yr[r][c][e] += T.x * pr - T.y * pi;
+                        yi[r][c][e] += T.x * pi + T.y * pr;
+                    }
             }
         }
     }
-    if (!active) return;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int col = colbase + cw0 + t * 16 + l16;
+    for (int c = 0; c < CTW; ++c) {
+        const int col = colbase + cw0 + c * 16 + l16;
         if (col >= Ct) continue;
         const int s = col / N, ox = col - s * N;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = m0 + 4 * kk + r;
-            if (row < fo) Yp[(size_t)(s * fo + row) * N + ox] = make_float2(yr[t][r], yi[t][r]);
-        }
+        for (int r = 0; r < RTW; ++r)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = m0 + r * 16 + 4 * kk + e;
+                if (row < fo) Yp[(size_t)(s * fo + row) * N + ox] = make_float2(yr[r][c][e], yi[r][c][e]);
+            }
     }
 }
 
@@ -265,28 +278,27 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
     return ZNNI_OK;
 }
 
-// Tiling of the matrix-core kernel for a layer shape (host only).
+// Tiling of the matrix-core kernel for a layer shape (host only): wave tile RTW x CTW, row padding Mp.
 void plan_mac(LayerPlan* L)
 {
+    const int rt = (L->fo + 15) / 16;                   // 16-row tiles needed
+    const int nmblk = (rt + 4) / 5;                     // at most 5 row tiles per wave
+    const int RTW = (rt + nmblk - 1) / nmblk;
+    L->mac_RTW = RTW;
+    L->mac_nmblk = nmblk;
+    L->Mp = nmblk * RTW * 16;
     const int Ct = L->S * L->N;
-    static const int cand[6][2] = {{5, 2}, {4, 2}, {5, 1}, {4, 1}, {2, 1}, {1, 1}};   // (NT, CG), widest first
-    int best = 0;
-    long best_waste = -1;
-    for (int c = 0; c < 6; ++c) {
-        const int NW = 16 * cand[c][0] * cand[c][1];
-        const long waste = (long)((Ct + NW - 1) / NW) * NW - Ct;
-        if (best_waste < 0 || waste < best_waste) { best = c; best_waste = waste; }
+    // two column tiles per wave when the row count leaves room for the accumulators and no column is wasted
+    int CTW = 1;
+    if (RTW <= 3) {
+        const long w1 = (long)((Ct + 63) / 64) * 64, w2 = (long)((Ct + 127) / 128) * 128;
+        if (w2 <= w1) CTW = 2;
     }
-    L->mac_NT = cand[best][0];
-    L->mac_CG = cand[best][1];
-    const int NW = 16 * L->mac_NT * L->mac_CG;
+    L->mac_CTW = CTW;
+    const int NW = 64 * CTW;
     L->mac_ncolblk = (Ct + NW - 1) / NW;
-    const int rt = L->Mp / 16;
-    const int rgmax = 12 / L->mac_CG;
-    L->mac_RG = rt < rgmax ? rt : rgmax;
-    L->mac_nmblk = (rt + L->mac_RG - 1) / L->mac_RG;
-    // image-spectrum block kept in LDS: at most ~64 KB so two workgroups share a CU
-    int FC = (64 * 1024) / (NW * (int)sizeof(float2));
+    // image-spectrum block kept in LDS: at most ~32 KB so that several workgroups share a CU
+    int FC = (32 * 1024) / (NW * (int)sizeof(float2));
     FC &= ~3;
     if (FC < 4) FC = 4;
     if (FC > L->fp) FC = L->fp;
@@ -294,19 +306,19 @@ void plan_mac(LayerPlan* L)
     L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)FC * NW);
 }
 
-template <int NT, int CG>
-static znni_status launch_mac_nt(const LayerPlan& L, hipStream_t st)
+template <int RTW, int CTW>
+static znni_status launch_mac_t(const LayerPlan& L, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma<NT, CG>;
+    const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
     if (L.mac_lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.mac_lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.zc * L.N;
     const int per_pencil = L.mac_ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma<NT, CG><<<dim3((unsigned)blocks), dim3(64 * L.mac_RG * CG), L.mac_lds, st>>>(
-        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_RG,
-        L.mac_ncolblk, L.mac_nmblk, npencils);
+    k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), L.mac_lds, st>>>(
+        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_ncolblk, L.mac_nmblk,
+        npencils);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
@@ -319,14 +331,17 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
-    switch (L.mac_NT * 10 + L.mac_CG) {
-        case 52: return launch_mac_nt<5, 2>(L, st);
-        case 42: return launch_mac_nt<4, 2>(L, st);
-        case 51: return launch_mac_nt<5, 1>(L, st);
-        case 41: return launch_mac_nt<4, 1>(L, st);
-        case 21: return launch_mac_nt<2, 1>(L, st);
-        default: return launch_mac_nt<1, 1>(L, st);
+    switch (L.mac_RTW * 10 + L.mac_CTW) {
+        case 11: return launch_mac_t<1, 1>(L, st);
+        case 12: return launch_mac_t<1, 2>(L, st);
+        case 21: return launch_mac_t<2, 1>(L, st);
+        case 22: return launch_mac_t<2, 2>(L, st);
+        case 31: return launch_mac_t<3, 1>(L, st);
+        case 32: return launch_mac_t<3, 2>(L, st);
+        case 41: return launch_mac_t<4, 1>(L, st);
+        case 51: return launch_mac_t<5, 1>(L, st);
     }
+    return ZNNI_ERR_SHAPE;
 }
 
 }  // namespace znni

@@ -21,9 +21,9 @@ struct LayerPlan {
     int nimgo;    // S * fo
     int TL;       // lines per tile in the transform passes
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
-    int Mp;       // fo rounded up to a multiple of 16 (matrix-core tile rows)
+    int Mp;       // fo rounded up to whole row blocks of the matrix-core kernel (a multiple of 16)
     // tiling of the matrix-core multiply-accumulate (see mac.hip)
-    int mac_NT, mac_CG, mac_RG, mac_FC, mac_ncolblk, mac_nmblk;
+    int mac_RTW, mac_CTW, mac_FC, mac_ncolblk, mac_nmblk;
     size_t mac_lds;
     FftPlan fft;
     // workspace carving (device pointers)
