@@ -62,6 +62,12 @@ __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A,
     A[((size_t)oz * N + oy) * per + idx] = cscale(acc, scale);
 }
 
+__global__ void k_zero(float2* p, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = make_float2(0.f, 0.f);
+}
+
 // Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
 // a diagnostic path (flag ZNNI_MAC_REFERENCE) the matrix-core kernel can be compared with.
 __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
@@ -99,7 +105,7 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 // blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
 // row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
 // so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
-template <int RTW, int CTW>
+template <int RTW, int CTW, bool TAIL>
 __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
                                                   int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
@@ -108,7 +114,7 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
     extern __shared__ float2 lds[];
     constexpr int NW = 64 * CTW;
     float2* tws = lds;              // [N]
-    float2* Xs = lds + N;           // [FC][NW]
+    float2* Xs = lds + N;           // [FC + pad][NW]; pad rows are read ahead (4) or, zeroed, by surplus steps (16)
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int per_pencil = ncolblk * nmblk;
@@ -170,27 +176,29 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
                 Xs[i * NW + c] = v;
             }
         }
+        if (TAIL)       // surplus steps multiply these rows by zero; keep them finite
+            for (int e = threadIdx.x; e < 16 * NW; e += 256) Xs[fc * NW + e] = make_float2(0.f, 0.f);
         __syncthreads();
 
         // ---- k * fc/4 matrix-core steps; step (a, j) uses A[a][ic0 + 4j + kk][m0 + 16r + l16] and rows
-        // 4j..4j+3 of the staged block.  The loop body is branch-free and unrolled by four so that operands
-        // are fetched ahead of use without register copies: each of four sets of A registers is reloaded for
-        // step j+4 right after step j has consumed it, and the image fragments of step j+1 are read from LDS
-        // while step j computes.  The step count is rounded up to a multiple of four; surplus steps fetch
-        // from the last valid position and multiply A by zero.
-        const int nst = fc >> 2, nst4 = (nst + 3) & ~3;
+        // 4j..4j+3 of the staged block.  Steps run in groups of four.  At the top of a group the A operands of
+        // the NEXT group (which may belong to the next a) are requested into a second register set, so they
+        // have four steps of matrix-core work to arrive; the image fragments of step j+1 are read from LDS
+        // while step j computes.  Addresses only ever advance by constants; the last group of an a may hold
+        // surplus steps (fc/4 not a multiple of four), whose A values are real but multiplied by zero, and
+        // the request issued by the very last group reads the padding that follows A in the workspace.
+        const int nst = fc >> 2, ngr = (nst + 3) >> 2;
         const size_t jstride = (size_t)4 * Mp;
         const float2* Xw = Xs + kk * NW + cw0 + l16;
-#define ZNNI_MAC_STEP(AR, XA, XB, J)                                                                      \
+#define ZNNI_MAC_STEP(AR, XA, XB, MK)                                                                     \
     {                                                                                                     \
-        const float2* xr_ = Xw + min((J) + 1, nst - 1) * 4 * NW;                                          \
-        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XB[c] = xr_[c * 16];                              \
-        const float mk_ = (J) < nst ? 1.f : 0.f;                                                          \
+        xr += 4 * NW;                                                                                     \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XB[c] = xr[c * 16];                               \
         float ax_[RTW], ay_[RTW], as_[RTW];                                                               \
-        const float2* an_ = Aa + (size_t)min((J) + 4, nst - 1) * jstride;                                 \
         _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                                 \
-            ax_[r] = AR[r].x * mk_; ay_[r] = AR[r].y * mk_; as_[r] = ax_[r] + ay_[r];                     \
-            AR[r] = an_[r * 16];                                                                          \
+            ax_[r] = TAIL ? AR[r].x * (MK) : AR[r].x;                                                     \
+            ay_[r] = TAIL ? AR[r].y * (MK) : AR[r].y;                                                     \
+            as_[r] = ax_[r] + ay_[r];                                                                     \
         }                                                                                                 \
         _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                                 \
             const float xs_ = XA[c].x + XA[c].y;                                                          \
@@ -200,8 +208,16 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
                 p3[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as_[r], xs_, p3[r][c], 0, 0, 0);          \
             }                                                                                             \
         }                                                                                                 \
-        __builtin_amdgcn_sched_barrier(0); /* keep this step's fetches inside this step */                \
+        __builtin_amdgcn_sched_barrier(0); /* keep this step's LDS reads inside this step */              \
     }
+        float2 cur[4][RTW], nxt[4][RTW];
+        {
+            const float2* a0p = Ap + ((size_t)ic0 + kk) * Mp + m0 + l16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < RTW; ++r) cur[q][r] = a0p[(size_t)q * jstride + r * 16];
+        }
         for (int a = 0; a < k; ++a) {
             const float2* Aa = Ap + ((size_t)a * fp + ic0 + kk) * Mp + m0 + l16;
             floatx4 p1[RTW][CTW], p2[RTW][CTW], p3[RTW][CTW];
@@ -211,22 +227,29 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
                 for (int c = 0; c < CTW; ++c) {
                     p1[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[r][c] = p1[r][c]; p3[r][c] = p1[r][c];
                 }
-            float2 r0[RTW], r1[RTW], r2[RTW], r3[RTW];
-#pragma unroll
-            for (int r = 0; r < RTW; ++r) {
-                r0[r] = Aa[r * 16];
-                r1[r] = Aa[(size_t)min(1, nst - 1) * jstride + r * 16];
-                r2[r] = Aa[(size_t)min(2, nst - 1) * jstride + r * 16];
-                r3[r] = Aa[(size_t)min(3, nst - 1) * jstride + r * 16];
-            }
             float2 xa[CTW], xb[CTW];
+            const float2* xr = Xw;
 #pragma unroll
-            for (int c = 0; c < CTW; ++c) xa[c] = Xw[c * 16];
-            for (int j = 0; j < nst4; j += 4) {
-                ZNNI_MAC_STEP(r0, xa, xb, j)
-                ZNNI_MAC_STEP(r1, xb, xa, j + 1)
-                ZNNI_MAC_STEP(r2, xa, xb, j + 2)
-                ZNNI_MAC_STEP(r3, xb, xa, j + 3)
+            for (int c = 0; c < CTW; ++c) xa[c] = xr[c * 16];
+            for (int g = 0; g < ngr; ++g) {
+                // next group: four steps further in this a, or the first four steps of the next a
+                const float2* an = (g + 1 < ngr) ? Aa + (size_t)(g + 1) * 4 * jstride : Aa + (size_t)fp * Mp;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < RTW; ++r) nxt[q][r] = an[(size_t)q * jstride + r * 16];
+                __builtin_amdgcn_sched_barrier(0);      // requests go out before the group's arithmetic
+                const int jb = 4 * g;
+                const float m1 = jb + 1 < nst ? 1.f : 0.f, m2 = jb + 2 < nst ? 1.f : 0.f,
+                            m3 = jb + 3 < nst ? 1.f : 0.f;
+                ZNNI_MAC_STEP(cur[0], xa, xb, 1.f)
+                ZNNI_MAC_STEP(cur[1], xb, xa, m1)
+                ZNNI_MAC_STEP(cur[2], xa, xb, m2)
+                ZNNI_MAC_STEP(cur[3], xb, xa, m3)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < RTW; ++r) cur[q][r] = nxt[q][r];
             }
 #undef ZNNI_MAC_STEP
             // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element e of lane l is row 4*(l/16)+e, column l%16
@@ -275,6 +298,10 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
     const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
     k_kprep_y<<<dim3((per + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, L.k, per, scale);
     ZNNI_LAUNCH_CHECK();
+    // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
+    const size_t pad = (size_t)(L.fp + 32) * L.Mp;
+    k_zero<<<dim3((unsigned)((pad + 255) / 256)), dim3(256), 0, st>>>(L.A + (size_t)L.zc * L.N * per, pad);
+    ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
@@ -303,24 +330,31 @@ void plan_mac(LayerPlan* L)
     if (FC < 4) FC = 4;
     if (FC > L->fp) FC = L->fp;
     L->mac_FC = FC;
-    L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)FC * NW);
+    L->mac_tail = ((FC >> 2) & 3) != 0 || (((L->fp % FC) >> 2) & 3) != 0;
+    L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)(FC + (L->mac_tail ? 16 : 4)) * NW);
 }
 
-template <int RTW, int CTW>
-static znni_status launch_mac_t(const LayerPlan& L, hipStream_t st)
+template <int RTW, int CTW, bool TAIL>
+static znni_status launch_mac_tt(const LayerPlan& L, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
+    const void* fn = (const void*)k_mac_mfma<RTW, CTW, TAIL>;
     if (L.mac_lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.mac_lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.zc * L.N;
     const int per_pencil = L.mac_ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), L.mac_lds, st>>>(
+    k_mac_mfma<RTW, CTW, TAIL><<<dim3((unsigned)blocks), dim3(256), L.mac_lds, st>>>(
         L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_ncolblk, L.mac_nmblk,
         npencils);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
+}
+
+template <int RTW, int CTW>
+static znni_status launch_mac_t(const LayerPlan& L, hipStream_t st)
+{
+    return L.mac_tail ? launch_mac_tt<RTW, CTW, true>(L, st) : launch_mac_tt<RTW, CTW, false>(L, st);
 }
 
 znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)

@@ -25,6 +25,7 @@ struct LayerPlan {
     // tiling of the matrix-core multiply-accumulate (see mac.hip)
     int mac_RTW, mac_CTW, mac_FC, mac_ncolblk, mac_nmblk;
     size_t mac_lds;
+    bool mac_tail;     // some chunk's step count is not a multiple of four
     FftPlan fft;
     // workspace carving (device pointers)
     float2* tw;   // [N] exp(-2 pi i q / N)
