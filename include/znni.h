@@ -112,6 +112,13 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
                                     unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
                                     float* stage_ms);
 
+/*
+ * Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte
+ * aligned device pointers) done by one simple kernel on `stream`.  Hardware counters that report HBM traffic are
+ * calibrated against this kernel, whose traffic is known exactly: `bytes` read and `bytes` written.
+ */
+znni_status znni_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,7 @@ RELU = 1
 MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
-           "znni_conv3d_fft", "znni_conv3d_fft_profile")
+           "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_copy_probe")
 
 _lib = None
 
@@ -47,6 +47,8 @@ def lib():
         L.znni_conv3d_fft_profile.restype = i
         L.znni_conv3d_fft_profile.argtypes = [i, i, i, i, i, vp, vp, vp, vp, u, vp, sz, vp,
                                               ctypes.POINTER(ctypes.c_float)]
+        L.znni_copy_probe.restype = i
+        L.znni_copy_probe.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -124,3 +126,13 @@ def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=N
                                          _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
                                          st.cuda_stream, ms))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}
+
+
+def znni_copy_probe(dst, src, stream=None):
+    """Plain device copy src -> dst (same-size contiguous CUDA tensors); used to calibrate traffic counters."""
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    st = stream if stream is not None else torch.cuda.current_stream(src.device)
+    _check(lib().znni_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st.cuda_stream))
+    return dst

@@ -134,6 +134,12 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     return ZNNI_OK;
 }
 
+__global__ void k_copy_probe(float4* __restrict__ dst, const float4* __restrict__ src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace znni
 
 using namespace znni;
@@ -200,6 +206,19 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k, const fl
             if (hipEventElapsedTime(&stage_ms[s], ev[s], ev[s + 1]) != hipSuccess) rc = ZNNI_ERR_HIP;
     for (int e = 0; e < made; ++e) (void)hipEventDestroy(ev[e]);
     return rc;
+}
+
+znni_status znni_copy_probe(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src) return ZNNI_ERR_NULL;
+    if (bytes == 0 || (bytes & 15u)) return ZNNI_ERR_SHAPE;
+    if (((uintptr_t)dst | (uintptr_t)src) & 15u) return ZNNI_ERR_ALIGN;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    k_copy_probe<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>((float4*)dst, (const float4*)src, n16);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
 }
 
 }  // extern "C"

@@ -92,3 +92,5 @@ def test_layer_call_validates_before_any_gpu_work():
     ms = (ctypes.c_float * 8)()
     assert L.znni_conv3d_fft_profile(1, 1, 1, 8, 9, p, p, None, p, 0, ws, big, None, ms) == -2
     assert L.znni_conv3d_fft_profile(1, 1, 1, 8, 3, p, p, None, p, 0, ws, big, None, None) == -1
+    assert L.znni_copy_probe(None, p, 64, None) == -1 and L.znni_copy_probe(p, p, 0, None) == -2
+    assert L.znni_copy_probe(p, p, 24, None) == -2 and L.znni_copy_probe(p + 8, p, 64, None) == -7

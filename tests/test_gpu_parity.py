@@ -178,3 +178,11 @@ def test_relu_flag_and_null_bias(oracle):
     assert torch.equal(act, torch.clamp_min(pre, 0))
     tb = torch.from_numpy(b).to(lin.device)
     assert torch.allclose(pre, lin + tb[None, :, None, None, None], atol=1e-6)
+
+
+def test_copy_probe_copies():
+    src = torch.arange(1 << 20, dtype=torch.float32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    B.znni_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
