@@ -49,17 +49,35 @@ __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, 
 }
 
 // A[oz][oy][a][i<fp][j<Mp] = scale * sum_b A1[oz][b][a][i][j] exp(-2 pi i oy b / N)
-// (fp, Mp: f and fo rounded up to the matrix-core tile, 4 and 16; the padding holds zeros).
+// (fp, Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
+// One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once and the twiddle
+// index advances by b per oy, so the kernel is bound by its 8-byte stores.
+constexpr int KPREP_OY = 8;
 __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
                           int N, int k, int per, float scale)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j)
-    const int oy = blockIdx.y, oz = blockIdx.z;
+    const int oy0 = blockIdx.y * KPREP_OY, oz = blockIdx.z;
     if (idx >= per) return;
     const float2* a1 = A1 + (size_t)oz * k * per + idx;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int b = 0; b < k; ++b) acc = cadd(acc, cmul(a1[(size_t)b * per], tw[(oy * b) % N]));
-    A[((size_t)oz * N + oy) * per + idx] = cscale(acc, scale);
+    float2 acc[KPREP_OY];
+#pragma unroll
+    for (int o = 0; o < KPREP_OY; ++o) acc[o] = make_float2(0.f, 0.f);
+    for (int b = 0; b < k; ++b) {
+        const float2 v = a1[(size_t)b * per];
+        int q = (int)(((long long)oy0 * b) % N);
+        const int step = b % N;
+#pragma unroll
+        for (int o = 0; o < KPREP_OY; ++o) {
+            acc[o] = cadd(acc[o], cmul(v, tw[q]));
+            q += step;
+            if (q >= N) q -= N;
+        }
+    }
+    float2* d = A + ((size_t)oz * N + oy0) * per + idx;
+#pragma unroll
+    for (int o = 0; o < KPREP_OY; ++o)
+        if (oy0 + o < N) d[(size_t)o * per] = cscale(acc[o], scale);
 }
 
 __global__ void k_zero(float2* p, size_t count)
@@ -296,7 +314,8 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
                                                                     L.Mp);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
-    k_kprep_y<<<dim3((per + 255) / 256, L.N, L.zc), dim3(256), 0, st>>>(L.A1, L.A, L.tw, L.N, L.k, per, scale);
+    k_kprep_y<<<dim3((per + 255) / 256, (L.N + KPREP_OY - 1) / KPREP_OY, L.zc), dim3(256), 0, st>>>(
+        L.A1, L.A, L.tw, L.N, L.k, per, scale);
     ZNNI_LAUNCH_CHECK();
     // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
     const size_t pad = (size_t)(L.fp + 32) * L.Mp;

@@ -113,24 +113,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
                 v[m] = make_float2(ra[ec] * (me * ma), rb[ec] * (me * mb));
             }
         } else if constexpr (KIND == P_INV_Z) {
-            // lines yo0+2*la (A) and yo0+2*la+1 (B) of one (imgo, xo): Z = A + iB extended by Hermitian
-            // symmetry, conjugated for the inverse-by-forward route
-            const int yo0 = tile * 32, xo = mid;
-            const int ya = yo0 + 2 * la;
-            const float ma = ya < no ? 1.f : 0.f, mb = ya + 1 < no ? 1.f : 0.f;
-            const float2* pa = (const float2*)a.src + (((size_t)img * no + xo) * no + min(ya, no - 1)) * a.ldz;
-            const float2* pb = (const float2*)a.src + (((size_t)img * no + xo) * no + min(ya + 1, no - 1)) * a.ldz;
-#pragma unroll
-            for (int m = 0; m < R1; ++m) {
-                const int e = ja + R2 * m;
-                const bool direct = e < zc;
-                const int ee = direct ? e : N - e;
-                const float sg = direct ? 1.f : -1.f;                    // mirrored half: conjugate
-                float2 A = pa[ee], B = pb[ee];
-                A = make_float2(A.x * ma, A.y * (ma * sg));
-                B = make_float2(B.x * mb, B.y * (mb * sg));
-                v[m] = cconj(cadd(A, mul_pi(B)));
-            }
+            // filled below, from LDS
         } else {
             const float ml = la < nvalid ? 1.f : 0.f;
             const float2* ls = src + (size_t)min(la, nvalid - 1) * lpitch;
@@ -143,7 +126,44 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             }
         }
     }
-    __syncthreads();                          // twiddle table is in LDS
+    if constexpr (KIND == P_INV_Z) {
+        // The 32 lines yo0.. of one (imgo, xo) are read from HBM once, as they lie (zc values each), into LDS.
+        // Thread (ja, la) then assembles Z = A + iB for lines A = yo0+2*la, B = A+1, extended to all N bins by
+        // Hermitian symmetry and conjugated for the inverse-by-forward route.
+        constexpr int ZC = N / 2 + 1;
+        const int yo0 = tile * 32, xo = mid;
+        const int rows = min(32, no - yo0);
+        const float2* chunk = (const float2*)a.src + (((size_t)img * no + xo) * no + yo0) * a.ldz;
+        constexpr int ITER = (32 * ZC + NTH - 1) / NTH;
+        float2 raw[ITER];
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {       // all requests first ...
+            const int e = min(t + it * NTH, 32 * ZC - 1);
+            const int r = e / ZC, o = e - r * ZC;
+            raw[it] = chunk[(size_t)min(r, rows - 1) * a.ldz + o];
+        }
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {       // ... then the LDS stores
+            const int e = t + it * NTH;
+            const float mk = e / ZC < rows ? 1.f : 0.f;
+            if (e < 32 * ZC) buf[e] = make_float2(raw[it].x * mk, raw[it].y * mk);
+        }
+        __syncthreads();
+        if (in_a) {
+            const float2* ra = buf + (2 * la) * ZC;
+            const float2* rb = ra + ZC;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const int e = ja + R2 * m;
+                const bool direct = e < ZC;
+                const int ee = direct ? e : N - e;
+                float2 A = ra[ee], B = rb[ee];
+                if (!direct) { A = cconj(A); B = cconj(B); }
+                v[m] = cconj(cadd(A, mul_pi(B)));
+            }
+        }
+    }
+    __syncthreads();                          // twiddle table is in LDS; inverse z: raw lines fully consumed
     if (in_a) TS::step_a(v, la, ja, tws, buf);
     __syncthreads();
 
