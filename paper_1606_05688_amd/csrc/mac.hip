@@ -7,20 +7,22 @@
 // instead of N*N*zc); the third is evaluated where it is consumed, inside the multiply-accumulate
 //
 //     Yt[s][j](ox,oy,oz) = sum_i  Wt[j][i](ox,oy,oz) * Xt[s][i](ox,oy,oz),
-//     Wt[j][i](ox,oy,oz) = sum_{a<k} A[oz][oy][a][i][j] * exp(-2 pi i a ox / N)
+//     Wt[j][i](ox,oy,oz) = sum_{a<k} A[oz][oy](a,i,j) * exp(-2 pi i a ox / N)
 //
 // which is the second stage of Algorithm 3 (multiply the f image spectra by the f kernel spectra of output
 // image j, accumulate over the f products) without a stored kernel spectrum.  The 1/N^3 of the unnormalised
 // transforms is folded into A.
 //
-// For one (oz,oy) pencil the two sums commute:
+// For one (oz,oy) pencil this is one dense complex matrix product
 //
-//     Yt[j][col] = sum_a T[a*ox(col)] * P_a[j][col],     P_a = A_a (Mp x fp)  *  X (fp x columns)
+//     Yt[j][col] = sum_{(i,a)} A(a,i,j) * ( T[a*ox(col)] * X[i][col] ),     T[q] = exp(-2 pi i q / N),
 //
-// with col = s*N + ox running over all images of the batch: k dense complex matrix products per pencil whose
-// left operand does not depend on the column.  That is a contraction, so it runs on the matrix cores
-// (v_mfma_f32_16x16x4_f32), each complex product done as three real ones:
-//     P1 = Ar Xr, P2 = Ai Xi, P3 = (Ar+Ai)(Xr+Xi);  Re = P1 - P2, Im = P3 - P1 - P2.
+// with col = s*N + ox running over all images of the batch and the contraction index running over the f*k
+// (input image, tap) pairs: the left operand does not depend on the column, the right operand is the image
+// spectrum times a twiddle that depends on the tap and the column only.  That is a contraction, so it runs on
+// the matrix cores (v_mfma_f32_16x16x4_f32), each complex product done as three real ones:
+//     P1 = Ar Br, P2 = Ai Bi, P3 = (Ar+Ai)(Br+Bi);  Re = P1 - P2, Im = P3 - P1 - P2.
+// A is stored in the order the contraction walks it: [oz][oy][i/4][a][i%4][j<Mp].
 #include "znni_internal.h"
 
 namespace znni {
@@ -48,15 +50,15 @@ __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, 
     A1[(size_t)oz * per + idx] = acc;
 }
 
-// A[oz][oy][a][i<fp][j<Mp] = scale * sum_b A1[oz][b][a][i][j] exp(-2 pi i oy b / N)
-// (fp, Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
+// A[oz][oy][i/4][a][i%4][j<Mp] = scale * sum_b A1[oz][b][a][i][j] exp(-2 pi i oy b / N)
+// (i < fp, j < Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
 // One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once and the twiddle
 // index advances by b per oy, so the kernel is bound by its 8-byte stores.
 constexpr int KPREP_OY = 8;
 __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
-                          int N, int k, int per, float scale)
+                          int N, int k, int fp, int Mp, int per, float scale)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j)
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j) as laid out in A1
     const int oy0 = blockIdx.y * KPREP_OY, oz = blockIdx.z;
     if (idx >= per) return;
     const float2* a1 = A1 + (size_t)oz * k * per + idx;
@@ -74,7 +76,8 @@ __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A,
             if (q >= N) q -= N;
         }
     }
-    float2* d = A + ((size_t)oz * N + oy0) * per + idx;
+    const int j = idx % Mp, i = (idx / Mp) % fp, a = idx / (Mp * fp);
+    float2* d = A + ((size_t)oz * N + oy0) * per + (size_t)(((i >> 2) * k + a) * 4 + (i & 3)) * Mp + j;
 #pragma unroll
     for (int o = 0; o < KPREP_OY; ++o)
         if (oy0 + o < N) d[(size_t)o * per] = cscale(acc[o], scale);
@@ -102,7 +105,7 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
                 for (int i = 0; i < f; ++i) {
                     float2 W = make_float2(0.f, 0.f);
                     for (int a = 0; a < k; ++a)
-                        W = cadd(W, cmul(Ap[(size_t)(a * fp + i) * Mp + j], tw[(a * ox) % N]));
+                        W = cadd(W, cmul(Ap[(size_t)(((i >> 2) * k + a) * 4 + (i & 3)) * Mp + j], tw[(a * ox) % N]));
                     acc = cadd(acc, cmul(W, Xp[(size_t)(s * f + i) * N + ox]));
                 }
                 Yp[(size_t)(s * fo + j) * N + ox] = acc;
@@ -120,19 +123,26 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 // matrix-core operand layout (lane l supplies A[row l%16][k-index l/16]); the four waves of a workgroup read
 // the same A values, which the vector L1 serves.
 //
+// The contraction is a flat sequence of steps s = (i/4)*k + a, four contraction indices (input images) per
+// step.  Plain vector instructions do not overlap with matrix instructions on this hardware to any useful
+// degree, so the loop is built to need few of them: A addresses advance by a constant, A registers are
+// reloaded in two alternating sets of four steps (no copies), the right operand of step s+1 (image fragment
+// times twiddle, and their sum for the three-product scheme) is prepared during step s, and the combination
+// of the three partial products happens once, after the last step.
+//
 // blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
 // row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
 // so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
-template <int RTW, int CTW, bool TAIL>
-__global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
+template <int RTW, int CTW>
+__global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
                                                   int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
-                                                  int ncolblk, int nmblk, int npencils)
+                                                  int col0, int ncolblk, int nmblk, int npencils)
 {
     extern __shared__ float2 lds[];
     constexpr int NW = 64 * CTW;
     float2* tws = lds;              // [N]
-    float2* Xs = lds + N;           // [FC + pad][NW]; pad rows are read ahead (4) or, zeroed, by surplus steps (16)
+    float2* Xs = lds + N;           // [FC][NW]
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int per_pencil = ncolblk * nmblk;
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
     const int Ct = S * N;                           // columns of the pencil
     const int m0 = mblk * RTW * 16;                 // first output row of this block (Mp is a multiple of 16*RTW)
     const int cw0 = wave * CTW * 16;                // first column of this wave inside the block
-    const int colbase = colblk * NW;
+    const int colbase = col0 + colblk * NW;
 
     const float2* Xp = Xt + (size_t)pencil * S * f * N;
     const float2* Ap = A + (size_t)pencil * k * fp * Mp;
@@ -158,11 +168,13 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
 #pragma unroll
     for (int c = 0; c < CTW; ++c) oxs[c] = (colbase + cw0 + c * 16 + l16) % N;
 
-    floatx4 yr[RTW][CTW], yi[RTW][CTW];
+    floatx4 p1[RTW][CTW], p2[RTW][CTW], p3[RTW][CTW];
 #pragma unroll
     for (int r = 0; r < RTW; ++r)
 #pragma unroll
-        for (int c = 0; c < CTW; ++c) { yr[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; yi[r][c] = yr[r][c]; }
+        for (int c = 0; c < CTW; ++c) {
+            p1[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[r][c] = p1[r][c]; p3[r][c] = p1[r][c];
+        }
 
     for (int ic0 = 0; ic0 < fp; ic0 += FC) {
         const int fc = min(FC, fp - ic0);           // multiple of 4
@@ -194,109 +206,115 @@ __global__ __launch_bounds__(256) void k_mac_mfma(const float2* __restrict__ Xt,
                 Xs[i * NW + c] = v;
             }
         }
-        if (TAIL)       // surplus steps multiply these rows by zero; keep them finite
-            for (int e = threadIdx.x; e < 16 * NW; e += 256) Xs[fc * NW + e] = make_float2(0.f, 0.f);
         __syncthreads();
 
-        // ---- k * fc/4 matrix-core steps; step (a, j) uses A[a][ic0 + 4j + kk][m0 + 16r + l16] and rows
-        // 4j..4j+3 of the staged block.  Steps run in groups of four.  At the top of a group the A operands of
-        // the NEXT group (which may belong to the next a) are requested into a second register set, so they
-        // have four steps of matrix-core work to arrive; the image fragments of step j+1 are read from LDS
-        // while step j computes.  Addresses only ever advance by constants; the last group of an a may hold
-        // surplus steps (fc/4 not a multiple of four), whose A values are real but multiplied by zero, and
-        // the request issued by the very last group reads the padding that follows A in the workspace.
-        const int nst = fc >> 2, ngr = (nst + 3) >> 2;
+        // ---- ST = (fc/4)*k steps.  Step s uses A[ic0/4*k + s][kk][m0 + 16r + l16], rows 4*(s/k)..+3 of the
+        // staged block and the twiddle of tap a = s % k.
+        const int ST = (fc >> 2) * k;
         const size_t jstride = (size_t)4 * Mp;
+        const float2* Ab = Ap + ((size_t)(ic0 >> 2) * k * 4 + kk) * Mp + m0 + l16;
         const float2* Xw = Xs + kk * NW + cw0 + l16;
-#define ZNNI_MAC_STEP(AR, XA, XB, MK)                                                                     \
+
+        // right-operand pipeline state: (i4n, an) = block row and tap of the step being prepared
+        int i4n = 0, an = 0;
+        int tix[CTW];
+        float2 bn[CTW];             // prepared right operand
+        float bsn[CTW];             // its real + imaginary part
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) tix[c] = 0;
+
+        // prepare the operand of the step (i4n, an) into bn/bsn, then advance the state by one step
+#define ZNNI_MAC_PREP()                                                                                   \
     {                                                                                                     \
-        xr += 4 * NW;                                                                                     \
-        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XB[c] = xr[c * 16];                               \
+        const float2* xr_ = Xw + i4n * 4 * NW;                                                            \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                                 \
+            const float2 x_ = xr_[c * 16];                                                                \
+            const float2 t_ = tws[tix[c]];                                                                \
+            bn[c] = make_float2(x_.x * t_.x - x_.y * t_.y, x_.x * t_.y + x_.y * t_.x);                    \
+            bsn[c] = bn[c].x + bn[c].y;                                                                   \
+        }                                                                                                 \
+        const bool wrap_ = (an + 1 == k);                                                                 \
+        an = wrap_ ? 0 : an + 1;                                                                          \
+        i4n = wrap_ ? min(i4n + 1, (fc >> 2) - 1) : i4n;                                                  \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                                 \
+            int t_ = tix[c] + oxs[c];                                                                     \
+            t_ = t_ >= N ? t_ - N : t_;                                                                   \
+            tix[c] = wrap_ ? 0 : t_;                                                                      \
+        }                                                                                                 \
+    }
+        // one step: consume AR (A operand registers of this step) and the prepared right operand, prepare the
+        // next right operand.  MK: 1 for real steps, 0 for the surplus steps of a masked group.
+#define ZNNI_MAC_STEP(AR, MASKED, MK)                                                                     \
+    {                                                                                                     \
+        float2 b_[CTW]; float bs_[CTW];                                                                   \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) { b_[c] = bn[c]; bs_[c] = bsn[c]; }               \
         float ax_[RTW], ay_[RTW], as_[RTW];                                                               \
         _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                                 \
-            ax_[r] = TAIL ? AR[r].x * (MK) : AR[r].x;                                                     \
-            ay_[r] = TAIL ? AR[r].y * (MK) : AR[r].y;                                                     \
+            ax_[r] = MASKED ? AR[r].x * (MK) : AR[r].x;                                                   \
+            ay_[r] = MASKED ? AR[r].y * (MK) : AR[r].y;                                                   \
             as_[r] = ax_[r] + ay_[r];                                                                     \
         }                                                                                                 \
+        ZNNI_MAC_PREP()                                                                                   \
         _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                                 \
-            const float xs_ = XA[c].x + XA[c].y;                                                          \
             _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                             \
-                p1[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ax_[r], XA[c].x, p1[r][c], 0, 0, 0);      \
-                p2[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ay_[r], XA[c].y, p2[r][c], 0, 0, 0);      \
-                p3[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as_[r], xs_, p3[r][c], 0, 0, 0);          \
+                p1[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ax_[r], b_[c].x, p1[r][c], 0, 0, 0);      \
+                p2[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ay_[r], b_[c].y, p2[r][c], 0, 0, 0);      \
+                p3[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as_[r], bs_[c], p3[r][c], 0, 0, 0);       \
             }                                                                                             \
         }                                                                                                 \
-        __builtin_amdgcn_sched_barrier(0); /* keep this step's LDS reads inside this step */              \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
     }
-        float2 cur[4][RTW], nxt[4][RTW];
-        {
-            const float2* a0p = Ap + ((size_t)ic0 + kk) * Mp + m0 + l16;
+        // a group of four steps starting at step S0: request the A operands of the following group into NXT
+        // (they get four steps to arrive), then run the four steps on CUR
+#define ZNNI_MAC_GROUP(CUR, NXT, S0, MASKED)                                                              \
+    {                                                                                                     \
+        const float2* an_ = Ab + (size_t)((S0) + 4) * jstride;                                            \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                     \
+            _Pragma("unroll") for (int r = 0; r < RTW; ++r) NXT[q][r] = an_[(size_t)q * jstride + r * 16];\
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        ZNNI_MAC_STEP(CUR[0], MASKED, 1.f)                                                                \
+        ZNNI_MAC_STEP(CUR[1], MASKED, ((S0) + 1 < ST ? 1.f : 0.f))                                        \
+        ZNNI_MAC_STEP(CUR[2], MASKED, ((S0) + 2 < ST ? 1.f : 0.f))                                        \
+        ZNNI_MAC_STEP(CUR[3], MASKED, ((S0) + 3 < ST ? 1.f : 0.f))                                        \
+    }
+        float2 ga[4][RTW], gb[4][RTW];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int r = 0; r < RTW; ++r) cur[q][r] = a0p[(size_t)q * jstride + r * 16];
+            for (int r = 0; r < RTW; ++r) ga[q][r] = Ab[(size_t)q * jstride + r * 16];
+        ZNNI_MAC_PREP()                             // operand of step 0
+        int s = 0;
+        for (; s + 8 <= ST; s += 8) {
+            ZNNI_MAC_GROUP(ga, gb, s, false)
+            ZNNI_MAC_GROUP(gb, ga, s + 4, false)
         }
-        for (int a = 0; a < k; ++a) {
-            const float2* Aa = Ap + ((size_t)a * fp + ic0 + kk) * Mp + m0 + l16;
-            floatx4 p1[RTW][CTW], p2[RTW][CTW], p3[RTW][CTW];
-#pragma unroll
-            for (int r = 0; r < RTW; ++r)
-#pragma unroll
-                for (int c = 0; c < CTW; ++c) {
-                    p1[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[r][c] = p1[r][c]; p3[r][c] = p1[r][c];
-                }
-            float2 xa[CTW], xb[CTW];
-            const float2* xr = Xw;
-#pragma unroll
-            for (int c = 0; c < CTW; ++c) xa[c] = xr[c * 16];
-            for (int g = 0; g < ngr; ++g) {
-                // next group: four steps further in this a, or the first four steps of the next a
-                const float2* an = (g + 1 < ngr) ? Aa + (size_t)(g + 1) * 4 * jstride : Aa + (size_t)fp * Mp;
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int r = 0; r < RTW; ++r) nxt[q][r] = an[(size_t)q * jstride + r * 16];
-                __builtin_amdgcn_sched_barrier(0);      // requests go out before the group's arithmetic
-                const int jb = 4 * g;
-                const float m1 = jb + 1 < nst ? 1.f : 0.f, m2 = jb + 2 < nst ? 1.f : 0.f,
-                            m3 = jb + 3 < nst ? 1.f : 0.f;
-                ZNNI_MAC_STEP(cur[0], xa, xb, 1.f)
-                ZNNI_MAC_STEP(cur[1], xb, xa, m1)
-                ZNNI_MAC_STEP(cur[2], xa, xb, m2)
-                ZNNI_MAC_STEP(cur[3], xb, xa, m3)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int r = 0; r < RTW; ++r) cur[q][r] = nxt[q][r];
-            }
+        // 0..7 steps left.  Requests past the last step read the following pencil or the zeroed padding
+        // behind A; surplus steps of a masked group multiply such values by zero.
+        if (ST - s >= 4) {
+            ZNNI_MAC_GROUP(ga, gb, s, false)
+            s += 4;
+            if (s < ST) ZNNI_MAC_GROUP(gb, ga, s, true)
+        } else if (s < ST) {
+            ZNNI_MAC_GROUP(ga, gb, s, true)
+        }
+#undef ZNNI_MAC_GROUP
 #undef ZNNI_MAC_STEP
-            // Yt += T[a*ox] * (P1-P2, P3-P1-P2); accumulator element e of lane l is row 4*(l/16)+e, column l%16
-#pragma unroll
-            for (int c = 0; c < CTW; ++c) {
-                const float2 T = tws[(a * oxs[c]) % N];
-#pragma unroll
-                for (int r = 0; r < RTW; ++r)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float pr = p1[r][c][e] - p2[r][c][e];
-                        const float pi = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
-                        yr[r][c][e] += T.x * pr - T.y * pi;
-                        yi[r][c][e] += T.x * pi + T.y * pr;
-                    }
-            }
-        }
+#undef ZNNI_MAC_PREP
     }
+    // accumulator element e of lane l is row 4*(l/16)+e, column l%16
 #pragma unroll
     for (int c = 0; c < CTW; ++c) {
         const int col = colbase + cw0 + c * 16 + l16;
         if (col >= Ct) continue;
-        const int s = col / N, ox = col - s * N;
+        const int sI = col / N, ox = col - sI * N;
 #pragma unroll
         for (int r = 0; r < RTW; ++r)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int row = m0 + r * 16 + 4 * kk + e;
-                if (row < fo) Yp[(size_t)(s * fo + row) * N + ox] = make_float2(yr[r][c][e], yi[r][c][e]);
+                const float re = p1[r][c][e] - p2[r][c][e];
+                const float im = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
+                if (row < fo) Yp[(size_t)(sI * fo + row) * N + ox] = make_float2(re, im);
             }
     }
 }
@@ -315,7 +333,7 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
     k_kprep_y<<<dim3((per + 255) / 256, (L.N + KPREP_OY - 1) / KPREP_OY, L.zc), dim3(256), 0, st>>>(
-        L.A1, L.A, L.tw, L.N, L.k, per, scale);
+        L.A1, L.A, L.tw, L.N, L.k, L.fp, L.Mp, per, scale);
     ZNNI_LAUNCH_CHECK();
     // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
     const size_t pad = (size_t)(L.fp + 32) * L.Mp;
@@ -324,7 +342,8 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
     return ZNNI_OK;
 }
 
-// Tiling of the matrix-core kernel for a layer shape (host only): wave tile RTW x CTW, row padding Mp.
+// Tiling of the matrix-core kernel for a layer shape (host only): rows per wave RTW, row padding Mp, and the
+// columns cut into blocks of 128 (two column tiles per wave) with a 64-wide remainder where that wastes less.
 void plan_mac(LayerPlan* L)
 {
     const int rt = (L->fo + 15) / 16;                   // 16-row tiles needed
@@ -334,46 +353,38 @@ void plan_mac(LayerPlan* L)
     L->mac_nmblk = nmblk;
     L->Mp = nmblk * RTW * 16;
     const int Ct = L->S * L->N;
-    // two column tiles per wave when the row count leaves room for the accumulators and no column is wasted
-    int CTW = 1;
-    if (RTW <= 3) {
-        const long w1 = (long)((Ct + 63) / 64) * 64, w2 = (long)((Ct + 127) / 128) * 128;
-        if (w2 <= w1) CTW = 2;
+    L->mac_nseg = 0;
+    int col = 0;
+    if (RTW <= 3 && Ct >= 128) {                        // room for 2 x RTW accumulator tiles per wave
+        L->mac_seg[L->mac_nseg++] = MacSegment{2, Ct / 128, 0};
+        col = (Ct / 128) * 128;
     }
-    L->mac_CTW = CTW;
-    const int NW = 64 * CTW;
-    L->mac_ncolblk = (Ct + NW - 1) / NW;
-    // image-spectrum block kept in LDS: at most ~32 KB so that several workgroups share a CU
-    int FC = (32 * 1024) / (NW * (int)sizeof(float2));
+    if (col < Ct) L->mac_seg[L->mac_nseg++] = MacSegment{1, (Ct - col + 63) / 64, col};
+    // image-spectrum block kept in LDS: about 48 KB at most, so that three workgroups share a CU
+    const int nwmax = 64 * L->mac_seg[0].CTW;
+    int FC = (48 * 1024) / (nwmax * (int)sizeof(float2));
     FC &= ~3;
     if (FC < 4) FC = 4;
     if (FC > L->fp) FC = L->fp;
     L->mac_FC = FC;
-    L->mac_tail = ((FC >> 2) & 3) != 0 || (((L->fp % FC) >> 2) & 3) != 0;
-    L->mac_lds = sizeof(float2) * ((size_t)L->N + (size_t)(FC + (L->mac_tail ? 16 : 4)) * NW);
-}
-
-template <int RTW, int CTW, bool TAIL>
-static znni_status launch_mac_tt(const LayerPlan& L, hipStream_t st)
-{
-    const void* fn = (const void*)k_mac_mfma<RTW, CTW, TAIL>;
-    if (L.mac_lds > 48 * 1024 &&
-        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.mac_lds) != hipSuccess)
-        return ZNNI_ERR_HIP;
-    const int npencils = L.zc * L.N;
-    const int per_pencil = L.mac_ncolblk * L.mac_nmblk;
-    const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma<RTW, CTW, TAIL><<<dim3((unsigned)blocks), dim3(256), L.mac_lds, st>>>(
-        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, L.mac_ncolblk, L.mac_nmblk,
-        npencils);
-    ZNNI_LAUNCH_CHECK();
-    return ZNNI_OK;
 }
 
 template <int RTW, int CTW>
-static znni_status launch_mac_t(const LayerPlan& L, hipStream_t st)
+static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
 {
-    return L.mac_tail ? launch_mac_tt<RTW, CTW, true>(L, st) : launch_mac_tt<RTW, CTW, false>(L, st);
+    const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
+    const size_t lds = sizeof(float2) * ((size_t)L.N + (size_t)L.mac_FC * 64 * CTW);
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return ZNNI_ERR_HIP;
+    const int npencils = L.zc * L.N;
+    const int per_pencil = sg.ncolblk * L.mac_nmblk;
+    const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
+    k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
+        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+        L.mac_nmblk, npencils);
+    ZNNI_LAUNCH_CHECK();
+    return ZNNI_OK;
 }
 
 znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
@@ -384,17 +395,22 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
-    switch (L.mac_RTW * 10 + L.mac_CTW) {
-        case 11: return launch_mac_t<1, 1>(L, st);
-        case 12: return launch_mac_t<1, 2>(L, st);
-        case 21: return launch_mac_t<2, 1>(L, st);
-        case 22: return launch_mac_t<2, 2>(L, st);
-        case 31: return launch_mac_t<3, 1>(L, st);
-        case 32: return launch_mac_t<3, 2>(L, st);
-        case 41: return launch_mac_t<4, 1>(L, st);
-        case 51: return launch_mac_t<5, 1>(L, st);
+    for (int g = 0; g < L.mac_nseg; ++g) {
+        const MacSegment& sg = L.mac_seg[g];
+        znni_status rc = ZNNI_ERR_SHAPE;
+        switch (L.mac_RTW * 10 + sg.CTW) {
+            case 11: rc = launch_mac_t<1, 1>(L, sg, st); break;
+            case 12: rc = launch_mac_t<1, 2>(L, sg, st); break;
+            case 21: rc = launch_mac_t<2, 1>(L, sg, st); break;
+            case 22: rc = launch_mac_t<2, 2>(L, sg, st); break;
+            case 31: rc = launch_mac_t<3, 1>(L, sg, st); break;
+            case 32: rc = launch_mac_t<3, 2>(L, sg, st); break;
+            case 41: rc = launch_mac_t<4, 1>(L, sg, st); break;
+            case 51: rc = launch_mac_t<5, 1>(L, sg, st); break;
+        }
+        if (rc) return rc;
     }
-    return ZNNI_ERR_SHAPE;
+    return ZNNI_OK;
 }
 
 }  // namespace znni

@@ -8,6 +8,12 @@
 
 namespace znni {
 
+// A run of column blocks of the multiply-accumulate handled by one launch: CTW column tiles per wave
+// (block width 64*CTW), ncolblk blocks starting at column col0.
+struct MacSegment {
+    int CTW, ncolblk, col0;
+};
+
 // Everything one call needs: sizes, the radix schedule, and where each buffer lives in the workspace.
 // Buffers buf0/buf1 are reused in turn by the stages (X1 -> X2 -> Xt, then Yt -> Y2 -> Y1), the way the
 // paper reuses its transform scratch (Section III-D, last paragraphs).
@@ -23,14 +29,13 @@ struct LayerPlan {
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
     int Mp;       // fo rounded up to whole row blocks of the matrix-core kernel (a multiple of 16)
     // tiling of the matrix-core multiply-accumulate (see mac.hip)
-    int mac_RTW, mac_CTW, mac_FC, mac_ncolblk, mac_nmblk;
-    size_t mac_lds;
-    bool mac_tail;     // some chunk's step count is not a multiple of four
+    int mac_RTW, mac_FC, mac_nmblk, mac_nseg;
+    MacSegment mac_seg[2];
     FftPlan fft;
     // workspace carving (device pointers)
     float2* tw;   // [N] exp(-2 pi i q / N)
     float2* A1;   // [zc][k(b)][k(a)][fp][Mp]  kernel transform after the z stage
-    float2* A;    // [zc][N][k][fp][Mp]  kernel transform after the z and y stages, scaled by 1/N^3
+    float2* A;    // [zc][N][fp/4][k][4][Mp]  kernel transform after the z and y stages, scaled by 1/N^3
     float2* buf0;
     float2* buf1;
     size_t bytes; // total workspace bytes
