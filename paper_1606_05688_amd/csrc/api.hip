@@ -66,7 +66,7 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     const size_t sz_tw = NN * c;
     const size_t sz_A1 = zc * k * k * L->fp * L->Mp * c;
     // + room for the operand requests the multiply-accumulate issues one group of steps past the end
-    const size_t sz_A = zc * NN * k * L->fp * L->Mp * c + (size_t)(L->fp + 32) * L->Mp * c;
+    const size_t sz_A = zc * NN * k * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
     size_t b0 = (size_t)L->nimg * nn * zc * nn;                    // X1
     size_t t = zc * NN * L->nimg * NN; if (t > b0) b0 = t;         // Xt
     t = (size_t)L->nimgo * zc * no * NN; if (t > b0) b0 = t;       // Y2

@@ -23,11 +23,9 @@
 // the matrix cores (v_mfma_f32_16x16x4_f32), each complex product done as three real ones:
 //     P1 = Ar Br, P2 = Ai Bi, P3 = (Ar+Ai)(Br+Bi);  Re = P1 - P2, Im = P3 - P1 - P2.
 // A is stored in the order the contraction walks it: [oz][oy][i/4][a][i%4][j<Mp].
-#include "znni_internal.h"
+#include "mac_common.h"
 
 namespace znni {
-
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // A1[oz][b][a][i<fp][j<Mp] = sum_c w[j][i][a][b][c] exp(-2 pi i oz c / N); zero where i >= f or j >= fo.
 // (j fastest, so the y stage below reads and writes contiguous runs.)
@@ -113,26 +111,18 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
     }
 }
 
-// Matrix-core multiply-accumulate.
+// Matrix-core multiply-accumulate for any number of taps k (work split: see mac_common.h).
 //
-// One workgroup = 4 waves = one pencil x one block of NW = 64*CTW columns x one block of 16*RTW output rows.
-// Four waves per workgroup put exactly one wave on each of the CU's four SIMDs, which keeps the four matrix
-// cores evenly loaded however many workgroups share the CU.  Wave w owns the RTW x CTW tiles (16x16 each) of
-// all RTW row tiles in its own 16*CTW columns.  The fp x NW block of image spectra stays in LDS for the whole
-// call (in chunks of FC input images if it does not fit); A is streamed from global memory straight into the
-// matrix-core operand layout (lane l supplies A[row l%16][k-index l/16]); the four waves of a workgroup read
-// the same A values, which the vector L1 serves.
+// The fp x NW block of image spectra stays in LDS for the whole call (in chunks of FC input images if it does
+// not fit); A is streamed from global memory straight into the matrix-core operand layout (lane l supplies
+// A[row l%16][k-index l/16]); the four waves of a workgroup read the same A values, which the vector L1 serves.
 //
 // The contraction is a flat sequence of steps s = (i/4)*k + a, four contraction indices (input images) per
-// step.  Plain vector instructions do not overlap with matrix instructions on this hardware to any useful
-// degree, so the loop is built to need few of them: A addresses advance by a constant, A registers are
-// reloaded in two alternating sets of four steps (no copies), the right operand of step s+1 (image fragment
-// times twiddle, and their sum for the three-product scheme) is prepared during step s, and the combination
-// of the three partial products happens once, after the last step.
-//
-// blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
-// row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
-// so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
+// step.  On this hardware every instruction a wave issues costs matrix-core time (vector and matrix
+// instructions do not overlap), so the loop is built to need few of them: A addresses advance by a constant,
+// A registers are reloaded in two alternating sets of four steps (no copies), the right operand of step s+1
+// (image fragment times twiddle, and their sum for the three-product scheme) is prepared during step s, and
+// the three partial products are combined once, after the last step.
 template <int RTW, int CTW>
 __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
@@ -144,23 +134,10 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
     float2* tws = lds;              // [N]
     float2* Xs = lds + N;           // [FC][NW]
 
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int per_pencil = ncolblk * nmblk;
-    const int pencil = (slot / per_pencil) * 8 + xcd;
-    if (pencil >= npencils) return;
-    const int sub = slot % per_pencil;
-    const int colblk = sub % ncolblk, mblk = sub / ncolblk;
-
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int l16 = lane & 15, kk = lane >> 4;
-    const int Ct = S * N;                           // columns of the pencil
-    const int m0 = mblk * RTW * 16;                 // first output row of this block (Mp is a multiple of 16*RTW)
-    const int cw0 = wave * CTW * 16;                // first column of this wave inside the block
-    const int colbase = col0 + colblk * NW;
-
-    const float2* Xp = Xt + (size_t)pencil * S * f * N;
-    const float2* Ap = A + (size_t)pencil * k * fp * Mp;
-    float2* Yp = Yt + (size_t)pencil * S * fo * N;
+    MacWork w;
+    if (!mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, k, fp, Mp, col0, ncolblk, nmblk, npencils)) return;
+    const int l16 = w.l16, kk = w.kk, m0 = w.m0, cw0 = w.cw0, colbase = w.colbase;
+    const float2* Ap = w.Ap;
 
     for (int q = threadIdx.x; q < N; q += 256) tws[q] = twg[q];
 
@@ -179,33 +156,7 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
     for (int ic0 = 0; ic0 < fp; ic0 += FC) {
         const int fc = min(FC, fp - ic0);           // multiple of 4
         __syncthreads();
-        // ---- stage the fc x NW block of image spectra (rows beyond f and columns beyond Ct hold zeros).
-        // Loads come from clamped, always valid addresses and are masked by a multiply, so the compiler keeps
-        // several of them in flight instead of branching around each one.
-        if ((N & 1) == 0) {
-            constexpr int HW = NW / 2;              // 16-byte units per row
-#pragma unroll 4
-            for (int e = threadIdx.x; e < fc * HW; e += 256) {
-                const int i = e / HW, c = (e - i * HW) * 2;
-                const int gi = ic0 + i, col = colbase + c;
-                const float mk = (gi < f && col < Ct) ? 1.f : 0.f;
-                const int colc = min(col, Ct - 2), gic = min(gi, f - 1);
-                const int sI = colc / N, ox = colc - sI * N;
-                const float4 v = *reinterpret_cast<const float4*>(Xp + (size_t)(sI * f + gic) * N + ox);
-                *reinterpret_cast<float4*>(Xs + i * NW + c) = make_float4(v.x * mk, v.y * mk, v.z * mk, v.w * mk);
-            }
-        } else {
-            for (int e = threadIdx.x; e < fc * NW; e += 256) {
-                const int i = e / NW, c = e - i * NW;
-                const int gi = ic0 + i, col = colbase + c;
-                float2 v = make_float2(0.f, 0.f);
-                if (gi < f && col < Ct) {
-                    const int sI = col / N, ox = col - sI * N;
-                    v = Xp[(size_t)(sI * f + gi) * N + ox];
-                }
-                Xs[i * NW + c] = v;
-            }
-        }
+        mac_stage_x<NW>(Xs, w, ic0, fc, f, N);
         __syncthreads();
 
         // ---- ST = (fc/4)*k steps.  Step s uses A[ic0/4*k + s][kk][m0 + 16r + l16], rows 4*(s/k)..+3 of the
@@ -301,22 +252,7 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
 #undef ZNNI_MAC_STEP
 #undef ZNNI_MAC_PREP
     }
-    // accumulator element e of lane l is row 4*(l/16)+e, column l%16
-#pragma unroll
-    for (int c = 0; c < CTW; ++c) {
-        const int col = colbase + cw0 + c * 16 + l16;
-        if (col >= Ct) continue;
-        const int sI = col / N, ox = col - sI * N;
-#pragma unroll
-        for (int r = 0; r < RTW; ++r)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int row = m0 + r * 16 + 4 * kk + e;
-                const float re = p1[r][c][e] - p2[r][c][e];
-                const float im = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
-                if (row < fo) Yp[(size_t)(sI * fo + row) * N + ox] = make_float2(re, im);
-            }
-    }
+    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo);
 }
 
 #define ZNNI_LAUNCH_CHECK()                         \
@@ -336,7 +272,7 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t s
         L.A1, L.A, L.tw, L.N, L.k, L.fp, L.Mp, per, scale);
     ZNNI_LAUNCH_CHECK();
     // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
-    const size_t pad = (size_t)(L.fp + 32) * L.Mp;
+    const size_t pad = (size_t)(L.fp + 64) * L.Mp;
     k_zero<<<dim3((unsigned)((pad + 255) / 256)), dim3(256), 0, st>>>(L.A + (size_t)L.zc * L.N * per, pad);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
@@ -398,6 +334,11 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
     for (int g = 0; g < L.mac_nseg; ++g) {
         const MacSegment& sg = L.mac_seg[g];
         znni_status rc = ZNNI_ERR_SHAPE;
+        if (mac_k_available(L.k)) {
+            rc = launch_mac_k(L, sg, st);
+            if (rc) return rc;
+            continue;
+        }
         switch (L.mac_RTW * 10 + sg.CTW) {
             case 11: rc = launch_mac_t<1, 1>(L, sg, st); break;
             case 12: rc = launch_mac_t<1, 2>(L, sg, st); break;

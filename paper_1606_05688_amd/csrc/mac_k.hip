@@ -1,0 +1,159 @@
+// mac_k.hip -- matrix-core multiply-accumulate with the number of kernel taps K known at compile time.
+//
+// Same computation, data layout and work split as the general kernel in mac.hip (see there and mac_common.h):
+//
+//     Yt[j][col] = sum_{(i,a)} A(a,i,j) * ( T[a*ox(col)] * X[i][col] ).
+//
+// With K fixed, one loop iteration covers one group of four input images (i/4) and all K taps, fully unrolled:
+// the K twiddles of a lane's columns live in registers for the whole kernel, the image fragment is read from LDS
+// once per iteration instead of once per step, there is no per-step bookkeeping, and the A operands of the next
+// iteration are requested, into the other of two register sets, before the current iteration's arithmetic.
+// Every instruction a wave issues costs matrix-core time on this hardware, so per 9*K (or 18*K) matrix
+// instructions the iteration carries only the 5 vector instructions per step and column tile that form the
+// right operand (complex product and real+imaginary sum), RTW additions per step for the left operand's
+// real+imaginary sum, the A loads and one LDS read.
+#include "mac_common.h"
+
+namespace znni {
+
+template <int RTW, int CTW, int K>
+__global__ __launch_bounds__(256, (RTW * CTW * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
+void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
+                  const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int col0,
+                  int ncolblk, int nmblk, int npencils)
+{
+    extern __shared__ float2 Xs[];          // [FC][NW]
+    constexpr int NW = 64 * CTW;
+    MacWork w;
+    if (!mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, K, fp, Mp, col0, ncolblk, nmblk, npencils)) return;
+
+    // twiddles of this lane's columns, one per tap
+    float2 T[K][CTW];
+#pragma unroll
+    for (int c = 0; c < CTW; ++c) {
+        const int ox = (w.colbase + w.cw0 + c * 16 + w.l16) % N;
+        int q = 0;
+#pragma unroll
+        for (int a = 0; a < K; ++a) {
+            T[a][c] = twg[q];
+            q += ox;
+            q = q >= N ? q - N : q;
+        }
+    }
+
+    floatx4 p1[RTW][CTW], p2[RTW][CTW], p3[RTW][CTW];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) {
+            p1[r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[r][c] = p1[r][c]; p3[r][c] = p1[r][c];
+        }
+
+    const size_t jstride = (size_t)4 * Mp;              // one step (one tap of one group of four images)
+    const size_t istride = (size_t)K * jstride;         // one iteration
+
+    for (int ic0 = 0; ic0 < fp; ic0 += FC) {
+        const int fc = min(FC, fp - ic0);               // multiple of 4
+        __syncthreads();
+        mac_stage_x<NW>(Xs, w, ic0, fc, f, N);
+        __syncthreads();
+
+        const int nI = fc >> 2;
+        const float2* Ab = w.Ap + ((size_t)(ic0 >> 2) * K * 4 + w.kk) * Mp + w.m0 + w.l16;
+        const float2* Xw = Xs + w.kk * NW + w.cw0 + w.l16;
+
+        // One iteration: image rows 4*I4..4*I4+3, all K taps, A operands in CUR.  First the A operands of the
+        // following iteration are requested into NXT (past the last iteration this reads the next pencil or the
+        // zeroed padding behind A; the values are never used) and the image fragment of the following
+        // iteration is read into XN.
+#define ZNNI_MAC_ITER(CUR, NXT, XC, XN, I4)                                                               \
+    {                                                                                                     \
+        const float2* an_ = Ab + (size_t)((I4) + 1) * istride;                                            \
+        _Pragma("unroll") for (int a = 0; a < K; ++a)                                                     \
+            _Pragma("unroll") for (int r = 0; r < RTW; ++r) NXT[a][r] = an_[(size_t)a * jstride + r * 16];\
+        const float2* xr_ = Xw + min((I4) + 1, nI - 1) * 4 * NW;                                          \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XN[c] = xr_[c * 16];                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        _Pragma("unroll") for (int a = 0; a < K; ++a) {                                                   \
+            float2 b_[CTW]; float bs_[CTW];                                                               \
+            _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                             \
+                b_[c] = make_float2(XC[c].x * T[a][c].x - XC[c].y * T[a][c].y,                            \
+                                    XC[c].x * T[a][c].y + XC[c].y * T[a][c].x);                           \
+                bs_[c] = b_[c].x + b_[c].y;                                                               \
+            }                                                                                             \
+            _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                             \
+                const float as_ = CUR[a][r].x + CUR[a][r].y;                                              \
+                _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                         \
+                    p1[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(CUR[a][r].x, b_[c].x, p1[r][c], 0, 0, 0); \
+                    p2[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(CUR[a][r].y, b_[c].y, p2[r][c], 0, 0, 0); \
+                    p3[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as_, bs_[c], p3[r][c], 0, 0, 0);      \
+                }                                                                                         \
+            }                                                                                             \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+        float2 ga[K][RTW], gb[K][RTW], xa[CTW], xb[CTW];
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+            for (int r = 0; r < RTW; ++r) ga[a][r] = Ab[(size_t)a * jstride + r * 16];
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) xa[c] = Xw[c * 16];
+        int i4 = 0;
+        for (; i4 + 2 <= nI; i4 += 2) {
+            ZNNI_MAC_ITER(ga, gb, xa, xb, i4)
+            ZNNI_MAC_ITER(gb, ga, xb, xa, i4 + 1)
+        }
+        if (i4 < nI) ZNNI_MAC_ITER(ga, gb, xa, xb, i4)
+#undef ZNNI_MAC_ITER
+    }
+    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo);
+}
+
+bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
+
+template <int RTW, int CTW, int K>
+static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+{
+    const void* fn = (const void*)k_mac_mfma_k<RTW, CTW, K>;
+    const size_t lds = sizeof(float2) * (size_t)L.mac_FC * 64 * CTW;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return ZNNI_ERR_HIP;
+    const int npencils = L.zc * L.N;
+    const int per_pencil = sg.ncolblk * L.mac_nmblk;
+    const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
+    k_mac_mfma_k<RTW, CTW, K><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
+        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk, L.mac_nmblk,
+        npencils);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
+}
+
+template <int K>
+static znni_status launch_tiles(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+{
+    switch (L.mac_RTW * 10 + sg.CTW) {
+        case 11: return launch_k<1, 1, K>(L, sg, st);
+        case 12: return launch_k<1, 2, K>(L, sg, st);
+        case 21: return launch_k<2, 1, K>(L, sg, st);
+        case 22: return launch_k<2, 2, K>(L, sg, st);
+        case 31: return launch_k<3, 1, K>(L, sg, st);
+        case 32: return launch_k<3, 2, K>(L, sg, st);
+        case 41: return launch_k<4, 1, K>(L, sg, st);
+        case 51: return launch_k<5, 1, K>(L, sg, st);
+    }
+    return ZNNI_ERR_SHAPE;
+}
+
+znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+{
+    switch (L.k) {
+        case 3: return launch_tiles<3>(L, sg, st);
+        case 5: return launch_tiles<5>(L, sg, st);
+        case 7: return launch_tiles<7>(L, sg, st);
+    }
+    return ZNNI_ERR_SHAPE;
+}
+
+}  // namespace znni
