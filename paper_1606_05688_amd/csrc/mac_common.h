@@ -92,14 +92,15 @@ __device__ __forceinline__ void mac_store(const MacWork& w, const floatx4 (&p1)[
         const int col = w.colbase + w.cw0 + c * 16 + w.l16;
         if (col >= w.Ct) continue;
         const int sI = col / N, ox = col - sI * N;
+        const int row0 = w.m0 + 4 * w.kk;
+        float2* y = w.Yp + (size_t)(sI * fo + row0) * N + ox;       // rows advance by N elements
 #pragma unroll
         for (int r = 0; r < RTW; ++r)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int row = w.m0 + r * 16 + 4 * w.kk + e;
                 const float re = p1[r][c][e] - p2[r][c][e];
                 const float im = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
-                if (row < fo) w.Yp[(size_t)(sI * fo + row) * N + ox] = make_float2(re, im);
+                if (row0 + r * 16 + e < fo) y[(size_t)(r * 16 + e) * N] = make_float2(re, im);
             }
     }
 }
