@@ -36,7 +36,7 @@ extern "C" {
 typedef enum {
     ZNNI_OK = 0,
     ZNNI_ERR_NULL = -1,             /* a required pointer is NULL                                         */
-    ZNNI_ERR_SHAPE = -2,            /* S, f, f' < 1, k < 1, k > n, or a count too large for the launch grid */
+    ZNNI_ERR_SHAPE = -2,            /* S, f, f' < 1, k < 1 or k > n on an axis, or a count too large for the launch grid */
     ZNNI_ERR_UNSUPPORTED_SIZE = -3, /* no supported transform size n~ >= n                                 */
     ZNNI_ERR_WORKSPACE = -4,        /* workspace smaller than znni_conv3d_fft_workspace reports            */
     ZNNI_ERR_FLAGS = -5,            /* unknown flag bit                                                    */
@@ -111,6 +111,26 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
                                     const float* in, const float* w, const float* bias, float* out,
                                     unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
                                     float* stage_ms);
+
+/*
+ * General image and kernel sizes (Section IV: an image has size n = <nx,ny,nz>, a kernel k = <kx,ky,kz>, the
+ * output n' = n - k + 1 on every axis).  n and k are HOST pointers to three ints in the order x, y, z, where x
+ * is the slowest and z the fastest (contiguous) index of the tensors:
+ *   in   [S][f][nx][ny][nz]      w   [fo][f][kx][ky][kz]      out  [S][fo][nx-kx+1][ny-ky+1][nz-kz+1]
+ * Each axis gets its own transform size znni_fft_size(n[axis]).  Everything else (pointer ownership, flags,
+ * workspace, stream, status codes) is as for the cubic calls above, which are these calls with
+ * n = <n,n,n>, k = <k,k,k>.  ZNNI_ERR_NULL if n or k is NULL.
+ */
+znni_status znni_conv3d_fft_workspace_v(int S, int f, int fo, const int n[3], const int k[3], size_t* bytes);
+
+znni_status znni_conv3d_fft_v(int S, int f, int fo, const int n[3], const int k[3],
+                              const float* in, const float* w, const float* bias, float* out,
+                              unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
+
+znni_status znni_conv3d_fft_profile_v(int S, int f, int fo, const int n[3], const int k[3],
+                                      const float* in, const float* w, const float* bias, float* out,
+                                      unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
+                                      float* stage_ms);
 
 /*
  * Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte

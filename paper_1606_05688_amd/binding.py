@@ -16,7 +16,8 @@ RELU = 1
 MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
-           "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_copy_probe")
+           "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
+           "znni_conv3d_fft_profile_v", "znni_copy_probe")
 
 _lib = None
 
@@ -47,6 +48,14 @@ def lib():
         L.znni_conv3d_fft_profile.restype = i
         L.znni_conv3d_fft_profile.argtypes = [i, i, i, i, i, vp, vp, vp, vp, u, vp, sz, vp,
                                               ctypes.POINTER(ctypes.c_float)]
+        i3 = ctypes.POINTER(ctypes.c_int)
+        L.znni_conv3d_fft_workspace_v.restype = i
+        L.znni_conv3d_fft_workspace_v.argtypes = [i, i, i, i3, i3, ctypes.POINTER(sz)]
+        L.znni_conv3d_fft_v.restype = i
+        L.znni_conv3d_fft_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
+        L.znni_conv3d_fft_profile_v.restype = i
+        L.znni_conv3d_fft_profile_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp,
+                                                ctypes.POINTER(ctypes.c_float)]
         L.znni_copy_probe.restype = i
         L.znni_copy_probe.argtypes = [vp, vp, sz, vp]
         _lib = L
@@ -66,9 +75,20 @@ def znni_fft_size(n):
     return int(lib().znni_fft_size(int(n)))
 
 
+def _triple(v):
+    """An edge length or a sequence <x, y, z> -> ctypes int[3]."""
+    t = (int(v),) * 3 if isinstance(v, int) else tuple(int(e) for e in v)
+    assert len(t) == 3, "a size is one edge length or three (x, y, z)"
+    return (ctypes.c_int * 3)(*t)
+
+
 def znni_conv3d_fft_workspace(S, f, fo, n, k):
+    """Workspace bytes for a layer; n and k are an edge length (cubic call) or (x, y, z) triples (general call)."""
     b = ctypes.c_size_t(0)
-    _check(lib().znni_conv3d_fft_workspace(int(S), int(f), int(fo), int(n), int(k), ctypes.byref(b)))
+    if isinstance(n, int) and isinstance(k, int):
+        _check(lib().znni_conv3d_fft_workspace(int(S), int(f), int(fo), n, k, ctypes.byref(b)))
+    else:
+        _check(lib().znni_conv3d_fft_workspace_v(int(S), int(f), int(fo), _triple(n), _triple(k), ctypes.byref(b)))
     return int(b.value)
 
 
@@ -84,34 +104,43 @@ def _flags(relu, mac_reference):
 def _marshal(inp, w, bias, out, workspace):
     assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
     assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 5
-    S, f, n = inp.shape[0], inp.shape[1], inp.shape[2]
-    assert inp.shape[3] == n and inp.shape[4] == n, "cubic images only"
-    fo, k = w.shape[0], w.shape[2]
-    assert w.shape[1] == f and w.shape[3] == k and w.shape[4] == k, "kernel bank must be [f', f, k, k, k]"
+    S, f = inp.shape[0], inp.shape[1]
+    n = tuple(int(e) for e in inp.shape[2:])
+    fo = w.shape[0]
+    k = tuple(int(e) for e in w.shape[2:])
+    assert w.shape[1] == f, "kernel bank must be [f', f, kx, ky, kz]"
+    oshape = (S, fo) + tuple(a - b + 1 for a, b in zip(n, k))
     if bias is not None:
         assert bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and bias.shape == (fo,)
     if out is None:
-        out = torch.empty((S, fo, n - k + 1, n - k + 1, n - k + 1), dtype=torch.float32, device=inp.device)
+        out = torch.empty([max(e, 0) for e in oshape], dtype=torch.float32, device=inp.device)
     else:
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
-        assert tuple(out.shape) == (S, fo, n - k + 1, n - k + 1, n - k + 1)
+        assert tuple(out.shape) == oshape
     if workspace is None:
         workspace = alloc_workspace(S, f, fo, n, k, inp.device)
     assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
     return S, f, fo, n, k, out, workspace
 
 
+def _cubic(n, k):
+    return n[0] == n[1] == n[2] and k[0] == k[1] == k[2]
+
+
 def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
                     mac_reference=False):
-    """out[S,f',n-k+1,...] = act(bias + valid 3D convolution of inp[S,f,n,n,n] with w[f',f,k,k,k]).
+    """out[S,f',n-k+1 per axis] = act(bias + valid 3D convolution of inp[S,f,nx,ny,nz] with w[f',f,kx,ky,kz]).
 
+    Cubic shapes go through znni_conv3d_fft, all others through znni_conv3d_fft_v.
     Asynchronous on `stream` (a torch.cuda.Stream; default: torch's current stream)."""
     S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
-    _check(lib().znni_conv3d_fft(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
-                                 bias.data_ptr() if bias is not None else None, out.data_ptr(),
-                                 _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
-                                 st.cuda_stream))
+    tail = (inp.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, out.data_ptr(),
+            _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(), st.cuda_stream)
+    if _cubic(n, k):
+        _check(lib().znni_conv3d_fft(S, f, fo, n[0], k[0], *tail))
+    else:
+        _check(lib().znni_conv3d_fft_v(S, f, fo, _triple(n), _triple(k), *tail))
     return out
 
 
@@ -121,10 +150,12 @@ def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=N
     S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
     ms = (ctypes.c_float * len(STAGES))()
-    _check(lib().znni_conv3d_fft_profile(S, f, fo, n, k, inp.data_ptr(), w.data_ptr(),
-                                         bias.data_ptr() if bias is not None else None, out.data_ptr(),
-                                         _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
-                                         st.cuda_stream, ms))
+    tail = (inp.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, out.data_ptr(),
+            _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(), st.cuda_stream, ms)
+    if _cubic(n, k):
+        _check(lib().znni_conv3d_fft_profile(S, f, fo, n[0], k[0], *tail))
+    else:
+        _check(lib().znni_conv3d_fft_profile_v(S, f, fo, _triple(n), _triple(k), *tail))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}
 
 

@@ -40,42 +40,51 @@ static void make_fft_plan(int N, FftPlan* P)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan* L)
+znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* L)
 {
-    if (S < 1 || f < 1 || fo < 1 || n < 1 || k < 1 || k > n) return ZNNI_ERR_SHAPE;
-    const int N = fft_size(n);
-    if (N == 0) return ZNNI_ERR_UNSUPPORTED_SIZE;
+    if (!n || !k) return ZNNI_ERR_NULL;
+    if (S < 1 || f < 1 || fo < 1) return ZNNI_ERR_SHAPE;
+    for (int a = 0; a < 3; ++a)
+        if (n[a] < 1 || k[a] < 1 || k[a] > n[a]) return ZNNI_ERR_SHAPE;
+    Dims& d = L->d;
+    d.nx = n[0]; d.ny = n[1]; d.nz = n[2];
+    d.kx = k[0]; d.ky = k[1]; d.kz = k[2];
+    d.Nx = fft_size(d.nx); d.Ny = fft_size(d.ny); d.Nz = fft_size(d.nz);
+    if (d.Nx == 0 || d.Ny == 0 || d.Nz == 0) return ZNNI_ERR_UNSUPPORTED_SIZE;
     // launch-grid limits (grid y/z <= 65535) and 32-bit index products used inside the kernels
     if ((long long)S * f > 65535 || (long long)S * fo > 65535) return ZNNI_ERR_SHAPE;
-    if (((long long)fo + 15) * (f + 3) * k * k > (1ll << 30)) return ZNNI_ERR_SHAPE;
-    if ((long long)S * (f > fo ? f : fo) * n > (1ll << 30)) return ZNNI_ERR_SHAPE;
-    L->S = S; L->f = f; L->fo = fo; L->n = n; L->k = k;
-    L->N = N;
-    L->zc = N / 2 + 1;
-    L->no = n - k + 1;
-    L->ldz = (L->zc + 15) & ~15;     // Y1 rows start on 128-byte boundaries
+    const int kmax = d.kx > d.ky ? (d.kx > d.kz ? d.kx : d.kz) : (d.ky > d.kz ? d.ky : d.kz);
+    const int nmax = d.nx > d.ny ? (d.nx > d.nz ? d.nx : d.nz) : (d.ny > d.nz ? d.ny : d.nz);
+    if (((long long)fo + 15) * (f + 3) * kmax * kmax > (1ll << 30)) return ZNNI_ERR_SHAPE;
+    if ((long long)S * (f > fo ? f : fo) * nmax > (1ll << 30)) return ZNNI_ERR_SHAPE;
+    L->S = S; L->f = f; L->fo = fo;
+    d.zc = d.Nz / 2 + 1;
+    d.nox = d.nx - d.kx + 1; d.noy = d.ny - d.ky + 1; d.noz = d.nz - d.kz + 1;
+    d.ldz = (d.zc + 15) & ~15;       // Y1 rows start on 128-byte boundaries
     L->nimg = S * f;
     L->nimgo = S * fo;
-    L->TL = lines_per_tile(N);
     L->fp = (f + 3) & ~3;
     plan_mac(L);        // also sets Mp
-    make_fft_plan(N, &L->fft);
+    make_fft_plan(d.Nx, &L->fftx);
+    make_fft_plan(d.Ny, &L->ffty);
+    make_fft_plan(d.Nz, &L->fftz);
 
     const size_t c = sizeof(float2);
-    const size_t zc = L->zc, no = L->no, nn = n, NN = N;
-    const size_t sz_tw = NN * c;
-    const size_t sz_A1 = zc * k * k * L->fp * L->Mp * c;
+    const size_t zc = d.zc, nimg = L->nimg, nimgo = L->nimgo;
+    const size_t sz_A1 = zc * d.ky * d.kx * L->fp * L->Mp * c;
     // + room for the operand requests the multiply-accumulate issues one group of steps past the end
-    const size_t sz_A = zc * NN * k * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
-    size_t b0 = (size_t)L->nimg * nn * zc * nn;                    // X1
-    size_t t = zc * NN * L->nimg * NN; if (t > b0) b0 = t;         // Xt
-    t = (size_t)L->nimgo * zc * no * NN; if (t > b0) b0 = t;       // Y2
-    size_t b1 = (size_t)L->nimg * zc * NN * nn;                    // X2
-    t = zc * NN * L->nimgo * NN; if (t > b1) b1 = t;               // Yt
-    t = (size_t)L->nimgo * no * no * L->ldz; if (t > b1) b1 = t;   // Y1
+    const size_t sz_A = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
+    size_t b0 = nimg * d.nx * zc * d.ny;                             // X1
+    size_t t = zc * d.Ny * nimg * d.Nx; if (t > b0) b0 = t;          // Xt
+    t = nimgo * zc * d.nox * d.Ny; if (t > b0) b0 = t;               // Y2
+    size_t b1 = nimg * zc * d.Ny * d.nx;                             // X2
+    t = zc * d.Ny * nimgo * d.Nx; if (t > b1) b1 = t;                // Yt
+    t = nimgo * d.nox * d.noy * d.ldz; if (t > b1) b1 = t;           // Y1
     size_t off = 0;
     char* p = (char*)base;
-    L->tw = (float2*)(p + off); off += align_up(sz_tw, 256);
+    L->twx = (float2*)(p + off); off += align_up((size_t)d.Nx * c, 256);
+    L->twy = (float2*)(p + off); off += align_up((size_t)d.Ny * c, 256);
+    L->twz = (float2*)(p + off); off += align_up((size_t)d.Nz * c, 256);
     L->A1 = (float2*)(p + off); off += align_up(sz_A1, 256);
     L->A = (float2*)(p + off); off += align_up(sz_A, 256);
     L->buf0 = (float2*)(p + off); off += align_up(b0 * c, 256);
@@ -84,8 +93,9 @@ znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan*
     return ZNNI_OK;
 }
 
-static znni_status validate(int S, int f, int fo, int n, int k, const float* in, const float* w, float* out,
-                            unsigned flags, void* workspace, size_t workspace_bytes, LayerPlan* L)
+static znni_status validate(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                            const float* w, float* out, unsigned flags, void* workspace,
+                            size_t workspace_bytes, LayerPlan* L)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
     if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE)) return ZNNI_ERR_FLAGS;
@@ -146,14 +156,14 @@ using namespace znni;
 
 extern "C" {
 
-int znni_version(void) { return 100; }
+int znni_version(void) { return 200; }
 
 const char* znni_status_string(znni_status st)
 {
     switch (st) {
         case ZNNI_OK: return "ok";
         case ZNNI_ERR_NULL: return "a required pointer is NULL";
-        case ZNNI_ERR_SHAPE: return "bad layer shape (need S,f,f' >= 1 and 1 <= k <= n, counts within launch limits)";
+        case ZNNI_ERR_SHAPE: return "bad layer shape (need S,f,f' >= 1 and 1 <= k <= n on every axis, counts within launch limits)";
         case ZNNI_ERR_UNSUPPORTED_SIZE: return "no supported transform size for this image edge";
         case ZNNI_ERR_WORKSPACE: return "workspace too small";
         case ZNNI_ERR_FLAGS: return "unknown flag bit";
@@ -165,7 +175,7 @@ const char* znni_status_string(znni_status st)
 
 int znni_fft_size(int n) { return fft_size(n); }
 
-znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t* bytes)
+znni_status znni_conv3d_fft_workspace_v(int S, int f, int fo, const int n[3], const int k[3], size_t* bytes)
 {
     if (!bytes) return ZNNI_ERR_NULL;
     LayerPlan L;
@@ -175,9 +185,9 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
     return ZNNI_OK;
 }
 
-znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k, const float* in, const float* w,
-                            const float* bias, float* out, unsigned flags, void* workspace,
-                            size_t workspace_bytes, void* stream)
+znni_status znni_conv3d_fft_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                              const float* w, const float* bias, float* out, unsigned flags, void* workspace,
+                              size_t workspace_bytes, void* stream)
 {
     LayerPlan L;
     znni_status rc = validate(S, f, fo, n, k, in, w, out, flags, workspace, workspace_bytes, &L);
@@ -185,9 +195,9 @@ znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k, const float* in,
     return run(L, in, w, bias, out, flags, (hipStream_t)stream, nullptr);
 }
 
-znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k, const float* in, const float* w,
-                                    const float* bias, float* out, unsigned flags, void* workspace,
-                                    size_t workspace_bytes, void* stream, float* stage_ms)
+znni_status znni_conv3d_fft_profile_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                                      const float* w, const float* bias, float* out, unsigned flags,
+                                      void* workspace, size_t workspace_bytes, void* stream, float* stage_ms)
 {
     if (!stage_ms) return ZNNI_ERR_NULL;
     LayerPlan L;
@@ -206,6 +216,29 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k, const fl
             if (hipEventElapsedTime(&stage_ms[s], ev[s], ev[s + 1]) != hipSuccess) rc = ZNNI_ERR_HIP;
     for (int e = 0; e < made; ++e) (void)hipEventDestroy(ev[e]);
     return rc;
+}
+
+znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t* bytes)
+{
+    const int nn[3] = {n, n, n}, kk[3] = {k, k, k};
+    return znni_conv3d_fft_workspace_v(S, f, fo, nn, kk, bytes);
+}
+
+znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k, const float* in, const float* w,
+                            const float* bias, float* out, unsigned flags, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    const int nn[3] = {n, n, n}, kk[3] = {k, k, k};
+    return znni_conv3d_fft_v(S, f, fo, nn, kk, in, w, bias, out, flags, workspace, workspace_bytes, stream);
+}
+
+znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k, const float* in, const float* w,
+                                    const float* bias, float* out, unsigned flags, void* workspace,
+                                    size_t workspace_bytes, void* stream, float* stage_ms)
+{
+    const int nn[3] = {n, n, n}, kk[3] = {k, k, k};
+    return znni_conv3d_fft_profile_v(S, f, fo, nn, kk, in, w, bias, out, flags, workspace, workspace_bytes,
+                                     stream, stage_ms);
 }
 
 znni_status znni_copy_probe(void* dst, const void* src, size_t bytes, void* stream)

@@ -1,17 +1,18 @@
 // mac.hip -- pruned kernel transform and the per-bin multiply-accumulate.
 //
-// Kernel side of the layer (Sections III-A and IV-B-2).  A k^3 kernel zero-padded to N^3 is transformed
-// axis by axis, touching only lines that are not all zero: k^2 lines along z, then k*zc lines along y, then
-// N*zc lines along x.  With k small each of these one-dimensional transforms of a k-sample line is evaluated
-// directly from its k non-zero inputs.  The first two stages are stored (array A, k*N*zc values per kernel
-// instead of N*N*zc); the third is evaluated where it is consumed, inside the multiply-accumulate
+// Kernel side of the layer (Sections III-A and IV-B-2).  A kx*ky*kz kernel zero-padded to Nx*Ny*Nz is
+// transformed axis by axis, touching only lines that are not all zero: kx*ky lines along z, then kx*zc lines
+// along y, then Ny*zc lines along x (for a cubic layer: k^2, k*zc, N*zc).  With k small each of these
+// one-dimensional transforms of a k-sample line is evaluated directly from its k non-zero inputs.  The first
+// two stages are stored (array A, kx*Ny*zc values per kernel instead of Nx*Ny*zc); the third is evaluated
+// where it is consumed, inside the multiply-accumulate
 //
 //     Yt[s][j](ox,oy,oz) = sum_i  Wt[j][i](ox,oy,oz) * Xt[s][i](ox,oy,oz),
-//     Wt[j][i](ox,oy,oz) = sum_{a<k} A[oz][oy](a,i,j) * exp(-2 pi i a ox / N)
+//     Wt[j][i](ox,oy,oz) = sum_{a<kx} A[oz][oy](a,i,j) * exp(-2 pi i a ox / Nx)
 //
 // which is the second stage of Algorithm 3 (multiply the f image spectra by the f kernel spectra of output
-// image j, accumulate over the f products) without a stored kernel spectrum.  The 1/N^3 of the unnormalised
-// transforms is folded into A.
+// image j, accumulate over the f products) without a stored kernel spectrum.  The 1/(Nx Ny Nz) of the
+// unnormalised transforms is folded into A.  Below, N stands for Nx and k for kx.
 //
 // For one (oz,oy) pencil this is one dense complex matrix product
 //
@@ -27,43 +28,44 @@
 
 namespace znni {
 
-// A1[oz][b][a][i<fp][j<Mp] = sum_c w[j][i][a][b][c] exp(-2 pi i oz c / N); zero where i >= f or j >= fo.
-// (j fastest, so the y stage below reads and writes contiguous runs.)
-__global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, const float2* __restrict__ tw,
-                          int N, int f, int fo, int k, int fp, int Mp)
+// A1[oz][b<ky][a<kx][i<fp][j<Mp] = sum_{c<kz} w[j][i][a][b][c] exp(-2 pi i oz c / Nz); zero where i >= f or
+// j >= fo.  (j fastest, so the y stage below reads and writes contiguous runs.)
+__global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, const float2* __restrict__ twz,
+                          Dims d, int f, int fo, int fp, int Mp)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int oz = blockIdx.y;
-    const int per = k * k * fp * Mp;
+    const int per = d.ky * d.kx * fp * Mp;
     if (idx >= per) return;
     const int j = idx % Mp;
     const int i = (idx / Mp) % fp;
     const int ba = idx / (Mp * fp);
-    const int a = ba % k, b = ba / k;
+    const int a = ba % d.kx, b = ba / d.kx;
     float2 acc = make_float2(0.f, 0.f);
     if (i < f && j < fo) {
-        const float* wr = w + ((((size_t)j * f + i) * k + a) * k + b) * k;
-        for (int c = 0; c < k; ++c) acc = caxpy(acc, wr[c], tw[(oz * c) % N]);
+        const float* wr = w + ((((size_t)j * f + i) * d.kx + a) * d.ky + b) * d.kz;
+        for (int c = 0; c < d.kz; ++c) acc = caxpy(acc, wr[c], twz[(oz * c) % d.Nz]);
     }
     A1[(size_t)oz * per + idx] = acc;
 }
 
-// A[oz][oy][i/4][a][i%4][j<Mp] = scale * sum_b A1[oz][b][a][i][j] exp(-2 pi i oy b / N)
+// A[oz][oy<Ny][i/4][a<kx][i%4][j<Mp] = scale * sum_{b<ky} A1[oz][b][a][i][j] exp(-2 pi i oy b / Ny)
 // (i < fp, j < Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
 // One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once and the twiddle
 // index advances by b per oy, so the kernel is bound by its 8-byte stores.
 constexpr int KPREP_OY = 8;
 __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
-                          int N, int k, int fp, int Mp, int per, float scale)
+                          int N, int k, int ky, int fp, int Mp, int per, float scale)
 {
+    // N = Ny, k = kx (taps left for the multiply-accumulate), ky = taps summed here, per = kx*fp*Mp
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j) as laid out in A1
     const int oy0 = blockIdx.y * KPREP_OY, oz = blockIdx.z;
     if (idx >= per) return;
-    const float2* a1 = A1 + (size_t)oz * k * per + idx;
+    const float2* a1 = A1 + (size_t)oz * ky * per + idx;
     float2 acc[KPREP_OY];
 #pragma unroll
     for (int o = 0; o < KPREP_OY; ++o) acc[o] = make_float2(0.f, 0.f);
-    for (int b = 0; b < k; ++b) {
+    for (int b = 0; b < ky; ++b) {
         const float2 v = a1[(size_t)b * per];
         int q = (int)(((long long)oy0 * b) % N);
         const int step = b % N;
@@ -92,7 +94,8 @@ __global__ void k_zero(float2* p, size_t count)
 __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
                              const float2* __restrict__ tw, int N, int S, int f, int fo, int k, int fp, int Mp)
 {
-    const size_t pencil = (size_t)blockIdx.y * N + blockIdx.x;
+    // N = Nx, k = kx; grid = (Ny, zc)
+    const size_t pencil = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
     const float2* Xp = Xt + pencil * S * f * N;
     const float2* Ap = A + pencil * k * fp * Mp;
     float2* Yp = Yt + pencil * S * fo * N;
@@ -262,18 +265,18 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
 
 znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st)
 {
-    const int per = L.k * L.fp * L.Mp;
-    const int per1 = per * L.k;
-    k_kprep_z<<<dim3((per1 + 255) / 256, L.zc), dim3(256), 0, st>>>(w, L.A1, L.tw, L.N, L.f, L.fo, L.k, L.fp,
-                                                                    L.Mp);
+    const Dims& d = L.d;
+    const int per = d.kx * L.fp * L.Mp;
+    const int per1 = per * d.ky;
+    k_kprep_z<<<dim3((per1 + 255) / 256, d.zc), dim3(256), 0, st>>>(w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp);
     ZNNI_LAUNCH_CHECK();
-    const float scale = (float)(1.0 / ((double)L.N * L.N * L.N));
-    k_kprep_y<<<dim3((per + 255) / 256, (L.N + KPREP_OY - 1) / KPREP_OY, L.zc), dim3(256), 0, st>>>(
-        L.A1, L.A, L.tw, L.N, L.k, L.fp, L.Mp, per, scale);
+    const float scale = (float)(1.0 / ((double)d.Nx * d.Ny * d.Nz));
+    k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256), 0, st>>>(
+        L.A1, L.A, L.twy, d.Ny, d.kx, d.ky, L.fp, L.Mp, per, scale);
     ZNNI_LAUNCH_CHECK();
     // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
     const size_t pad = (size_t)(L.fp + 64) * L.Mp;
-    k_zero<<<dim3((unsigned)((pad + 255) / 256)), dim3(256), 0, st>>>(L.A + (size_t)L.zc * L.N * per, pad);
+    k_zero<<<dim3((unsigned)((pad + 255) / 256)), dim3(256), 0, st>>>(L.A + (size_t)d.zc * d.Ny * per, pad);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
@@ -288,7 +291,7 @@ void plan_mac(LayerPlan* L)
     L->mac_RTW = RTW;
     L->mac_nmblk = nmblk;
     L->Mp = nmblk * RTW * 16;
-    const int Ct = L->S * L->N;
+    const int Ct = L->S * L->d.Nx;
     L->mac_nseg = 0;
     int col = 0;
     if (RTW <= 3 && Ct >= 128) {                        // room for 2 x RTW accumulator tiles per wave
@@ -309,15 +312,15 @@ template <int RTW, int CTW>
 static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
 {
     const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
-    const size_t lds = sizeof(float2) * ((size_t)L.N + (size_t)L.mac_FC * 64 * CTW);
+    const size_t lds = sizeof(float2) * ((size_t)L.d.Nx + (size_t)L.mac_FC * 64 * CTW);
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return ZNNI_ERR_HIP;
-    const int npencils = L.zc * L.N;
+    const int npencils = L.d.zc * L.d.Ny;
     const int per_pencil = sg.ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
     k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+        L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f, L.fo, L.d.kx, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
         L.mac_nmblk, npencils);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
@@ -326,15 +329,15 @@ static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, hipStr
 znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
 {
     if (flags & ZNNI_MAC_REFERENCE) {
-        k_mac_simple<<<dim3(L.N, L.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.k,
-                                                            L.fp, L.Mp);
+        k_mac_simple<<<dim3(L.d.Ny, L.d.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f,
+                                                                 L.fo, L.d.kx, L.fp, L.Mp);
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
     for (int g = 0; g < L.mac_nseg; ++g) {
         const MacSegment& sg = L.mac_seg[g];
         znni_status rc = ZNNI_ERR_SHAPE;
-        if (mac_k_available(L.k)) {
+        if (mac_k_available(L.d.kx)) {
             rc = launch_mac_k(L, sg, st);
             if (rc) return rc;
             continue;

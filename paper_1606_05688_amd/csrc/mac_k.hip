@@ -120,12 +120,12 @@ static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, hipStream_
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return ZNNI_ERR_HIP;
-    const int npencils = L.zc * L.N;
+    const int npencils = L.d.zc * L.d.Ny;
     const int per_pencil = sg.ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
     k_mac_mfma_k<RTW, CTW, K><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.buf1, L.tw, L.N, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk, L.mac_nmblk,
-        npencils);
+        L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+        L.mac_nmblk, npencils);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
@@ -148,7 +148,7 @@ static znni_status launch_tiles(const LayerPlan& L, const MacSegment& sg, hipStr
 
 znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
 {
-    switch (L.k) {
+    switch (L.d.kx) {
         case 3: return launch_tiles<3>(L, sg, st);
         case 5: return launch_tiles<5>(L, sg, st);
         case 7: return launch_tiles<7>(L, sg, st);

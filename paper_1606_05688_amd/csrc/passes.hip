@@ -9,17 +9,18 @@
 //
 // Pruning (Section III-A): lines that are zero padding are never read or transformed (they only exist when
 // n~ > n); on the inverse side only the n' = n-k+1 valid outputs of a line are stored, so the later passes
-// run n'/n~ (y) and (n'/n~)^2 (z) of the lines.
+// run nox/Nx (y) and nox*noy/(Nx*Ny) (z) of the lines.
 //
-// Layouts (N = n~, zc = N/2+1, no = n', img = s*f + i, imgo = s*f' + j; all complex interleaved fp32):
-//   in  [img][x<n][y<n][z<n]              real
-//   X1  [img][x<n][oz<zc][y<n]            after z
-//   X2  [img][oz][oy<N][x<n]              after y
-//   Xt  [oz][oy][img][ox<N]               after x   ("pencil" order: one (oz,oy) pair holds all images)
-//   Yt  [oz][oy][imgo][ox<N]              accumulated output spectra
-//   Y2  [imgo][oz][xo<no][oy<N]           after inverse x, cropped to valid x
-//   Y1  [imgo][xo][yo<no][oz<zc (ldz)]    after inverse y, cropped to valid y
-//   out [imgo][xo][yo][zo<no]             real, after inverse z + bias + transfer function
+// Layouts (image <nx,ny,nz>, transform sizes <Nx,Ny,Nz>, zc = Nz/2+1, valid outputs <nox,noy,noz>,
+// img = s*f + i, imgo = s*f' + j; all complex interleaved fp32):
+//   in  [img][x<nx][y<ny][z<nz]             real
+//   X1  [img][x<nx][oz<zc][y<ny]            after z
+//   X2  [img][oz][oy<Ny][x<nx]              after y
+//   Xt  [oz][oy][img][ox<Nx]                after x   ("pencil" order: one (oz,oy) pair holds all images)
+//   Yt  [oz][oy][imgo][ox<Nx]               accumulated output spectra
+//   Y2  [imgo][oz][xo<nox][oy<Ny]           after inverse x, cropped to valid x
+//   Y1  [imgo][xo][yo<noy][oz<zc (ldz)]     after inverse y, cropped to valid y
+//   out [imgo][xo][yo][zo<noz]              real, after inverse z + bias + transfer function
 #include "znni_internal.h"
 
 namespace znni {
@@ -54,146 +55,151 @@ __device__ __forceinline__ Lds carve(float2* base, int N, int nlines, const floa
 
 // ---- forward, axis z: real -> complex.  Two real lines ride through one complex transform.
 __global__ void k_fwd_z(const float* __restrict__ in, float2* __restrict__ X1, const float2* __restrict__ twg,
-                        FftPlan P, int n, int zc, int TL)
+                        FftPlan P, Dims d, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N, nl = TL >> 1;
     Lds L = carve(lds, N, nl, twg);
     const int y0 = blockIdx.x * TL, x = blockIdx.y, img = blockIdx.z;
-    const int nvalid = min(TL, n - y0);
-    const float* src = in + ((size_t)(img * n + x) * n + y0) * n;
+    const int ny = d.ny, nz = d.nz, zc = d.zc;
+    const int nvalid = min(TL, ny - y0);
+    const float* src = in + (((size_t)img * d.nx + x) * ny + y0) * nz;
     for (int e = threadIdx.x; e < nl * N; e += blockDim.x) {
         const int p = e / N, z = e - p * N;
         float re = 0.f, im = 0.f;
-        if (z < n) {
-            if (2 * p < nvalid) re = src[(2 * p) * n + z];
-            if (2 * p + 1 < nvalid) im = src[(2 * p + 1) * n + z];
+        if (z < nz) {
+            if (2 * p < nvalid) re = src[(size_t)(2 * p) * nz + z];
+            if (2 * p + 1 < nvalid) im = src[(size_t)(2 * p + 1) * nz + z];
         }
         L.a[p * L.ld + z] = make_float2(re, im);
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, nl, L.ld, P);
-    float2* dst = X1 + (size_t)(img * n + x) * zc * n + y0;
+    float2* dst = X1 + ((size_t)img * d.nx + x) * zc * ny + y0;
     for (int e = threadIdx.x; e < zc * TL; e += blockDim.x) {
         const int l = e & (TL - 1), oz = e / TL;
         if (l >= nvalid) continue;
         const float2* row = r + (l >> 1) * L.ld;
         const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
         const float2 v = (l & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f) : cscale(cadd(z1, z2), 0.5f);
-        dst[(size_t)oz * n + l] = v;
+        dst[(size_t)oz * ny + l] = v;
     }
 }
 
 // ---- forward, axis y
 __global__ void k_fwd_y(const float2* __restrict__ X1, float2* __restrict__ X2, const float2* __restrict__ twg,
-                        FftPlan P, int n, int zc, int TL)
+                        FftPlan P, Dims d, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
     const int x0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
-    const int nvalid = min(TL, n - x0);
+    const int nx = d.nx, ny = d.ny, zc = d.zc;
+    const int nvalid = min(TL, nx - x0);
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, y = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid && y < n) v = X1[((size_t)(img * n + x0 + l) * zc + oz) * n + y];
+        if (l < nvalid && y < ny) v = X1[(((size_t)img * nx + x0 + l) * zc + oz) * ny + y];
         L.a[l * L.ld + y] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = X2 + ((size_t)img * zc + oz) * N * n + x0;
+    float2* dst = X2 + ((size_t)img * zc + oz) * N * nx + x0;
     for (int e = threadIdx.x; e < N * TL; e += blockDim.x) {
         const int l = e & (TL - 1), oy = e / TL;
-        if (l < nvalid) dst[(size_t)oy * n + l] = r[l * L.ld + oy];
+        if (l < nvalid) dst[(size_t)oy * nx + l] = r[l * L.ld + oy];
     }
 }
 
 // ---- forward, axis x; writes pencil order
 __global__ void k_fwd_x(const float2* __restrict__ X2, float2* __restrict__ Xt, const float2* __restrict__ twg,
-                        FftPlan P, int n, int zc, int nimg, int TL)
+                        FftPlan P, Dims d, int nimg, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
     const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
-    const int nvalid = min(TL, N - oy0);
-    const float2* src = X2 + (((size_t)img * zc + oz) * N + oy0) * n;
+    const int nx = d.nx, Ny = d.Ny, zc = d.zc;
+    const int nvalid = min(TL, Ny - oy0);
+    const float2* src = X2 + (((size_t)img * zc + oz) * Ny + oy0) * nx;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, x = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid && x < n) v = src[(size_t)l * n + x];
+        if (l < nvalid && x < nx) v = src[(size_t)l * nx + x];
         L.a[l * L.ld + x] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, ox = e - l * N;
-        if (l < nvalid) Xt[(((size_t)oz * N + oy0 + l) * nimg + img) * N + ox] = r[l * L.ld + ox];
+        if (l < nvalid) Xt[(((size_t)oz * Ny + oy0 + l) * nimg + img) * N + ox] = r[l * L.ld + ox];
     }
 }
 
-// The inverse transform of a line is conj(forward(conj(line))); the 1/N^3 factor is folded into the
+// The inverse transform of a line is conj(forward(conj(line))); the 1/(Nx Ny Nz) factor is folded into the
 // kernel spectra.
 
-// ---- inverse, axis x; keeps x in [k-1, n-1]
+// ---- inverse, axis x; keeps x in [kx-1, nx-1]
 __global__ void k_inv_x(const float2* __restrict__ Yt, float2* __restrict__ Y2, const float2* __restrict__ twg,
-                        FftPlan P, int zc, int nimgo, int no, int k, int TL)
+                        FftPlan P, Dims d, int nimgo, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
     const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
-    const int nvalid = min(TL, N - oy0);
+    const int Ny = d.Ny, zc = d.zc, nox = d.nox;
+    const int nvalid = min(TL, Ny - oy0);
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, ox = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid) v = cconj(Yt[(((size_t)oz * N + oy0 + l) * nimgo + img) * N + ox]);
+        if (l < nvalid) v = cconj(Yt[(((size_t)oz * Ny + oy0 + l) * nimgo + img) * N + ox]);
         L.a[l * L.ld + ox] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = Y2 + ((size_t)img * zc + oz) * no * N + oy0;
-    for (int e = threadIdx.x; e < no * TL; e += blockDim.x) {
+    float2* dst = Y2 + ((size_t)img * zc + oz) * nox * Ny + oy0;
+    for (int e = threadIdx.x; e < nox * TL; e += blockDim.x) {
         const int l = e & (TL - 1), xo = e / TL;
-        if (l < nvalid) dst[(size_t)xo * N + l] = cconj(r[l * L.ld + xo + k - 1]);
+        if (l < nvalid) dst[(size_t)xo * Ny + l] = cconj(r[l * L.ld + xo + d.kx - 1]);
     }
 }
 
-// ---- inverse, axis y; keeps y in [k-1, n-1]; only lines with valid x exist
+// ---- inverse, axis y; keeps y in [ky-1, ny-1]; only lines with valid x exist
 __global__ void k_inv_y(const float2* __restrict__ Y2, float2* __restrict__ Y1, const float2* __restrict__ twg,
-                        FftPlan P, int zc, int ldz, int no, int k, int TL)
+                        FftPlan P, Dims d, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
     const int oz0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
+    const int zc = d.zc, nox = d.nox, noy = d.noy, ldz = d.ldz;
     const int nvalid = min(TL, zc - oz0);
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, oy = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid) v = cconj(Y2[(((size_t)img * zc + oz0 + l) * no + xo) * N + oy]);
+        if (l < nvalid) v = cconj(Y2[(((size_t)img * zc + oz0 + l) * nox + xo) * N + oy]);
         L.a[l * L.ld + oy] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = Y1 + ((size_t)img * no + xo) * no * ldz + oz0;
-    for (int e = threadIdx.x; e < no * TL; e += blockDim.x) {
+    float2* dst = Y1 + ((size_t)img * nox + xo) * noy * ldz + oz0;
+    for (int e = threadIdx.x; e < noy * TL; e += blockDim.x) {
         const int l = e & (TL - 1), yo = e / TL;
-        if (l < nvalid) dst[(size_t)yo * ldz + l] = cconj(r[l * L.ld + yo + k - 1]);
+        if (l < nvalid) dst[(size_t)yo * ldz + l] = cconj(r[l * L.ld + yo + d.ky - 1]);
     }
 }
 
-// ---- inverse, axis z: complex -> real for two lines at once; keeps z in [k-1, n-1]; bias + transfer
+// ---- inverse, axis z: complex -> real for two lines at once; keeps z in [kz-1, nz-1]; bias + transfer
 __global__ void k_inv_z(const float2* __restrict__ Y1, float* __restrict__ out, const float* __restrict__ bias,
-                        const float2* __restrict__ twg, FftPlan P, int zc, int ldz, int fo, int no, int k,
-                        int relu, int TL)
+                        const float2* __restrict__ twg, FftPlan P, Dims d, int fo, int relu, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N, nl = TL >> 1;
     Lds L = carve(lds, N, nl, twg);
     const int yo0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
-    const int nvalid = min(TL, no - yo0);
-    const float2* src = Y1 + (((size_t)img * no + xo) * no + yo0) * ldz;
+    const int zc = d.zc, nox = d.nox, noy = d.noy, noz = d.noz, ldz = d.ldz;
+    const int nvalid = min(TL, noy - yo0);
+    const float2* src = Y1 + (((size_t)img * nox + xo) * noy + yo0) * ldz;
     for (int e = threadIdx.x; e < nl * N; e += blockDim.x) {
         const int p = e / N, o = e - p * N;
         const bool direct = o < zc;
@@ -209,14 +215,14 @@ __global__ void k_inv_z(const float2* __restrict__ Y1, float* __restrict__ out, 
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, nl, L.ld, P);
     const float bj = bias ? bias[img % fo] : 0.f;
-    float* dst = out + (((size_t)img * no + xo) * no + yo0) * no;
-    for (int e = threadIdx.x; e < TL * no; e += blockDim.x) {
-        const int l = e / no, zo = e - l * no;
+    float* dst = out + (((size_t)img * nox + xo) * noy + yo0) * noz;
+    for (int e = threadIdx.x; e < TL * noz; e += blockDim.x) {
+        const int l = e / noz, zo = e - l * noz;
         if (l >= nvalid) continue;
-        const float2 t = r[(l >> 1) * L.ld + zo + k - 1];
+        const float2 t = r[(l >> 1) * L.ld + zo + d.kz - 1];
         float v = ((l & 1) ? -t.y : t.x) + bj;
         if (relu) v = fmaxf(v, 0.f);
-        dst[(size_t)l * no + zo] = v;
+        dst[(size_t)l * noz + zo] = v;
     }
 }
 
@@ -247,86 +253,97 @@ static znni_status allow_lds(const void* fn, size_t bytes)
 
 znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
 {
-    k_twiddles<<<dim3((L.N + 255) / 256), dim3(256), 0, st>>>(L.tw, L.N);
+    const Dims& d = L.d;
+    k_twiddles<<<dim3((d.Nx + 255) / 256), dim3(256), 0, st>>>(L.twx, d.Nx);
+    ZNNI_LAUNCH_CHECK();
+    k_twiddles<<<dim3((d.Ny + 255) / 256), dim3(256), 0, st>>>(L.twy, d.Ny);
+    ZNNI_LAUNCH_CHECK();
+    k_twiddles<<<dim3((d.Nz + 255) / 256), dim3(256), 0, st>>>(L.twz, d.Nz);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_fwd_z(L, in, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL / 2);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Nz)) return launch_fast_fwd_z(L, in, st);
+    const int TL = lines_per_tile(d.Nz);
+    const size_t lds = pass_lds_bytes(d.Nz, TL / 2);
     znni_status rc = allow_lds((const void*)k_fwd_z, lds);
     if (rc) return rc;
-    dim3 grid((L.n + TL - 1) / TL, L.n, L.nimg);
-    k_fwd_z<<<grid, dim3(256), lds, st>>>(in, L.buf0, L.tw, L.fft, L.n, L.zc, TL);
+    dim3 grid((d.ny + TL - 1) / TL, d.nx, L.nimg);
+    k_fwd_z<<<grid, dim3(256), lds, st>>>(in, L.buf0, L.twz, L.fftz, d, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_fwd_y(L, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Ny)) return launch_fast_fwd_y(L, st);
+    const int TL = lines_per_tile(d.Ny);
+    const size_t lds = pass_lds_bytes(d.Ny, TL);
     znni_status rc = allow_lds((const void*)k_fwd_y, lds);
     if (rc) return rc;
-    dim3 grid((L.n + TL - 1) / TL, L.zc, L.nimg);
-    k_fwd_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.tw, L.fft, L.n, L.zc, TL);
+    dim3 grid((d.nx + TL - 1) / TL, d.zc, L.nimg);
+    k_fwd_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.twy, L.ffty, d, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_fwd_x(L, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Nx)) return launch_fast_fwd_x(L, st);
+    const int TL = lines_per_tile(d.Nx);
+    const size_t lds = pass_lds_bytes(d.Nx, TL);
     znni_status rc = allow_lds((const void*)k_fwd_x, lds);
     if (rc) return rc;
-    dim3 grid((L.N + TL - 1) / TL, L.zc, L.nimg);
-    k_fwd_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.tw, L.fft, L.n, L.zc, L.nimg, TL);
+    dim3 grid((d.Ny + TL - 1) / TL, d.zc, L.nimg);
+    k_fwd_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.twx, L.fftx, d, L.nimg, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_inv_x(L, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Nx)) return launch_fast_inv_x(L, st);
+    const int TL = lines_per_tile(d.Nx);
+    const size_t lds = pass_lds_bytes(d.Nx, TL);
     znni_status rc = allow_lds((const void*)k_inv_x, lds);
     if (rc) return rc;
-    dim3 grid((L.N + TL - 1) / TL, L.zc, L.nimgo);
-    k_inv_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.tw, L.fft, L.zc, L.nimgo, L.no, L.k, TL);
+    dim3 grid((d.Ny + TL - 1) / TL, d.zc, L.nimgo);
+    k_inv_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.twx, L.fftx, d, L.nimgo, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_inv_y(L, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Ny)) return launch_fast_inv_y(L, st);
+    const int TL = lines_per_tile(d.Ny);
+    const size_t lds = pass_lds_bytes(d.Ny, TL);
     znni_status rc = allow_lds((const void*)k_inv_y, lds);
     if (rc) return rc;
-    dim3 grid((L.zc + TL - 1) / TL, L.no, L.nimgo);
-    k_inv_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.tw, L.fft, L.zc, L.ldz, L.no, L.k, TL);
+    dim3 grid((d.zc + TL - 1) / TL, d.nox, L.nimgo);
+    k_inv_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.twy, L.ffty, d, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {
-    if (fast_pass_available(L.N)) return launch_fast_inv_z(L, bias, out, flags, st);
-    const int TL = L.TL;
-    const size_t lds = pass_lds_bytes(L.N, TL / 2);
+    const Dims& d = L.d;
+    if (fast_pass_available(d.Nz)) return launch_fast_inv_z(L, bias, out, flags, st);
+    const int TL = lines_per_tile(d.Nz);
+    const size_t lds = pass_lds_bytes(d.Nz, TL / 2);
     znni_status rc = allow_lds((const void*)k_inv_z, lds);
     if (rc) return rc;
-    dim3 grid((L.no + TL - 1) / TL, L.no, L.nimgo);
-    k_inv_z<<<grid, dim3(256), lds, st>>>(L.buf1, out, bias, L.tw, L.fft, L.zc, L.ldz, L.fo, L.no, L.k,
-                                          (flags & ZNNI_RELU) ? 1 : 0, TL);
+    dim3 grid((d.noy + TL - 1) / TL, d.nox, L.nimgo);
+    k_inv_z<<<grid, dim3(256), lds, st>>>(L.buf1, out, bias, L.twz, L.fftz, d, L.fo, (flags & ZNNI_RELU) ? 1 : 0,
+                                          TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }

@@ -22,7 +22,8 @@ struct PassArgs {
     void* dst;
     const float2* tw;      // [N]
     const float* bias;     // inv_z only
-    int n, zc, no, k, ldz, nimg, fo, relu;
+    Dims d;
+    int nimg, fo, relu;
 };
 
 template <int R1, int R2> struct TwoStep {
@@ -67,7 +68,8 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     for (int q = t; q < N; q += NTH) tws[q] = a.tw[q];
 
     const int tile = blockIdx.x, mid = blockIdx.y, img = blockIdx.z;
-    const int n = a.n, zc = a.zc, no = a.no;
+    const Dims& d = a.d;
+    const int zc = d.zc;
 
     // ---- where the 16 lines of this tile start, how far apart they are, how many exist, how long they are
     const float2* src = nullptr;      // complex passes
@@ -75,20 +77,20 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     int nvalid = 0, lin = N;
     if constexpr (KIND == P_FWD_Y) {          // tile: 16 x of one (img, oz); lines along y in X1
         const int x0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + ((size_t)(img * n + x0) * zc + oz) * n;
-        lpitch = (size_t)zc * n; nvalid = min(16, n - x0); lin = n;
+        src = (const float2*)a.src + (((size_t)img * d.nx + x0) * zc + oz) * d.ny;
+        lpitch = (size_t)zc * d.ny; nvalid = min(16, d.nx - x0); lin = d.ny;
     } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
         const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz) * N + oy0) * n;
-        lpitch = n; nvalid = min(16, N - oy0); lin = n;
+        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.nx;
+        lpitch = d.nx; nvalid = min(16, d.Ny - oy0); lin = d.nx;
     } else if constexpr (KIND == P_INV_X) {   // tile: 16 oy of one (oz, imgo); lines along ox in Yt
         const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)oz * N + oy0) * a.nimg + img) * N;
-        lpitch = (size_t)a.nimg * N; nvalid = min(16, N - oy0);
+        src = (const float2*)a.src + (((size_t)oz * d.Ny + oy0) * a.nimg + img) * N;
+        lpitch = (size_t)a.nimg * N; nvalid = min(16, d.Ny - oy0);
     } else if constexpr (KIND == P_INV_Y) {   // tile: 16 oz of one (imgo, xo); lines along oy in Y2
         const int oz0 = tile * 16, xo = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz0) * no + xo) * N;
-        lpitch = (size_t)no * N; nvalid = min(16, zc - oz0);
+        src = (const float2*)a.src + (((size_t)img * zc + oz0) * d.nox + xo) * N;
+        lpitch = (size_t)d.nox * N; nvalid = min(16, zc - oz0);
     }
 
     // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
@@ -103,13 +105,14 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             // two real lines y0+2*la, y0+2*la+1 of one (img, x) ride as real and imaginary part
             const int y0 = tile * 32, x = mid;
             const int ya = y0 + 2 * la;
-            const float ma = ya < n ? 1.f : 0.f, mb = ya + 1 < n ? 1.f : 0.f;
-            const float* ra = (const float*)a.src + ((size_t)(img * n + x) * n + min(ya, n - 1)) * n;
-            const float* rb = (const float*)a.src + ((size_t)(img * n + x) * n + min(ya + 1, n - 1)) * n;
+            const int ny = d.ny, nz = d.nz;
+            const float ma = ya < ny ? 1.f : 0.f, mb = ya + 1 < ny ? 1.f : 0.f;
+            const float* ra = (const float*)a.src + (((size_t)img * d.nx + x) * ny + min(ya, ny - 1)) * nz;
+            const float* rb = (const float*)a.src + (((size_t)img * d.nx + x) * ny + min(ya + 1, ny - 1)) * nz;
 #pragma unroll
             for (int m = 0; m < R1; ++m) {
-                const int e = ja + R2 * m, ec = min(e, n - 1);
-                const float me = e < n ? 1.f : 0.f;
+                const int e = ja + R2 * m, ec = min(e, nz - 1);
+                const float me = e < nz ? 1.f : 0.f;
                 v[m] = make_float2(ra[ec] * (me * ma), rb[ec] * (me * mb));
             }
         } else if constexpr (KIND == P_INV_Z) {
@@ -132,15 +135,15 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         // Hermitian symmetry and conjugated for the inverse-by-forward route.
         constexpr int ZC = N / 2 + 1;
         const int yo0 = tile * 32, xo = mid;
-        const int rows = min(32, no - yo0);
-        const float2* chunk = (const float2*)a.src + (((size_t)img * no + xo) * no + yo0) * a.ldz;
+        const int rows = min(32, d.noy - yo0);
+        const float2* chunk = (const float2*)a.src + (((size_t)img * d.nox + xo) * d.noy + yo0) * d.ldz;
         constexpr int ITER = (32 * ZC + NTH - 1) / NTH;
         float2 raw[ITER];
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {       // all requests first ...
             const int e = min(t + it * NTH, 32 * ZC - 1);
             const int r = e / ZC, o = e - r * ZC;
-            raw[it] = chunk[(size_t)min(r, rows - 1) * a.ldz + o];
+            raw[it] = chunk[(size_t)min(r, rows - 1) * d.ldz + o];
         }
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {       // ... then the LDS stores
@@ -175,28 +178,28 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     if constexpr (KIND == P_FWD_Y) {
         // X2[img][oz][oy][x0 + lb]
         if (q < R1 && lb < nvalid) {
-            float2* d = (float2*)a.dst + ((size_t)img * zc + mid) * N * n + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * N * d.nx + tile * 16 + lb;
 #pragma unroll
-            for (int r = 0; r < R2; ++r) d[(size_t)(q + R1 * r) * n] = u[r];
+            for (int r = 0; r < R2; ++r) o[(size_t)(q + R1 * r) * d.nx] = u[r];
         }
     } else if constexpr (KIND == P_INV_X) {
-        // Y2[imgo][oz][xo][oy0 + lb], xo = element - (k-1) in [0, no)
+        // Y2[imgo][oz][xo][oy0 + lb], xo = element - (kx-1) in [0, nox)
         if (q < R1 && lb < nvalid) {
-            float2* d = (float2*)a.dst + ((size_t)img * zc + mid) * no * N + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * d.nox * d.Ny + tile * 16 + lb;
 #pragma unroll
             for (int r = 0; r < R2; ++r) {
-                const int xo = q + R1 * r - (a.k - 1);
-                if (xo >= 0 && xo < no) d[(size_t)xo * N] = cconj(u[r]);
+                const int xo = q + R1 * r - (d.kx - 1);
+                if (xo >= 0 && xo < d.nox) o[(size_t)xo * d.Ny] = cconj(u[r]);
             }
         }
     } else if constexpr (KIND == P_INV_Y) {
         // Y1[imgo][xo][yo][oz0 + lb]
         if (q < R1 && lb < nvalid) {
-            float2* d = (float2*)a.dst + ((size_t)img * no + mid) * no * a.ldz + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * d.nox + mid) * d.noy * d.ldz + tile * 16 + lb;
 #pragma unroll
             for (int r = 0; r < R2; ++r) {
-                const int yo = q + R1 * r - (a.k - 1);
-                if (yo >= 0 && yo < no) d[(size_t)yo * a.ldz] = cconj(u[r]);
+                const int yo = q + R1 * r - (d.ky - 1);
+                if (yo >= 0 && yo < d.noy) o[(size_t)yo * d.ldz] = cconj(u[r]);
             }
         }
     } else {
@@ -211,34 +214,36 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             // Xt[oz][oy0 + l][img][ox]: whole lines, contiguous
             const int oy0 = tile * 16;
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
-                float2* d = (float2*)a.dst + (((size_t)mid * N + oy0 + l) * a.nimg + img) * N;
-                for (int e = t % 64; e < N; e += 64) d[e] = buf[l * P + e];
+                float2* o = (float2*)a.dst + (((size_t)mid * d.Ny + oy0 + l) * a.nimg + img) * N;
+                for (int e = t % 64; e < N; e += 64) o[e] = buf[l * P + e];
             }
         } else if constexpr (KIND == P_FWD_Z) {
             // untangle the two real lines and store X1[img][x][oz][y0 + ll], ll < 32 fastest across lanes
             const int y0 = tile * 32;
-            float2* d = (float2*)a.dst + (size_t)(img * n + mid) * zc * n + y0;
+            const int ny = d.ny;
+            float2* o = (float2*)a.dst + ((size_t)img * d.nx + mid) * zc * ny + y0;
             const int ll = t & 31;
-            if (y0 + ll < n) {
+            if (y0 + ll < ny) {
                 const float2* row = buf + (ll >> 1) * P;
                 for (int oz = t >> 5; oz < zc; oz += NTH / 32) {
                     const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
-                    d[(size_t)oz * n + ll] = (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
+                    o[(size_t)oz * ny + ll] = (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
                                                       : cscale(cadd(z1, z2), 0.5f);
                 }
             }
         } else {   // P_INV_Z: real part -> line 2l, minus imaginary part -> line 2l+1; crop, bias, transfer
             const int yo0 = tile * 32;
             const float bj = a.bias ? a.bias[img % a.fo] : 0.f;
-            float* d = (float*)a.dst + (((size_t)img * no + mid) * no + yo0) * no;
-            const int rows = min(32, no - yo0);
+            const int noz = d.noz;
+            float* o = (float*)a.dst + (((size_t)img * d.nox + mid) * d.noy + yo0) * noz;
+            const int rows = min(32, d.noy - yo0);
             for (int ll = t / 64; ll < rows; ll += NTH / 64) {
-                const float2* row = buf + (ll >> 1) * P + (a.k - 1);
-                for (int zo = t % 64; zo < no; zo += 64) {
+                const float2* row = buf + (ll >> 1) * P + (d.kz - 1);
+                for (int zo = t % 64; zo < noz; zo += 64) {
                     const float2 c = row[zo];
                     float v = ((ll & 1) ? -c.y : c.x) + bj;
                     if (a.relu) v = fmaxf(v, 0.f);
-                    d[(size_t)ll * no + zo] = v;
+                    o[(size_t)ll * noz + zo] = v;
                 }
             }
         }
@@ -274,45 +279,51 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
 
 bool fast_pass_available(int N) { return N == 16 || N == 64 || N == 128 || N == 256 || N == 320; }
 
-static PassArgs base_args(const LayerPlan& L, const void* src, void* dst)
+static PassArgs base_args(const LayerPlan& L, const void* src, void* dst, const float2* tw, int nimg)
 {
     PassArgs a;
-    a.src = src; a.dst = dst; a.tw = L.tw; a.bias = nullptr;
-    a.n = L.n; a.zc = L.zc; a.no = L.no; a.k = L.k; a.ldz = L.ldz; a.nimg = L.nimg; a.fo = L.fo; a.relu = 0;
+    a.src = src; a.dst = dst; a.tw = tw; a.bias = nullptr;
+    a.d = L.d; a.nimg = nimg; a.fo = L.fo; a.relu = 0;
     return a;
 }
 
 znni_status launch_fast_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 {
-    return launch_kind<P_FWD_Z>(L.N, base_args(L, in, L.buf0), dim3((L.n + 31) / 32, L.n, L.nimg), st);
+    const Dims& d = L.d;
+    return launch_kind<P_FWD_Z>(d.Nz, base_args(L, in, L.buf0, L.twz, L.nimg), dim3((d.ny + 31) / 32, d.nx, L.nimg),
+                                st);
 }
 znni_status launch_fast_fwd_y(const LayerPlan& L, hipStream_t st)
 {
-    return launch_kind<P_FWD_Y>(L.N, base_args(L, L.buf0, L.buf1), dim3((L.n + 15) / 16, L.zc, L.nimg), st);
+    const Dims& d = L.d;
+    return launch_kind<P_FWD_Y>(d.Ny, base_args(L, L.buf0, L.buf1, L.twy, L.nimg),
+                                dim3((d.nx + 15) / 16, d.zc, L.nimg), st);
 }
 znni_status launch_fast_fwd_x(const LayerPlan& L, hipStream_t st)
 {
-    return launch_kind<P_FWD_X>(L.N, base_args(L, L.buf1, L.buf0), dim3((L.N + 15) / 16, L.zc, L.nimg), st);
+    const Dims& d = L.d;
+    return launch_kind<P_FWD_X>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimg),
+                                dim3((d.Ny + 15) / 16, d.zc, L.nimg), st);
 }
 znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
 {
-    PassArgs a = base_args(L, L.buf1, L.buf0);
-    a.nimg = L.nimgo;
-    return launch_kind<P_INV_X>(L.N, a, dim3((L.N + 15) / 16, L.zc, L.nimgo), st);
+    const Dims& d = L.d;
+    return launch_kind<P_INV_X>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimgo),
+                                dim3((d.Ny + 15) / 16, d.zc, L.nimgo), st);
 }
 znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)
 {
-    PassArgs a = base_args(L, L.buf0, L.buf1);
-    a.nimg = L.nimgo;
-    return launch_kind<P_INV_Y>(L.N, a, dim3((L.zc + 15) / 16, L.no, L.nimgo), st);
+    const Dims& d = L.d;
+    return launch_kind<P_INV_Y>(d.Ny, base_args(L, L.buf0, L.buf1, L.twy, L.nimgo),
+                                dim3((d.zc + 15) / 16, d.nox, L.nimgo), st);
 }
 znni_status launch_fast_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {
-    PassArgs a = base_args(L, L.buf1, out);
-    a.nimg = L.nimgo;
+    const Dims& d = L.d;
+    PassArgs a = base_args(L, L.buf1, out, L.twz, L.nimgo);
     a.bias = bias;
     a.relu = (flags & ZNNI_RELU) ? 1 : 0;
-    return launch_kind<P_INV_Z>(L.N, a, dim3((L.no + 31) / 32, L.no, L.nimgo), st);
+    return launch_kind<P_INV_Z>(d.Nz, a, dim3((d.noy + 31) / 32, d.nox, L.nimgo), st);
 }
 
 }  // namespace znni

@@ -14,28 +14,37 @@ struct MacSegment {
     int CTW, ncolblk, col0;
 };
 
-// Everything one call needs: sizes, the radix schedule, and where each buffer lives in the workspace.
+// Sizes of one layer, per axis (Section IV: image size <nx,ny,nz>, kernel size <kx,ky,kz>, output size
+// n' = n - k + 1 per axis).  x is the slowest axis of the tensors, z the contiguous one.  Passed to kernels by value.
+struct Dims {
+    int nx, ny, nz;       // image
+    int kx, ky, kz;       // kernel
+    int Nx, Ny, Nz;       // transform sizes n~ >= n
+    int zc;               // Nz/2 + 1 bins along the halved axis
+    int nox, noy, noz;    // output n - k + 1
+    int ldz;              // row stride of Y1 (zc rounded up to a multiple of 16 complex = 128 bytes)
+};
+
+// Everything one call needs: sizes, the radix schedules, and where each buffer lives in the workspace.
 // Buffers buf0/buf1 are reused in turn by the stages (X1 -> X2 -> Xt, then Yt -> Y2 -> Y1), the way the
 // paper reuses its transform scratch (Section III-D, last paragraphs).
 struct LayerPlan {
-    int S, f, fo, n, k;
-    int N;        // transform size n~
-    int zc;       // N/2 + 1 bins along the halved axis
-    int no;       // n - k + 1
-    int ldz;      // row stride of Y1 (zc rounded up to a multiple of 16 complex = 128 bytes)
+    int S, f, fo;
+    Dims d;
     int nimg;     // S * f
     int nimgo;    // S * fo
-    int TL;       // lines per tile in the transform passes
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
     int Mp;       // fo rounded up to whole row blocks of the matrix-core kernel (a multiple of 16)
     // tiling of the matrix-core multiply-accumulate (see mac.hip)
     int mac_RTW, mac_FC, mac_nmblk, mac_nseg;
     MacSegment mac_seg[2];
-    FftPlan fft;
+    FftPlan fftx, ffty, fftz;
     // workspace carving (device pointers)
-    float2* tw;   // [N] exp(-2 pi i q / N)
-    float2* A1;   // [zc][k(b)][k(a)][fp][Mp]  kernel transform after the z stage
-    float2* A;    // [zc][N][fp/4][k][4][Mp]  kernel transform after the z and y stages, scaled by 1/N^3
+    float2* twx;  // [Nx] exp(-2 pi i q / Nx)
+    float2* twy;  // [Ny]
+    float2* twz;  // [Nz]
+    float2* A1;   // [zc][ky(b)][kx(a)][fp][Mp]      kernel transform after the z stage
+    float2* A;    // [zc][Ny][fp/4][kx][4][Mp]       after the z and y stages, scaled by 1/(Nx Ny Nz)
     float2* buf0;
     float2* buf1;
     size_t bytes; // total workspace bytes
@@ -43,7 +52,7 @@ struct LayerPlan {
 
 // Host-only: validate the shape and fill every field; pointers are offsets from `base` (may be NULL when
 // only the size is wanted).
-znni_status make_plan(int S, int f, int fo, int n, int k, void* base, LayerPlan* out);
+znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* out);
 
 int lines_per_tile(int N);
 

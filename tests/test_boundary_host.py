@@ -94,3 +94,35 @@ def test_layer_call_validates_before_any_gpu_work():
     assert L.znni_conv3d_fft_profile(1, 1, 1, 8, 3, p, p, None, p, 0, ws, big, None, None) == -1
     assert L.znni_copy_probe(None, p, 64, None) == -1 and L.znni_copy_probe(p, p, 0, None) == -2
     assert L.znni_copy_probe(p, p, 24, None) == -2 and L.znni_copy_probe(p + 8, p, 64, None) == -7
+
+
+def _i3(*v):
+    return (ctypes.c_int * 3)(*v)
+
+
+def test_general_shape_calls_validate_per_axis():
+    L = B.lib()
+    b = ctypes.c_size_t(0)
+    q = lambda n, k: L.znni_conv3d_fft_workspace_v(1, 2, 2, _i3(*n), _i3(*k), ctypes.byref(b))
+    assert q((8, 9, 10), (3, 2, 1)) == 0 and b.value > 0
+    assert q((8, 9, 10), (9, 2, 1)) == -2 and q((8, 9, 10), (3, 10, 1)) == -2 and q((8, 9, 10), (3, 2, 11)) == -2
+    assert q((8, 9, 0), (3, 2, 1)) == -2 and q((8, 9, 10), (3, 0, 1)) == -2
+    assert q((8, 1025, 10), (3, 2, 1)) == -3
+    assert L.znni_conv3d_fft_workspace_v(1, 2, 2, None, _i3(1, 1, 1), ctypes.byref(b)) == -1
+    assert L.znni_conv3d_fft_workspace_v(1, 2, 2, _i3(8, 8, 8), None, ctypes.byref(b)) == -1
+    p, ws, big = 0x1000, 0x100000, 1 << 40
+    assert L.znni_conv3d_fft_v(1, 1, 1, _i3(8, 6, 4), _i3(3, 7, 1), p, p, None, p, 0, ws, big, None) == -2
+    assert L.znni_conv3d_fft_v(1, 1, 1, None, _i3(3, 3, 1), p, p, None, p, 0, ws, big, None) == -1
+    assert L.znni_conv3d_fft_v(1, 1, 1, _i3(8, 6, 4), _i3(3, 3, 1), p, p, None, p, 0, ws, 64, None) == -4
+    ms = (ctypes.c_float * 8)()
+    assert L.znni_conv3d_fft_profile_v(1, 1, 1, _i3(8, 6, 4), _i3(3, 3, 5), p, p, None, p, 0, ws, big, None, ms) == -2
+
+
+def test_cubic_calls_are_the_general_calls_with_equal_axes():
+    for (S, f, fo, n, k) in [(1, 2, 3, 16, 3), (2, 5, 7, 33, 4)]:
+        assert B.znni_conv3d_fft_workspace(S, f, fo, n, k) == B.znni_conv3d_fft_workspace(S, f, fo, (n, n, n), (k, k, k))
+    # the workspace follows the per-axis transform sizes: doubling one image axis grows it by 1.5x to 2x
+    # (the stored kernel transforms do not grow with the x axis, the halved axis has Nz/2+1 bins)
+    a = B.znni_conv3d_fft_workspace(1, 4, 4, (32, 32, 32), (3, 3, 3))
+    for n in [(64, 32, 32), (32, 64, 32), (32, 32, 64)]:
+        assert 1.5 * a < B.znni_conv3d_fft_workspace(1, 4, 4, n, (3, 3, 3)) < 2.1 * a

@@ -79,6 +79,60 @@ def test_small_layers_full_compare(oracle, shape):
     _check_full(oracle, inp, w, None, False, f"small {shape} linear")
 
 
+def _rand_v(seed, S, f, fo, n, k):
+    r = np.random.default_rng(seed)
+    inp = r.uniform(-1, 1, (S, f) + tuple(n)).astype(np.float32)
+    w = (r.standard_normal((fo, f) + tuple(k)) * (f * k[0] * k[1] * k[2]) ** -0.5).astype(np.float32)
+    b = (r.standard_normal(fo) * np.sqrt(0.1)).astype(np.float32)
+    return inp, w, b
+
+
+# (S, f, fo, <nx,ny,nz>, <kx,ky,kz>): image and kernel sizes that differ per axis (Section IV's general
+# n = <nx,ny,nz>, k = <kx,ky,kz>), so that an axis mix-up anywhere in a pass, the kernel transform or a crop
+# window changes the result.  Covers: all three transform sizes different; in-register and generic passes mixed
+# in one layer; padded axes; tap counts with and without a specialised multiply-accumulate kernel; a kernel as
+# long as the image on one axis; flat (one-voxel-thick) images and kernels.
+ANISO = [
+    (1, 2, 3, (12, 20, 16), (3, 2, 5)),
+    (2, 3, 2, (16, 24, 40), (5, 3, 2)),       # z generic (40), x in-register (16)
+    (1, 2, 2, (64, 18, 33), (7, 4, 3)),       # x in-register; y = 18, z 33 -> 35 padded
+    (1, 4, 5, (21, 64, 17), (2, 7, 6)),       # y in-register, x 21 = 7*3, z 17 -> 18
+    (1, 1, 2, (10, 15, 128), (4, 1, 9)),      # long contiguous axis, k = 1 on y
+    (1, 2, 1, (128, 9, 14), (3, 9, 2)),       # kernel as long as the image on y: one output along y
+    (2, 2, 2, (1, 30, 30), (1, 5, 5)),        # flat image: a batch of 2D convolutions
+    (1, 3, 3, (30, 1, 25), (3, 1, 5)),
+    (1, 2, 2, (28, 36, 1), (5, 3, 1)),
+    (1, 48, 20, (16, 20, 24), (5, 3, 3)),     # many input images: several chunks / row blocks in the multiply-accumulate
+]
+
+
+@pytest.mark.parametrize("shape", ANISO, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
+def test_anisotropic_layers_full_compare(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand_v(500 + sum(n) + sum(k), S, f, fo, n, k)
+    _check_full(oracle, inp, w, b, True, f"aniso {shape}")
+    _say(f"[parity/full] aniso {shape} plain multiply-accumulate")
+    got = _run_gpu(inp, w, b, False, mac_reference=True).cpu().numpy().astype(np.float64)
+    exp = oracle.conv3d(inp, w, b, relu=False)
+    assert np.all(np.abs(got - exp) <= oracle.tolerance(inp, w)[None, :, None, None, None])
+
+
+def test_anisotropic_delta_kernel_moves_each_axis_by_its_own_offset():
+    """A one-tap kernel at (a0,b0,c0) of a <kx,ky,kz> kernel must return the image shifted by
+    (kx-1-a0, ky-1-b0, kz-1-c0): exact in fp32 up to the transform's rounding, and wrong on any axis swap."""
+    n, k, tap = (20, 16, 24), (4, 3, 5), (1, 2, 3)
+    r = np.random.default_rng(77)
+    inp = r.uniform(-1, 1, (1, 1) + n).astype(np.float32)
+    w = np.zeros((1, 1) + k, dtype=np.float32)
+    w[(0, 0) + tap] = 1.0
+    got = _run_gpu(inp, w, None, False).cpu().numpy()
+    o = [k[a] - 1 - tap[a] for a in range(3)]
+    m = [n[a] - k[a] + 1 for a in range(3)]
+    exp = inp[0, 0, o[0]:o[0] + m[0], o[1]:o[1] + m[1], o[2]:o[2] + m[2]]
+    assert got.shape == (1, 1) + tuple(m)
+    assert np.abs(got[0, 0] - exp).max() <= 1e-4
+
+
 # Transform lengths served by the two-step in-register passes (16, 64, 128, 256, 320), at the length itself
 # and just below it (zero-padded lines, ragged tiles of lines).
 TWO_STEP = [(2, 2, 3, 16, 3), (1, 2, 2, 15, 2), (1, 3, 2, 64, 5), (2, 1, 2, 61, 4), (1, 2, 1, 128, 3),
