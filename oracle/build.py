@@ -7,15 +7,15 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "znni_ref.c")
+SRCS = [os.path.join(HERE, "znni_ref.c"), os.path.join(HERE, "znni_ref_mpf.c")]
 LIB = os.path.join(HERE, "libznni_ref.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SRCS):
         return LIB
     cmd = ["gcc", "-O3", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-o", LIB, SRC]
+           "-o", LIB, *SRCS]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -33,6 +33,9 @@ def lib():
         L.znni_ref_conv3d_points_f64.argtypes = ([ctypes.c_int] * 9 + [fp, fp, fp, ip, ctypes.c_long, dp,
                                                                       ctypes.c_uint, ctypes.c_int])
         L.znni_ref_max_threads.restype = ctypes.c_int
+        for fn in (L.znni_ref_maxpool, L.znni_ref_mpf):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_int] * 8 + [fp, fp]
         _lib = L
     return _lib
 
@@ -95,6 +98,34 @@ def conv3d_points(inp, w, bias, pts, relu=False, nthreads=0):
     if rc != 0:
         raise ValueError(f"znni_ref_conv3d_points_f64 failed with status {rc}")
     return out
+
+
+def _pool(fn_name, inp, p, out_shape):
+    inp, pin = _f32(inp)
+    S, f, nx, ny, nz = inp.shape
+    px, py, pz = _triple(p)
+    if min(px, py, pz) < 1:
+        raise ValueError("pooling window must be at least 1 on every axis")
+    out = np.empty(out_shape(S, f, nx, ny, nz, px, py, pz), dtype=np.float32)
+    rc = getattr(lib(), fn_name)(S, f, nx, ny, nz, px, py, pz, pin,
+                                 out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc != 0:
+        raise ValueError(f"{fn_name} failed with status {rc}")
+    return out
+
+
+def maxpool(inp, p):
+    """Max pooling with window p (Section VI): inp [S,f,nx,ny,nz] fp32 -> fp32 [S,f,nx/px,ny/py,nz/pz]."""
+    return _pool("znni_ref_maxpool", inp, p,
+                 lambda S, f, nx, ny, nz, px, py, pz: (S, f, max(nx // px, 0), max(ny // py, 0), max(nz // pz, 0)))
+
+
+def mpf(inp, p):
+    """Max-pooling fragments with window p (Section VI): inp [S,f,nx,ny,nz] fp32 ->
+    fp32 [S*px*py*pz, f, floor(nx/px), floor(ny/py), floor(nz/pz)], fragment (ox,oy,oz) of input s at batch
+    index s*px*py*pz + (ox*py + oy)*pz + oz."""
+    return _pool("znni_ref_mpf", inp, p,
+                 lambda S, f, nx, ny, nz, px, py, pz: (S * px * py * pz, f, nx // px, ny // py, nz // pz))
 
 
 def tolerance(inp, w, rel=1e-4):
