@@ -133,6 +133,30 @@ znni_status znni_conv3d_fft_profile_v(int S, int f, int fo, const int n[3], cons
                                       float* stage_ms);
 
 /*
+ * Max-pooling fragments (Section VI, second paragraph).  For every offset o = (ox,oy,oz), 0 <= o < p, the image
+ * is max-pooled with window p = <px,py,pz> starting at o:
+ *     F[o][a][b][c] = max over the p-block of I starting at (ox + px a, oy + py b, oz + pz c),   a,b,c < m,
+ * where n + 1 must be divisible by p on every axis with p > 1, so that every fragment has size
+ * m = floor(n / p) per axis (the case the paper states).  A batch of S tuples of f images becomes a batch of
+ * S*px*py*pz tuples (the most significant dimension grows, Section VII-A):
+ *     in   [S][f][nx][ny][nz]                       device, read-only, 4-byte aligned
+ *     out  [S*px*py*pz][f][mx][my][mz]              device, written (every element);
+ *          tuple s*px*py*pz + (ox*py + oy)*pz + oz holds the fragments of offset (ox,oy,oz) of input s
+ *   n, p  HOST pointers to three ints (x, y, z; z contiguous); 1 <= p <= 4 and p <= n <= 4096 per axis
+ * Needs no workspace; asynchronous on `stream`.  ZNNI_ERR_SHAPE if the divisibility rule fails,
+ * ZNNI_ERR_UNSUPPORTED_SIZE for a window above 4.
+ */
+znni_status znni_mpf(int S, int f, const int n[3], const int p[3], const float* in, float* out, void* stream);
+
+/*
+ * Max pooling (Section VI, first paragraph): the image is cut into blocks of size p and each block is replaced by
+ * its maximum; n must be divisible by p on every axis.
+ *     in [S][f][nx][ny][nz]  ->  out [S][f][nx/px][ny/py][nz/pz]      (device pointers, 4-byte aligned)
+ * Needs no workspace; asynchronous on `stream`.
+ */
+znni_status znni_maxpool(int S, int f, const int n[3], const int p[3], const float* in, float* out, void* stream);
+
+/*
  * Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte
  * aligned device pointers) done by one simple kernel on `stream`.  Hardware counters that report HBM traffic are
  * calibrated against this kernel, whose traffic is known exactly: `bytes` read and `bytes` written.

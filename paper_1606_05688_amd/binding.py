@@ -17,7 +17,7 @@ MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_copy_probe")
+           "znni_conv3d_fft_profile_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
 
 _lib = None
 
@@ -56,6 +56,9 @@ def lib():
         L.znni_conv3d_fft_profile_v.restype = i
         L.znni_conv3d_fft_profile_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp,
                                                 ctypes.POINTER(ctypes.c_float)]
+        for fn in (L.znni_mpf, L.znni_maxpool):
+            fn.restype = i
+            fn.argtypes = [i, i, i3, i3, vp, vp, vp]
         L.znni_copy_probe.restype = i
         L.znni_copy_probe.argtypes = [vp, vp, sz, vp]
         _lib = L
@@ -157,6 +160,34 @@ def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=N
     else:
         _check(lib().znni_conv3d_fft_profile_v(S, f, fo, _triple(n), _triple(k), *tail))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}
+
+
+def _pool(fn, inp, p, oshape, out, stream):
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
+    S, f = inp.shape[0], inp.shape[1]
+    n = tuple(int(e) for e in inp.shape[2:])
+    p = tuple(int(e) for e in _triple(p))
+    shape = oshape(S, f, n, p)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=inp.device)
+    else:
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == shape
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(fn(S, f, _triple(n), _triple(p), inp.data_ptr(), out.data_ptr(), st.cuda_stream))
+    return out
+
+
+def znni_mpf(inp, p, out=None, stream=None):
+    """Max-pooling fragments with window p (edge or (px,py,pz)): [S,f,nx,ny,nz] -> [S*px*py*pz, f, n//p ...]."""
+    return _pool(lib().znni_mpf, inp, p,
+                 lambda S, f, n, p: (S * p[0] * p[1] * p[2], f) + tuple(max(a // max(b, 1), 0) for a, b in zip(n, p)),
+                 out, stream)
+
+
+def znni_maxpool(inp, p, out=None, stream=None):
+    """Max pooling with window p: [S,f,nx,ny,nz] -> [S, f, nx/px, ny/py, nz/pz]."""
+    return _pool(lib().znni_maxpool, inp, p,
+                 lambda S, f, n, p: (S, f) + tuple(max(a // max(b, 1), 0) for a, b in zip(n, p)), out, stream)
 
 
 def znni_copy_probe(dst, src, stream=None):

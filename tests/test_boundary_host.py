@@ -126,3 +126,20 @@ def test_cubic_calls_are_the_general_calls_with_equal_axes():
     a = B.znni_conv3d_fft_workspace(1, 4, 4, (32, 32, 32), (3, 3, 3))
     for n in [(64, 32, 32), (32, 64, 32), (32, 32, 64)]:
         assert 1.5 * a < B.znni_conv3d_fft_workspace(1, 4, 4, n, (3, 3, 3)) < 2.1 * a
+
+
+def test_pooling_calls_validate_before_any_gpu_work():
+    L = B.lib()
+    p = 0x1000
+    for fn in (L.znni_mpf, L.znni_maxpool):
+        assert fn(1, 1, None, _i3(2, 2, 2), p, p, None) == -1
+        assert fn(1, 1, _i3(7, 7, 7), None, p, p, None) == -1
+        assert fn(0, 1, _i3(8, 8, 8), _i3(1, 1, 1), p, p, None) == -2
+        assert fn(1, 1, _i3(8, 8, 8), _i3(1, 0, 1), p, p, None) == -2
+        assert fn(1, 1, _i3(8, 2, 8), _i3(1, 3, 1), p, p, None) == -2          # window larger than the image
+        assert fn(1, 1, _i3(8, 8, 8), _i3(1, 1, 1), None, p, None) == -1
+        assert fn(1, 1, _i3(8, 8, 8), _i3(1, 1, 1), p, p + 2, None) == -7
+    # fragments need n + 1 divisible by p (where p > 1), plain pooling needs n divisible by p
+    assert L.znni_mpf(1, 1, _i3(8, 7, 7), _i3(2, 2, 2), p, p, None) == -2
+    assert L.znni_mpf(1, 1, _i3(9, 9, 9), _i3(5, 1, 1), p, p, None) == -3      # window above the supported 4
+    assert L.znni_maxpool(1, 1, _i3(8, 7, 8), _i3(2, 2, 2), p, p, None) == -2
