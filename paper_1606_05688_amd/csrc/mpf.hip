@@ -7,9 +7,10 @@
 //
 // The layer only moves data (4 bytes in, 4 bytes out per voxel), so the kernel is built to read every input voxel
 // from HBM once and to write contiguous runs.  A workgroup owns a tile of TY x ZT positions (Y, Z) and marches
-// along x: per input plane it stages (TY+py-1) rows of (ZT+pz-1) voxels in LDS (the next plane's loads are already
-// in flight), reduces along z, then along y, and keeps the last px plane results of each of its positions in
-// registers; their maximum is M[x-px+1][Y][Z].  Positions are numbered so that consecutive lanes hold
+// along x: per input plane it stages (TY+py-1) rows of (ZT+pz-1) voxels in LDS (two LDS planes alternate, one
+// barrier per plane; the next plane's loads are already in flight), takes the maximum over the py x pz block of
+// each position, and keeps the last px plane results of each of its positions in registers; their maximum is
+// M[x-px+1][Y][Z].  Positions are numbered so that consecutive lanes hold
 // consecutive voxels of one fragment row, so a wave stores contiguous runs.  Re-read overhead: the py-1 halo rows,
 // the pz-1 halo columns and the px-1 halo planes per chunk of x.
 #include <stdint.h>
@@ -19,10 +20,9 @@
 namespace znni {
 
 constexpr int MPF_TY = 16;      // Y positions per tile
-constexpr int MPF_ZT = 128;     // at most this many Z positions per tile
 constexpr int MPF_PMAX = 4;     // largest window per axis
-constexpr int MPF_NP = MPF_TY * MPF_ZT / 256;                                        // positions per thread
-constexpr int MPF_NL = ((MPF_TY + MPF_PMAX - 1) * (MPF_ZT + MPF_PMAX - 1) + 255) / 256;   // staged voxels per thread
+// A tile covers at most ZT = 128 or 256 positions along z (template parameter; 256 or 512 threads): the wider
+// tile reads whole rows of images up to 256 voxels wide in one piece, which HBM serves faster than two half rows.
 
 struct MpfArgs {
     int nx, ny, nz;      // image
@@ -34,15 +34,19 @@ struct MpfArgs {
     int XC;              // x positions per chunk (a multiple of px)
 };
 
-template <int PX>
-__global__ __launch_bounds__(256) void k_mpf(const float* __restrict__ in, float* __restrict__ out, MpfArgs a)
+// PX: window along x.  PY, PZ: windows along y and z when known at compile time, 0 = take them from the arguments.
+template <int PX, int PY, int PZ, int MPF_ZT>
+__global__ __launch_bounds__(2 * MPF_ZT) void k_mpf(const float* __restrict__ in, float* __restrict__ out, MpfArgs a)
 {
-    __shared__ float raw[(MPF_TY + MPF_PMAX - 1) * (MPF_ZT + MPF_PMAX - 1)];
-    __shared__ float zf[(MPF_TY + MPF_PMAX - 1) * MPF_ZT];
+    constexpr int NT = 2 * MPF_ZT;                                                            // threads
+    constexpr int MPF_NP = MPF_TY * MPF_ZT / NT;                                              // positions per thread
+    constexpr int MPF_NL = ((MPF_TY + MPF_PMAX - 1) * (MPF_ZT + MPF_PMAX - 1) + NT - 1) / NT; // staged voxels per thread
+    constexpr int RAW = (MPF_TY + MPF_PMAX - 1) * (MPF_ZT + MPF_PMAX - 1);
+    __shared__ float raw[2][RAW];                        // two planes: one being read, one being filled
     const int t = threadIdx.x;
     const int zt = blockIdx.x % a.nzt, yt = (blockIdx.x / a.nzt) % a.nyt, xc = blockIdx.x / (a.nzt * a.nyt);
     const int img = blockIdx.y;
-    const int py = a.py, pz = a.pz, nz = a.nz;
+    const int py = PY ? PY : a.py, pz = PZ ? PZ : a.pz, nz = a.nz;
     const int Yn = py * a.my, Zn = pz * a.mz, Xn = PX * a.mx;
     const int ZT = pz * a.CT;
     const int Y0 = yt * MPF_TY, Z0 = zt * ZT, X0 = xc * a.XC;
@@ -55,27 +59,28 @@ __global__ __launch_bounds__(256) void k_mpf(const float* __restrict__ in, float
     int goff[MPF_NL], loff[MPF_NL];
 #pragma unroll
     for (int i = 0; i < MPF_NL; ++i) {
-        const int e = t + 256 * i;
+        const int e = t + NT * i;
         const bool ok = e < rows * W;
         const int ec = ok ? e : 0;
         const int r = ec / W, c = ec - r * W;
         goff[i] = (Y0 + r) * nz + Z0 + c;
         loff[i] = ok ? r * W + c : -1;
     }
-    // ---- positions of this thread: LDS slot of (Yl, Zl) in zf and where the voxel goes inside its fragment
-    int zoff[MPF_NP];
+    // ---- positions of this thread: LDS slot of the block's first voxel and where the result goes inside its
+    // fragment.  Position e = (Yl, oz, c) with c fastest: consecutive lanes hold consecutive voxels of one
+    // fragment row.
+    int roff[MPF_NP];
     size_t ooff[MPF_NP];
     const size_t fragvox = (size_t)a.mx * a.my * a.mz;
     const int s = img / a.f, i_in = img - s * a.f;
     const int alpha = PX * py * pz;
 #pragma unroll
     for (int i = 0; i < MPF_NP; ++i) {
-        const int e = t + 256 * i;
+        const int e = t + NT * i;
         const int Yl = e / ZT, rem = e - Yl * ZT;
         const int oz = rem / a.CT, c = rem - oz * a.CT;
-        const int Zl = oz + pz * c;
-        const bool ok = Yl < TYv && c < CTv && oz < pz;
-        zoff[i] = ok ? Yl * ZTv + Zl : -1;
+        const bool ok = Yl < TYv && c < CTv;
+        roff[i] = ok ? Yl * W + oz + pz * c : -1;
         const int Y = Y0 + Yl, oy = Y % py, b = Y / py;
         const int batch0 = s * alpha + oy * pz + oz;             // fragment of offset (0, oy, oz)
         ooff[i] = ((size_t)batch0 * a.f + i_in) * fragvox + (size_t)b * a.mz + (Z0 / pz + c);
@@ -96,38 +101,31 @@ __global__ __launch_bounds__(256) void k_mpf(const float* __restrict__ in, float
         for (int r = 0; r < PX; ++r) {
             const int xl = xb + r;                       // plane X0 + xl
             if (xl < nplanes) {                          // uniform over the workgroup
-                __syncthreads();                         // earlier reads of raw and zf are done
+                float* cur = raw[xl & 1];                // its readers of two planes ago passed the last barrier
 #pragma unroll
                 for (int i = 0; i < MPF_NL; ++i)
-                    if (loff[i] >= 0) raw[loff[i]] = v[i];
+                    if (loff[i] >= 0) cur[loff[i]] = v[i];
                 __syncthreads();
                 if (xl + 1 < nplanes) {                  // next plane: loads stay in flight during the arithmetic
                     const float* nxt = plane + (size_t)(xl + 1) * plane_stride;
 #pragma unroll
                     for (int i = 0; i < MPF_NL; ++i) v[i] = nxt[goff[i]];
                 }
-                for (int e = t; e < rows * ZTv; e += 256) {          // maximum along z
-                    const int rr = e / ZTv, zl = e - rr * ZTv;
-                    const float* p = raw + rr * W + zl;
-                    float m = p[0];
-                    for (int c = 1; c < pz; ++c) m = fmaxf(m, p[c]);
-                    zf[e] = m;
-                }
-                __syncthreads();
+                const int X = max(X0 + xl - (PX - 1), 0);        // results exist from plane PX-1 of the chunk on
+                float* obase = out + (size_t)(X % PX) * ox_stride + (size_t)(X / PX) * a_stride;
 #pragma unroll
-                for (int i = 0; i < MPF_NP; ++i) {                   // maximum along y, then along x
-                    if (zoff[i] < 0) continue;
-                    const float* p = zf + zoff[i];
+                for (int i = 0; i < MPF_NP; ++i) {       // maximum over the y-z block, then along x
+                    if (roff[i] < 0) continue;
+                    const float* p = cur + roff[i];
                     float m = p[0];
-                    for (int b = 1; b < py; ++b) m = fmaxf(m, p[b * ZTv]);
+                    for (int b = 0; b < py; ++b)
+                        for (int c = 0; c < pz; ++c) m = fmaxf(m, p[b * W + c]);
                     ring[r][i] = m;
                     if (xl >= PX - 1) {
                         float mm = ring[0][i];
 #pragma unroll
                         for (int q = 1; q < PX; ++q) mm = fmaxf(mm, ring[q][i]);
-                        const int X = X0 + xl - (PX - 1);
-                        const int ox = X % PX, aa = X / PX;
-                        out[ooff[i] + (size_t)ox * ox_stride + (size_t)aa * a_stride] = mm;
+                        obase[ooff[i]] = mm;
                     }
                 }
             }
@@ -155,7 +153,15 @@ template <int PX>
 static znni_status launch_mpf_t(const float* in, float* out, const MpfArgs& a, int nimg, hipStream_t st)
 {
     const int nxc = (PX * a.mx + a.XC - 1) / a.XC;
-    k_mpf<PX><<<dim3((unsigned)(a.nyt * a.nzt * nxc), (unsigned)nimg), dim3(256), 0, st>>>(in, out, a);
+    const dim3 grid((unsigned)(a.nyt * a.nzt * nxc), (unsigned)nimg);
+    const bool wide = a.pz * a.CT > 128;
+    if (a.py == PX && a.pz == PX) {    // cubic windows: all three extents known at compile time
+        if (wide) k_mpf<PX, PX, PX, 256><<<grid, dim3(512), 0, st>>>(in, out, a);
+        else k_mpf<PX, PX, PX, 128><<<grid, dim3(256), 0, st>>>(in, out, a);
+    } else {
+        if (wide) k_mpf<PX, 0, 0, 256><<<grid, dim3(512), 0, st>>>(in, out, a);
+        else k_mpf<PX, 0, 0, 128><<<grid, dim3(256), 0, st>>>(in, out, a);
+    }
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
@@ -192,7 +198,9 @@ znni_status znni_mpf(int S, int f, const int n[3], const int p[3], const float* 
     a.mx = n[0] / p[0]; a.my = n[1] / p[1]; a.mz = n[2] / p[2];
     a.f = f;
     if ((long long)S * p[0] * p[1] * p[2] * f > (1ll << 31) - 1) return ZNNI_ERR_SHAPE;
-    a.CT = a.mz < MPF_ZT / a.pz ? a.mz : MPF_ZT / a.pz;
+    // fragment columns per tile: 256 positions along z when the image is wider than 128, else 128
+    const int zt_max = a.pz * a.mz > 128 ? 256 : 128;
+    a.CT = a.mz < zt_max / a.pz ? a.mz : zt_max / a.pz;
     a.nzt = (a.mz + a.CT - 1) / a.CT;
     a.nyt = (a.py * a.my + MPF_TY - 1) / MPF_TY;
     // x positions per chunk: about 32 planes, so the px-1 halo planes cost a few percent and there are enough
