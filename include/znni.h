@@ -133,6 +133,30 @@ znni_status znni_conv3d_fft_profile_v(int S, int f, int fo, const int n[3], cons
                                       float* stage_ms);
 
 /*
+ * The layer under a memory budget (Section VII-A: a layer of shape (S, f, f') computed as sub-layers of shapes
+ * (S_i, f_i, f'_i), each small enough for the memory at hand).  The budget is the workspace the caller can
+ * spare.  The division follows the preference stated there: the whole layer if it fits; else sub-batches
+ * (f_i = f, f'_i = f', the largest S_i that fits), which transform every input and output image once; else
+ * S_i = 1 with blocks of f_i input and f'_i output images (f_i from {f, multiples of 4, 2, 1}, f'_i from
+ * {f', multiples of 16, 8, 4, 2, 1}), chosen to move the fewest bytes.  In the last case the sub-layers of one block of output images add their
+ * products into that block's spectra, which are inverse-transformed once, after the last input block; bias and
+ * transfer function are applied there.  The result equals znni_conv3d_fft_v's up to fp32 rounding (the sum over
+ * input images is taken in a different order).
+ *
+ * znni_conv3d_fft_sublayers_v: host only.  Writes the division for `budget_bytes` to sub[3] = {S_i, f_i, f'_i}
+ *   and the workspace it needs (<= budget_bytes) to *bytes.  ZNNI_ERR_WORKSPACE if even the smallest division
+ *   (S_i = f_i = f'_i = 1) does not fit; *bytes then holds what that division needs.
+ * znni_conv3d_fft_budget_v: runs the layer with the division chosen for workspace_bytes.  Arguments, ownership,
+ *   alignment and status codes as for znni_conv3d_fft_v; ZNNI_ERR_WORKSPACE if no division fits.
+ */
+znni_status znni_conv3d_fft_sublayers_v(int S, int f, int fo, const int n[3], const int k[3],
+                                        size_t budget_bytes, int sub[3], size_t* bytes);
+
+znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const int k[3],
+                                     const float* in, const float* w, const float* bias, float* out,
+                                     unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Max-pooling fragments (Section VI, second paragraph).  For every offset o = (ox,oy,oz), 0 <= o < p, the image
  * is max-pooled with window p = <px,py,pz> starting at o:
  *     F[o][a][b][c] = max over the p-block of I starting at (ox + px a, oy + py b, oz + pz c),   a,b,c < m,

@@ -17,7 +17,7 @@ MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
+           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
 
 _lib = None
 
@@ -56,6 +56,10 @@ def lib():
         L.znni_conv3d_fft_profile_v.restype = i
         L.znni_conv3d_fft_profile_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp,
                                                 ctypes.POINTER(ctypes.c_float)]
+        L.znni_conv3d_fft_sublayers_v.restype = i
+        L.znni_conv3d_fft_sublayers_v.argtypes = [i, i, i, i3, i3, sz, i3, ctypes.POINTER(sz)]
+        L.znni_conv3d_fft_budget_v.restype = i
+        L.znni_conv3d_fft_budget_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
         for fn in (L.znni_mpf, L.znni_maxpool):
             fn.restype = i
             fn.argtypes = [i, i, i3, i3, vp, vp, vp]
@@ -160,6 +164,28 @@ def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=N
     else:
         _check(lib().znni_conv3d_fft_profile_v(S, f, fo, _triple(n), _triple(k), *tail))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}
+
+
+def znni_conv3d_fft_sublayers(S, f, fo, n, k, budget_bytes):
+    """Division of a layer for a workspace budget: ((S_i, f_i, f'_i), workspace bytes needed)."""
+    sub = (ctypes.c_int * 3)()
+    b = ctypes.c_size_t(0)
+    _check(lib().znni_conv3d_fft_sublayers_v(int(S), int(f), int(fo), _triple(n), _triple(k), int(budget_bytes),
+                                             sub, ctypes.byref(b)))
+    return tuple(sub), int(b.value)
+
+
+def znni_conv3d_fft_budget(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
+                           mac_reference=False):
+    """The layer computed as sub-layers that fit `workspace` (a torch uint8 CUDA tensor, required)."""
+    assert workspace is not None, "the workspace is the budget"
+    S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(lib().znni_conv3d_fft_budget_v(S, f, fo, _triple(n), _triple(k), inp.data_ptr(), w.data_ptr(),
+                                          bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                                          _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
+                                          st.cuda_stream))
+    return out
 
 
 def _pool(fn, inp, p, oshape, out, stream):

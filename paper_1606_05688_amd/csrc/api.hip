@@ -40,7 +40,8 @@ static void make_fft_plan(int N, FftPlan* P)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* L)
+// Shape part of a plan: validates, fills every size and the array sizes sz[]; assigns no pointers.
+static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[3], LayerPlan* L)
 {
     if (!n || !k) return ZNNI_ERR_NULL;
     if (S < 1 || f < 1 || fo < 1) return ZNNI_ERR_SHAPE;
@@ -71,25 +72,145 @@ znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void
 
     const size_t c = sizeof(float2);
     const size_t zc = d.zc, nimg = L->nimg, nimgo = L->nimgo;
-    const size_t sz_A1 = zc * d.ky * d.kx * L->fp * L->Mp * c;
-    // + room for the operand requests the multiply-accumulate issues one group of steps past the end
-    const size_t sz_A = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
+    L->sz[0] = zc * d.ky * d.kx * L->fp * L->Mp * c;                                    // A1
+    // A + room for the operand requests the multiply-accumulate issues one group of steps past the end
+    L->sz[1] = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
     size_t b0 = nimg * d.nx * zc * d.ny;                             // X1
     size_t t = zc * d.Ny * nimg * d.Nx; if (t > b0) b0 = t;          // Xt
     t = nimgo * zc * d.nox * d.Ny; if (t > b0) b0 = t;               // Y2
     size_t b1 = nimg * zc * d.Ny * d.nx;                             // X2
-    t = zc * d.Ny * nimgo * d.Nx; if (t > b1) b1 = t;                // Yt
     t = nimgo * d.nox * d.noy * d.ldz; if (t > b1) b1 = t;           // Y1
+    L->sz[2] = b0 * c;
+    L->sz[3] = b1 * c;
+    L->sz[4] = zc * d.Ny * nimgo * d.Nx * c;                         // Yt
+    return ZNNI_OK;
+}
+
+// Pointer part: carve the workspace at `base` into arrays of the given byte sizes.  own_yt = false: the output
+// spectra share buf1 (a whole-layer call never needs X2 or Y1 while Yt is alive).
+static void place_plan(LayerPlan* L, void* base, const size_t sz[5], bool own_yt)
+{
+    const Dims& d = L->d;
+    const size_t c = sizeof(float2);
     size_t off = 0;
     char* p = (char*)base;
     L->twx = (float2*)(p + off); off += align_up((size_t)d.Nx * c, 256);
     L->twy = (float2*)(p + off); off += align_up((size_t)d.Ny * c, 256);
     L->twz = (float2*)(p + off); off += align_up((size_t)d.Nz * c, 256);
-    L->A1 = (float2*)(p + off); off += align_up(sz_A1, 256);
-    L->A = (float2*)(p + off); off += align_up(sz_A, 256);
-    L->buf0 = (float2*)(p + off); off += align_up(b0 * c, 256);
-    L->buf1 = (float2*)(p + off); off += align_up(b1 * c, 256);
+    L->A1 = (float2*)(p + off); off += align_up(sz[0], 256);
+    L->A = (float2*)(p + off); off += align_up(sz[1], 256);
+    L->buf0 = (float2*)(p + off); off += align_up(sz[2], 256);
+    const size_t b1 = own_yt ? sz[3] : (sz[3] > sz[4] ? sz[3] : sz[4]);
+    L->buf1 = (float2*)(p + off); off += align_up(b1, 256);
+    if (own_yt) { L->Yt = (float2*)(p + off); off += align_up(sz[4], 256); }
+    else L->Yt = L->buf1;
     L->bytes = off;
+}
+
+znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* L)
+{
+    znni_status rc = shape_plan(S, f, fo, n, k, L);
+    if (rc) return rc;
+    place_plan(L, base, L->sz, false);
+    return ZNNI_OK;
+}
+
+// ------------------------------------------------------------------------------------------- sub-layers
+// Section VII-A: a layer of shape (S, f, f') can be computed as sub-layers of shapes (S_i, f_i, f'_i), each small
+// enough for the memory at hand.  Here the memory at hand is the caller's workspace.  The division follows the
+// paper's preference: whole-layer if it fits; else sub-batches (f_i = f, f'_i = f', S_i < S), which transform
+// every input and output once; else S_i = 1 with blocks of f_a input and f'_a output images.  In the last case
+// the sub-layers of one output block accumulate their products in the output spectra (kept in a buffer of their
+// own), so each output block is inverse-transformed once, and the input transforms are repeated once per output
+// block.
+struct Division {
+    int Si, fi, foi;
+    bool own_yt;
+    size_t sz[5];
+    size_t bytes;
+};
+
+// Workspace of a division: arrays sized for its largest sub-layer (the ragged last chunks are smaller).
+static znni_status division_bytes(int S, int f, int fo, const int n[3], const int k[3], Division* D)
+{
+    D->own_yt = D->fi < f;
+    for (int q = 0; q < 5; ++q) D->sz[q] = 0;
+    // distinct sub-layer shapes: full or ragged in each of S, f, f'
+    const int Ss[2] = {D->Si, S % D->Si}, fs[2] = {D->fi, f % D->fi}, fos[2] = {D->foi, fo % D->foi};
+    LayerPlan L;
+    for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b)
+            for (int c = 0; c < 2; ++c) {
+                if (Ss[a] == 0 || fs[b] == 0 || fos[c] == 0) continue;
+                znni_status rc = shape_plan(Ss[a], fs[b], fos[c], n, k, &L);
+                if (rc) return rc;
+                for (int q = 0; q < 5; ++q)
+                    if (L.sz[q] > D->sz[q]) D->sz[q] = L.sz[q];
+            }
+    place_plan(&L, nullptr, D->sz, D->own_yt);
+    D->bytes = L.bytes;
+    return ZNNI_OK;
+}
+
+// Rough HBM traffic of a division in units of one transformed image (what the choice between blockings is
+// based on): three forward passes per input image and output block, one read-modify-write of the output spectra
+// per input block, three inverse passes per output image.
+static double division_cost(int f, int fo, int fi, int foi)
+{
+    const double nfo = (fo + foi - 1) / foi, nfi = (f + fi - 1) / fi;
+    return 5.0 * f * nfo + 2.0 * fo * (nfi - 1) + 5.0 * fo;
+}
+
+static znni_status choose_division(int S, int f, int fo, const int n[3], const int k[3], size_t budget,
+                                   Division* D)
+{
+    if (!n || !k) return ZNNI_ERR_NULL;
+    if (S < 1 || f < 1 || fo < 1) return ZNNI_ERR_SHAPE;
+    D->Si = S; D->fi = f; D->foi = fo;
+    znni_status rc = division_bytes(S, f, fo, n, k, D);
+    if (rc) return rc;
+    if (D->bytes <= budget) return ZNNI_OK;
+    // sub-batches: the largest S_i that fits
+    if (S > 1) {
+        int lo = 0, hi = S;             // lo fits (0 = none), hi does not
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) / 2;
+            D->Si = mid;
+            rc = division_bytes(S, f, fo, n, k, D);
+            if (rc) return rc;
+            if (D->bytes <= budget) lo = mid; else hi = mid;
+        }
+        if (lo >= 1) {
+            D->Si = lo;
+            return division_bytes(S, f, fo, n, k, D);
+        }
+    }
+    // blocks of input and output images, one input at a time: input blocks of f, then multiples of 4 (the
+    // matrix-core contraction step), then 2 and 1; output blocks of f', then multiples of 16 (the matrix-core
+    // tile), then 8, 4, 2, 1
+    D->Si = 1;
+    Division best;
+    double best_cost = -1.0;
+    auto next = [](int cur, int full, int step) {
+        if (cur > step) return cur == full && full % step ? full / step * step : cur - step;
+        return cur / 2;                 // step, step/2, ..., 1, 0
+    };
+    for (int foi = fo; foi >= 1; foi = next(foi, fo, 16)) {
+        // the largest input block that fits with this output block
+        int fit = 0;
+        for (int fi = f; fi >= 1; fi = next(fi, f, 4)) {
+            D->fi = fi; D->foi = foi;
+            rc = division_bytes(S, f, fo, n, k, D);
+            if (rc) return rc;
+            if (D->bytes <= budget) { fit = fi; break; }
+        }
+        if (fit) {
+            const double cost = division_cost(f, fo, fit, foi);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = *D; }
+        }
+    }
+    if (best_cost < 0) return ZNNI_ERR_WORKSPACE;
+    *D = best;
     return ZNNI_OK;
 }
 
@@ -107,6 +228,12 @@ static znni_status validate(int S, int f, int fo, const int n[3], const int k[3]
     return ZNNI_OK;
 }
 
+#define ZNNI_DO(call)          \
+    do {                       \
+        rc = (call);           \
+        if (rc) return rc;     \
+    } while (0)
+
 // Runs the stages in order; if ev != NULL records ev[s] before stage s and ev[ZNNI_NUM_STAGES] at the end.
 static znni_status run(const LayerPlan& L, const float* in, const float* w, const float* bias, float* out,
                        unsigned flags, hipStream_t st, hipEvent_t* ev)
@@ -116,14 +243,9 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     do {                                                                      \
         if (ev && hipEventRecord(ev[s], st) != hipSuccess) return ZNNI_ERR_HIP; \
     } while (0)
-#define ZNNI_DO(call)          \
-    do {                       \
-        rc = (call);           \
-        if (rc) return rc;     \
-    } while (0)
     ZNNI_DO(launch_twiddles(L, st));
     ZNNI_MARK(ZNNI_STAGE_KERNEL_PREP);
-    ZNNI_DO(launch_kernel_prep(L, w, st));
+    ZNNI_DO(launch_kernel_prep(L, w, (size_t)L.f * L.d.kx * L.d.ky * L.d.kz, st));
     ZNNI_MARK(ZNNI_STAGE_FWD_Z);
     ZNNI_DO(launch_fwd_z(L, in, st));
     ZNNI_MARK(ZNNI_STAGE_FWD_Y);
@@ -131,7 +253,7 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_MARK(ZNNI_STAGE_FWD_X);
     ZNNI_DO(launch_fwd_x(L, st));
     ZNNI_MARK(ZNNI_STAGE_MAC);
-    ZNNI_DO(launch_mac(L, flags, st));
+    ZNNI_DO(launch_mac(L, flags, 0, st));
     ZNNI_MARK(ZNNI_STAGE_INV_X);
     ZNNI_DO(launch_inv_x(L, st));
     ZNNI_MARK(ZNNI_STAGE_INV_Y);
@@ -140,9 +262,46 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_DO(launch_inv_z(L, bias, out, flags, st));
     ZNNI_MARK(ZNNI_NUM_STAGES);
 #undef ZNNI_MARK
-#undef ZNNI_DO
     return ZNNI_OK;
 }
+
+// The layer as the sub-layers of division D, all on one workspace.
+static znni_status run_divided(const Division& D, int S, int f, int fo, const int n[3], const int k[3],
+                               const float* in, const float* w, const float* bias, float* out, unsigned flags,
+                               void* workspace, hipStream_t st)
+{
+    znni_status rc;
+    const size_t nvox = (size_t)n[0] * n[1] * n[2], kvol = (size_t)k[0] * k[1] * k[2];
+    const size_t ovox = (size_t)(n[0] - k[0] + 1) * (n[1] - k[1] + 1) * (n[2] - k[2] + 1);
+    bool tw_done = false;
+    for (int s0 = 0; s0 < S; s0 += D.Si) {
+        const int Sc = S - s0 < D.Si ? S - s0 : D.Si;
+        for (int j0 = 0; j0 < fo; j0 += D.foi) {
+            const int foc = fo - j0 < D.foi ? fo - j0 : D.foi;
+            LayerPlan L;
+            for (int i0 = 0; i0 < f; i0 += D.fi) {
+                const int fc = f - i0 < D.fi ? f - i0 : D.fi;
+                // a block of images is one contiguous tensor only if it spans all images of a tuple or one tuple
+                if (Sc > 1 && (fc != f || foc != fo)) return ZNNI_ERR_SHAPE;
+                ZNNI_DO(shape_plan(Sc, fc, foc, n, k, &L));
+                for (int q = 0; q < 5; ++q)
+                    if (L.sz[q] > D.sz[q]) return ZNNI_ERR_WORKSPACE;
+                place_plan(&L, workspace, D.sz, D.own_yt);
+                if (!tw_done) { ZNNI_DO(launch_twiddles(L, st)); tw_done = true; }
+                ZNNI_DO(launch_kernel_prep(L, w + ((size_t)j0 * f + i0) * kvol, (size_t)f * kvol, st));
+                ZNNI_DO(launch_fwd_z(L, in + ((size_t)s0 * f + i0) * nvox, st));
+                ZNNI_DO(launch_fwd_y(L, st));
+                ZNNI_DO(launch_fwd_x(L, st));
+                ZNNI_DO(launch_mac(L, flags, i0 > 0, st));
+            }
+            ZNNI_DO(launch_inv_x(L, st));
+            ZNNI_DO(launch_inv_y(L, st));
+            ZNNI_DO(launch_inv_z(L, bias ? bias + j0 : nullptr, out + ((size_t)s0 * fo + j0) * ovox, flags, st));
+        }
+    }
+    return ZNNI_OK;
+}
+#undef ZNNI_DO
 
 __global__ void k_copy_probe(float4* __restrict__ dst, const float4* __restrict__ src, size_t n16)
 {
@@ -239,6 +398,38 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k, const fl
     const int nn[3] = {n, n, n}, kk[3] = {k, k, k};
     return znni_conv3d_fft_profile_v(S, f, fo, nn, kk, in, w, bias, out, flags, workspace, workspace_bytes,
                                      stream, stage_ms);
+}
+
+znni_status znni_conv3d_fft_sublayers_v(int S, int f, int fo, const int n[3], const int k[3],
+                                        size_t budget_bytes, int sub[3], size_t* bytes)
+{
+    if (!sub || !bytes) return ZNNI_ERR_NULL;
+    Division D;
+    znni_status rc = choose_division(S, f, fo, n, k, budget_bytes, &D);
+    if (rc == ZNNI_ERR_WORKSPACE) {
+        // report what the smallest division would need
+        D.Si = 1; D.fi = 1; D.foi = 1;
+        if (division_bytes(S, f, fo, n, k, &D) == ZNNI_OK) *bytes = D.bytes;
+        return rc;
+    }
+    if (rc) return rc;
+    sub[0] = D.Si; sub[1] = D.fi; sub[2] = D.foi;
+    *bytes = D.bytes;
+    return ZNNI_OK;
+}
+
+znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                                     const float* w, const float* bias, float* out, unsigned flags,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE)) return ZNNI_ERR_FLAGS;
+    Division D;
+    znni_status rc = choose_division(S, f, fo, n, k, workspace_bytes, &D);
+    if (rc) return rc;
+    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u) return ZNNI_ERR_ALIGN;
+    if ((uintptr_t)workspace & 255u) return ZNNI_ERR_ALIGN;
+    return run_divided(D, S, f, fo, n, k, in, w, bias, out, flags, workspace, (hipStream_t)stream);
 }
 
 znni_status znni_copy_probe(void* dst, const void* src, size_t bytes, void* stream)

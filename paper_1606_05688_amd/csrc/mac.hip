@@ -31,7 +31,7 @@ namespace znni {
 // A1[oz][b<ky][a<kx][i<fp][j<Mp] = sum_{c<kz} w[j][i][a][b][c] exp(-2 pi i oz c / Nz); zero where i >= f or
 // j >= fo.  (j fastest, so the y stage below reads and writes contiguous runs.)
 __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, const float2* __restrict__ twz,
-                          Dims d, int f, int fo, int fp, int Mp)
+                          Dims d, int f, int fo, int fp, int Mp, size_t wj_stride)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int oz = blockIdx.y;
@@ -43,7 +43,7 @@ __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, 
     const int a = ba % d.kx, b = ba / d.kx;
     float2 acc = make_float2(0.f, 0.f);
     if (i < f && j < fo) {
-        const float* wr = w + ((((size_t)j * f + i) * d.kx + a) * d.ky + b) * d.kz;
+        const float* wr = w + (size_t)j * wj_stride + ((((size_t)i) * d.kx + a) * d.ky + b) * d.kz;
         for (int c = 0; c < d.kz; ++c) acc = caxpy(acc, wr[c], twz[(oz * c) % d.Nz]);
     }
     A1[(size_t)oz * per + idx] = acc;
@@ -92,7 +92,8 @@ __global__ void k_zero(float2* p, size_t count)
 // Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
 // a diagnostic path (flag ZNNI_MAC_REFERENCE) the matrix-core kernel can be compared with.
 __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
-                             const float2* __restrict__ tw, int N, int S, int f, int fo, int k, int fp, int Mp)
+                             const float2* __restrict__ tw, int N, int S, int f, int fo, int k, int fp, int Mp,
+                             int accumulate)
 {
     // N = Nx, k = kx; grid = (Ny, zc)
     const size_t pencil = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
@@ -109,7 +110,8 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
                         W = cadd(W, cmul(Ap[(size_t)(((i >> 2) * k + a) * 4 + (i & 3)) * Mp + j], tw[(a * ox) % N]));
                     acc = cadd(acc, cmul(W, Xp[(size_t)(s * f + i) * N + ox]));
                 }
-                Yp[(size_t)(s * fo + j) * N + ox] = acc;
+                float2* dst = Yp + (size_t)(s * fo + j) * N + ox;
+                *dst = accumulate ? cadd(*dst, acc) : acc;
             }
     }
 }
@@ -130,7 +132,7 @@ template <int RTW, int CTW>
 __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                   float2* __restrict__ Yt, const float2* __restrict__ twg,
                                                   int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
-                                                  int col0, int ncolblk, int nmblk, int npencils)
+                                                  int col0, int ncolblk, int nmblk, int npencils, int accumulate)
 {
     extern __shared__ float2 lds[];
     constexpr int NW = 64 * CTW;
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
 #undef ZNNI_MAC_STEP
 #undef ZNNI_MAC_PREP
     }
-    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo);
+    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo, accumulate);
 }
 
 #define ZNNI_LAUNCH_CHECK()                         \
@@ -263,12 +265,13 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
         if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP; \
     } while (0)
 
-znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st)
+znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_stride, hipStream_t st)
 {
     const Dims& d = L.d;
     const int per = d.kx * L.fp * L.Mp;
     const int per1 = per * d.ky;
-    k_kprep_z<<<dim3((per1 + 255) / 256, d.zc), dim3(256), 0, st>>>(w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp);
+    k_kprep_z<<<dim3((per1 + 255) / 256, d.zc), dim3(256), 0, st>>>(w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp,
+                                                                    wj_stride);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)d.Nx * d.Ny * d.Nz));
     k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256), 0, st>>>(
@@ -309,7 +312,7 @@ void plan_mac(LayerPlan* L)
 }
 
 template <int RTW, int CTW>
-static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
 {
     const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
     const size_t lds = sizeof(float2) * ((size_t)L.d.Nx + (size_t)L.mac_FC * 64 * CTW);
@@ -320,17 +323,17 @@ static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, hipStr
     const int per_pencil = sg.ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
     k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f, L.fo, L.d.kx, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
-        L.mac_nmblk, npencils);
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.d.kx, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+        L.mac_nmblk, npencils, accumulate);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
 
-znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
+znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipStream_t st)
 {
     if (flags & ZNNI_MAC_REFERENCE) {
-        k_mac_simple<<<dim3(L.d.Ny, L.d.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f,
-                                                                 L.fo, L.d.kx, L.fp, L.Mp);
+        k_mac_simple<<<dim3(L.d.Ny, L.d.zc), dim3(256), 0, st>>>(L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f,
+                                                                 L.fo, L.d.kx, L.fp, L.Mp, accumulate);
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
@@ -338,19 +341,19 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st)
         const MacSegment& sg = L.mac_seg[g];
         znni_status rc = ZNNI_ERR_SHAPE;
         if (mac_k_available(L.d.kx)) {
-            rc = launch_mac_k(L, sg, st);
+            rc = launch_mac_k(L, sg, accumulate, st);
             if (rc) return rc;
             continue;
         }
         switch (L.mac_RTW * 10 + sg.CTW) {
-            case 11: rc = launch_mac_t<1, 1>(L, sg, st); break;
-            case 12: rc = launch_mac_t<1, 2>(L, sg, st); break;
-            case 21: rc = launch_mac_t<2, 1>(L, sg, st); break;
-            case 22: rc = launch_mac_t<2, 2>(L, sg, st); break;
-            case 31: rc = launch_mac_t<3, 1>(L, sg, st); break;
-            case 32: rc = launch_mac_t<3, 2>(L, sg, st); break;
-            case 41: rc = launch_mac_t<4, 1>(L, sg, st); break;
-            case 51: rc = launch_mac_t<5, 1>(L, sg, st); break;
+            case 11: rc = launch_mac_t<1, 1>(L, sg, accumulate, st); break;
+            case 12: rc = launch_mac_t<1, 2>(L, sg, accumulate, st); break;
+            case 21: rc = launch_mac_t<2, 1>(L, sg, accumulate, st); break;
+            case 22: rc = launch_mac_t<2, 2>(L, sg, accumulate, st); break;
+            case 31: rc = launch_mac_t<3, 1>(L, sg, accumulate, st); break;
+            case 32: rc = launch_mac_t<3, 2>(L, sg, accumulate, st); break;
+            case 41: rc = launch_mac_t<4, 1>(L, sg, accumulate, st); break;
+            case 51: rc = launch_mac_t<5, 1>(L, sg, accumulate, st); break;
         }
         if (rc) return rc;
     }

@@ -82,10 +82,11 @@ __device__ __forceinline__ void mac_stage_x(float2* Xs, const MacWork& w, int ic
 
 // Combine the three partial products (Re = P1 - P2, Im = P3 - P1 - P2) and store the wave's tiles.
 // Accumulator element e of lane l is row 4*(l/16)+e, column l%16.
+// accumulate != 0: the result is added to what Yt already holds.
 template <int RTW, int CTW>
 __device__ __forceinline__ void mac_store(const MacWork& w, const floatx4 (&p1)[RTW][CTW],
                                           const floatx4 (&p2)[RTW][CTW], const floatx4 (&p3)[RTW][CTW], int N,
-                                          int fo)
+                                          int fo, int accumulate)
 {
 #pragma unroll
     for (int c = 0; c < CTW; ++c) {
@@ -98,15 +99,23 @@ __device__ __forceinline__ void mac_store(const MacWork& w, const floatx4 (&p1)[
         for (int r = 0; r < RTW; ++r)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float re = p1[r][c][e] - p2[r][c][e];
-                const float im = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
-                if (row0 + r * 16 + e < fo) y[(size_t)(r * 16 + e) * N] = make_float2(re, im);
+                float re = p1[r][c][e] - p2[r][c][e];
+                float im = p3[r][c][e] - p1[r][c][e] - p2[r][c][e];
+                if (row0 + r * 16 + e < fo) {
+                    float2* dst = y + (size_t)(r * 16 + e) * N;
+                    if (accumulate) {
+                        const float2 old = *dst;
+                        re += old.x;
+                        im += old.y;
+                    }
+                    *dst = make_float2(re, im);
+                }
             }
     }
 }
 
 // mac_k.hip: kernels with the number of kernel taps known at compile time (k = 3, 5, 7).
 bool mac_k_available(int k);
-znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st);
+znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st);
 
 }  // namespace znni

@@ -20,7 +20,7 @@ template <int RTW, int CTW, int K>
 __global__ __launch_bounds__(256, (RTW * CTW * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
 void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
                   const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int col0,
-                  int ncolblk, int nmblk, int npencils)
+                  int ncolblk, int nmblk, int npencils, int accumulate)
 {
     extern __shared__ float2 Xs[];          // [FC][NW]
     constexpr int NW = 64 * CTW;
@@ -107,13 +107,13 @@ void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, f
         if (i4 < nI) ZNNI_MAC_ITER(ga, gb, xa, xb, i4)
 #undef ZNNI_MAC_ITER
     }
-    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo);
+    mac_store<RTW, CTW>(w, p1, p2, p3, N, fo, accumulate);
 }
 
 bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
 
 template <int RTW, int CTW, int K>
-static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
 {
     const void* fn = (const void*)k_mac_mfma_k<RTW, CTW, K>;
     const size_t lds = sizeof(float2) * (size_t)L.mac_FC * 64 * CTW;
@@ -124,34 +124,34 @@ static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, hipStream_
     const int per_pencil = sg.ncolblk * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
     k_mac_mfma_k<RTW, CTW, K><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.buf1, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
-        L.mac_nmblk, npencils);
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+        L.mac_nmblk, npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
 
 template <int K>
-static znni_status launch_tiles(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+static znni_status launch_tiles(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
 {
     switch (L.mac_RTW * 10 + sg.CTW) {
-        case 11: return launch_k<1, 1, K>(L, sg, st);
-        case 12: return launch_k<1, 2, K>(L, sg, st);
-        case 21: return launch_k<2, 1, K>(L, sg, st);
-        case 22: return launch_k<2, 2, K>(L, sg, st);
-        case 31: return launch_k<3, 1, K>(L, sg, st);
-        case 32: return launch_k<3, 2, K>(L, sg, st);
-        case 41: return launch_k<4, 1, K>(L, sg, st);
-        case 51: return launch_k<5, 1, K>(L, sg, st);
+        case 11: return launch_k<1, 1, K>(L, sg, accumulate, st);
+        case 12: return launch_k<1, 2, K>(L, sg, accumulate, st);
+        case 21: return launch_k<2, 1, K>(L, sg, accumulate, st);
+        case 22: return launch_k<2, 2, K>(L, sg, accumulate, st);
+        case 31: return launch_k<3, 1, K>(L, sg, accumulate, st);
+        case 32: return launch_k<3, 2, K>(L, sg, accumulate, st);
+        case 41: return launch_k<4, 1, K>(L, sg, accumulate, st);
+        case 51: return launch_k<5, 1, K>(L, sg, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }
 
-znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, hipStream_t st)
+znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
 {
     switch (L.d.kx) {
-        case 3: return launch_tiles<3>(L, sg, st);
-        case 5: return launch_tiles<5>(L, sg, st);
-        case 7: return launch_tiles<7>(L, sg, st);
+        case 3: return launch_tiles<3>(L, sg, accumulate, st);
+        case 5: return launch_tiles<5>(L, sg, accumulate, st);
+        case 7: return launch_tiles<7>(L, sg, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }

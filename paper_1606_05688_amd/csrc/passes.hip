@@ -314,7 +314,7 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
     znni_status rc = allow_lds((const void*)k_inv_x, lds);
     if (rc) return rc;
     dim3 grid((d.Ny + TL - 1) / TL, d.zc, L.nimgo);
-    k_inv_x<<<grid, dim3(256), lds, st>>>(L.buf1, L.buf0, L.twx, L.fftx, d, L.nimgo, TL);
+    k_inv_x<<<grid, dim3(256), lds, st>>>(L.Yt, L.buf0, L.twx, L.fftx, d, L.nimgo, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }

@@ -308,7 +308,7 @@ znni_status launch_fast_fwd_x(const LayerPlan& L, hipStream_t st)
 znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    return launch_kind<P_INV_X>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimgo),
+    return launch_kind<P_INV_X>(d.Nx, base_args(L, L.Yt, L.buf0, L.twx, L.nimgo),
                                 dim3((d.Ny + 15) / 16, d.zc, L.nimgo), st);
 }
 znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)

@@ -47,6 +47,9 @@ struct LayerPlan {
     float2* A;    // [zc][Ny][fp/4][kx][4][Mp]       after the z and y stages, scaled by 1/(Nx Ny Nz)
     float2* buf0;
     float2* buf1;
+    float2* Yt;   // accumulated output spectra: buf1 itself for a whole-layer call; a buffer of its own when the
+                  // layer runs as sub-layers, because it must then survive the forward passes of later input chunks
+    size_t sz[5]; // bytes of A1, A, buf0, buf1 and of a separate Yt
     size_t bytes; // total workspace bytes
 };
 
@@ -57,12 +60,15 @@ znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void
 int lines_per_tile(int N);
 
 znni_status launch_twiddles(const LayerPlan& L, hipStream_t st);
-znni_status launch_kernel_prep(const LayerPlan& L, const float* w, hipStream_t st);
+// w points at kernel (j0, i0) of the bank; wj_stride = floats between the kernels of consecutive output images
+// (f_total * kx*ky*kz), so a sub-bank of a larger bank can be transformed in place.
+znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_stride, hipStream_t st);
 znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st);
 znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st);
 void plan_mac(LayerPlan* L);
-znni_status launch_mac(const LayerPlan& L, unsigned flags, hipStream_t st);
+// accumulate != 0: add to the spectra already in L.Yt instead of overwriting them (later chunks of input images).
+znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipStream_t st);
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);

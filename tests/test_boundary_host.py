@@ -143,3 +143,39 @@ def test_pooling_calls_validate_before_any_gpu_work():
     assert L.znni_mpf(1, 1, _i3(8, 7, 7), _i3(2, 2, 2), p, p, None) == -2
     assert L.znni_mpf(1, 1, _i3(9, 9, 9), _i3(5, 1, 1), p, p, None) == -3      # window above the supported 4
     assert L.znni_maxpool(1, 1, _i3(8, 7, 8), _i3(2, 2, 2), p, p, None) == -2
+
+
+def test_sublayer_division_follows_the_stated_preference():
+    S, f, fo, n, k = 8, 32, 32, (64, 64, 64), (7, 7, 7)
+    full = B.znni_conv3d_fft_workspace(S, f, fo, n, k)
+    assert B.znni_conv3d_fft_sublayers(S, f, fo, n, k, full) == ((S, f, fo), full)
+    assert B.znni_conv3d_fft_sublayers(S, f, fo, n, k, 10 * full) == ((S, f, fo), full)
+    prev = None
+    for frac in (0.9, 0.6, 0.4, 0.29):              # sub-batches while at least one whole input fits
+        sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, int(frac * full))
+        assert sub[1:] == (f, fo) and 1 <= sub[0] < S and need <= frac * full
+        assert prev is None or sub[0] <= prev
+        prev = sub[0]
+        # one more input per sub-batch would not fit
+        L = B.lib()
+        sub3 = (ctypes.c_int * 3)()
+        b = ctypes.c_size_t(0)
+        assert B.znni_conv3d_fft_workspace(sub[0] + 1, f, fo, n, k) > frac * full
+    one = B.znni_conv3d_fft_workspace(1, f, fo, n, k)
+    sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, one - 1)
+    assert sub[0] == 1 and (sub[1] < f or sub[2] < fo) and need <= one - 1
+    # smallest division; below it the query fails and reports what that division needs
+    L = B.lib()
+    sub3 = (ctypes.c_int * 3)()
+    b = ctypes.c_size_t(0)
+    assert L.znni_conv3d_fft_sublayers_v(S, f, fo, _i3(*n), _i3(*k), 1024, sub3, ctypes.byref(b)) == -4
+    floor = b.value
+    assert 0 < floor < one
+    assert B.znni_conv3d_fft_sublayers(S, f, fo, n, k, floor)[0] == (1, 1, 1)
+    assert L.znni_conv3d_fft_sublayers_v(S, f, fo, _i3(*n), _i3(*k), floor - 1, sub3, ctypes.byref(b)) == -4
+    assert L.znni_conv3d_fft_sublayers_v(S, f, fo, _i3(*n), _i3(*k), full, None, ctypes.byref(b)) == -1
+    assert L.znni_conv3d_fft_sublayers_v(S, 0, fo, _i3(*n), _i3(*k), full, sub3, ctypes.byref(b)) == -2
+    p = 0x1000
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 8, 0x100000, full, None) == -5
