@@ -80,6 +80,46 @@ def cpu_baseline(layer, workloads):
     }
 
 
+def _time_ms(torch, fn, reps):
+    """Average milliseconds of fn() over reps calls, by events on torch's current stream (where fn launches)."""
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def bench_mpf(torch, B, dev):
+    """Max-pooling fragments (Section VI) on 48 images of 255^3 with window 2^3 -> 8 x 48 fragments of 127^3:
+    the pooling layer that would follow a layer of the benchmark's size.  Pure data movement: 4 bytes read per
+    input voxel, 4 bytes written per fragment voxel."""
+    S, f, n, p = 1, 48, 255, 2
+    inp = torch.rand((S, f, n, n, n), device=dev) * 2 - 1
+    out = torch.empty((S * p ** 3, f) + (n // p,) * 3, device=dev)
+    ms = _time_ms(torch, lambda: B.znni_mpf(inp, p, out=out), 10)
+    nbytes = 4 * (inp.numel() + out.numel())
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": f"mpf_S{S}_f{f}_{n}c_p{p}", "ms": ms, "GB": nbytes / 1e9, "GB/s": gbs,
+            "frac_hbm": gbs / HBM_PEAK_GBS, "out_voxels_per_s": out.numel() / (ms * 1e-3)}
+
+
+def bench_sublayers(torch, B, layer, inp, w, bias, out, full_ms):
+    """The benchmark layer again with half of its workspace (Section VII-A sub-layers)."""
+    S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
+    full = B.znni_conv3d_fft_workspace(S, f, fo, n, k)
+    budget = full // 2
+    sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, budget)
+    ws = torch.empty(budget, dtype=torch.uint8, device=inp.device)
+    ms = _time_ms(torch, lambda: B.znni_conv3d_fft_budget(inp, w, bias, relu=layer.relu, out=out, workspace=ws), 3)
+    return {"workload": layer.name, "budget_bytes": budget, "workspace_bytes_used": need,
+            "division": {"S_i": sub[0], "f_i": sub[1], "f_out_i": sub[2]}, "ms": ms,
+            "out_voxels_per_s": layer.out_voxels / (ms * 1e-3), "slowdown_vs_whole_layer": ms / full_ms}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +127,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the short measurements of the pooling layer and of the budgeted (sub-layer) run")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run the library's plain 1 GiB copy kernel (calibrates rocprofv3 traffic counters)")
     args = ap.parse_args()
@@ -185,6 +227,12 @@ def main():
                        "frac_hbm": fft_bytes / (fft_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "stages": stages,
     }
+    if not args.no_extras:
+        # not part of the timed steps above: the rows built next to the hot path, measured once each
+        rec["next_rows"] = {"sublayers": bench_sublayers(torch, B, layer, inp, w, bias, out, ms_plain)}
+        del ws
+        torch.cuda.empty_cache()
+        rec["next_rows"]["mpf"] = bench_mpf(torch, B, dev)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(layer, W)
     print(json.dumps(rec))

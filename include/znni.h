@@ -157,6 +157,20 @@ znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const
                                      unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same layer by direct convolution (Section IV-A-1): no transforms, the sum over input images and kernel taps
+ * is evaluated as written, on the matrix cores.  Meant for small kernels and few input images, where it beats the
+ * transform route (Section VII: the choice of primitive per layer).  Tensors, flags (ZNNI_RELU only), ownership and
+ * status codes as for znni_conv3d_fft_v, except that in, w and out need 4-byte alignment only.  The workspace
+ * (znni_conv3d_direct_workspace_v bytes, 256-byte aligned) holds the kernel bank rearranged for the matrix cores.
+ * ZNNI_ERR_UNSUPPORTED_SIZE if the kernel is too large for this primitive (about 7^3 and up).
+ */
+znni_status znni_conv3d_direct_workspace_v(int S, int f, int fo, const int n[3], const int k[3], size_t* bytes);
+
+znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int k[3],
+                                 const float* in, const float* w, const float* bias, float* out,
+                                 unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Max-pooling fragments (Section VI, second paragraph).  For every offset o = (ox,oy,oz), 0 <= o < p, the image
  * is max-pooled with window p = <px,py,pz> starting at o:
  *     F[o][a][b][c] = max over the p-block of I starting at (ox + px a, oy + py b, oz + pz c),   a,b,c < m,

@@ -17,7 +17,7 @@ MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
+           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
 
 _lib = None
 
@@ -60,6 +60,10 @@ def lib():
         L.znni_conv3d_fft_sublayers_v.argtypes = [i, i, i, i3, i3, sz, i3, ctypes.POINTER(sz)]
         L.znni_conv3d_fft_budget_v.restype = i
         L.znni_conv3d_fft_budget_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
+        L.znni_conv3d_direct_workspace_v.restype = i
+        L.znni_conv3d_direct_workspace_v.argtypes = [i, i, i, i3, i3, ctypes.POINTER(sz)]
+        L.znni_conv3d_direct_v.restype = i
+        L.znni_conv3d_direct_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
         for fn in (L.znni_mpf, L.znni_maxpool):
             fn.restype = i
             fn.argtypes = [i, i, i3, i3, vp, vp, vp]
@@ -185,6 +189,27 @@ def znni_conv3d_fft_budget(inp, w, bias=None, relu=False, out=None, workspace=No
                                           bias.data_ptr() if bias is not None else None, out.data_ptr(),
                                           _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(),
                                           st.cuda_stream))
+    return out
+
+
+def znni_conv3d_direct_workspace(S, f, fo, n, k):
+    b = ctypes.c_size_t(0)
+    _check(lib().znni_conv3d_direct_workspace_v(int(S), int(f), int(fo), _triple(n), _triple(k), ctypes.byref(b)))
+    return int(b.value)
+
+
+def znni_conv3d_direct(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None):
+    """The layer by direct convolution on the matrix cores (same tensors and result as znni_conv3d_fft)."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
+    S, f = inp.shape[0], inp.shape[1]
+    if workspace is None:
+        workspace = torch.empty(znni_conv3d_direct_workspace(S, f, w.shape[0], tuple(inp.shape[2:]), tuple(w.shape[2:])),
+                                dtype=torch.uint8, device=inp.device)
+    S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(lib().znni_conv3d_direct_v(S, f, fo, _triple(n), _triple(k), inp.data_ptr(), w.data_ptr(),
+                                      bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                                      RELU if relu else 0, workspace.data_ptr(), workspace.numel(), st.cuda_stream))
     return out
 
 

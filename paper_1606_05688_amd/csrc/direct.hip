@@ -1,0 +1,277 @@
+// direct.hip -- the convolutional layer by direct convolution (Section IV-A-1), for small kernels and few images.
+//
+// The layer equation O[s][j] = act(bias[j] + sum_i w[j][i] * I[s][i]) written out per output voxel is one dense
+// contraction over the index (i, a, b, c) = (input image, kernel tap):
+//
+//     O[s][j][x][y][z] = sum_{i,a,b,c} w[j][i][a][b][c] * I[s][i][x+kx-1-a][y+ky-1-b][z+kz-1-c],
+//
+// a matrix product of the f' x (f kx ky kz) kernel bank with a (f kx ky kz) x (voxels) matrix of shifted image
+// values that is never formed: it runs on the matrix cores (v_mfma_f32_16x16x4_f32) with the shifted values read
+// from an image tile staged in LDS.  Where the paper's direct algorithm (Algorithm 1) loops over (s, j) in
+// parallel and over i serially, convolving whole images, here the parallel unit is a tile of output voxels for
+// all output images at once, so every staged input voxel is used by all f' kernels and all taps.
+//
+// Workgroup = 4 waves = one tile of TX x 4 x 32 output voxels (TX = 1 or 2) of one input s, one block of 16*RTW
+// output images.  A wave owns CTW column tiles (16 consecutive z each) and all RTW row tiles.  The contraction
+// walks input images in chunks of IC (their tiles, with a halo of k-1, are staged in LDS), and inside an image
+// the taps in steps of four (tap count padded to a multiple of four with zero weights).  Per step a lane reads
+// its tap's offset inside the tile from a small table, one image value per column tile from LDS, and its kernel
+// values from a bank rearranged once per call into the operand layout ([i][step][row tile][tap%4][row%16], so
+// a wave's load is one 256-byte run).
+#include <stdint.h>
+
+#include "znni_internal.h"
+
+namespace znni {
+
+typedef float floatx4_d __attribute__((ext_vector_type(4)));
+
+constexpr int DIRECT_NQ = 12;     // staged voxels per thread and image, at most
+constexpr int DIRECT_TY = 4, DIRECT_TZ = 32;
+
+struct DirectArgs {
+    const float* in;
+    const float* Wp;
+    const float* bias;
+    float* out;
+    Dims d;          // image, kernel and output sizes (transform sizes unused)
+    int S, f, fo;
+    int T4;          // taps per image, rounded up to a multiple of 4
+    int RT;          // row tiles of the rearranged bank (16 output images each)
+    int IC;          // images per staged chunk
+    int ntx, nty, ntz;
+    int relu;
+};
+
+// Wp[i][st][rt][kk][r] = w[rt*16 + r][i][tap st*4 + kk], zero beyond fo or beyond the last tap.
+__global__ void k_direct_prep(const float* __restrict__ w, float* __restrict__ Wp, int f, int fo, int taps, int T4,
+                              int RT, size_t wj_stride, size_t total)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int r = idx & 15, kk = (idx >> 4) & 3;
+    size_t q = idx >> 6;
+    const int rt = q % RT; q /= RT;
+    const int steps = T4 >> 2;
+    const int st = q % steps;
+    const int i = (int)(q / steps);
+    const int j = rt * 16 + r, tap = st * 4 + kk;
+    Wp[idx] = (j < fo && tap < taps) ? w[(size_t)j * wj_stride + (size_t)i * taps + tap] : 0.f;
+}
+
+template <int RTW, int CTW>
+__global__ __launch_bounds__(256) void k_direct(DirectArgs a)
+{
+    constexpr int TX = CTW / 2, TY = DIRECT_TY, TZ = DIRECT_TZ;
+    extern __shared__ float lds[];
+    int* delta = reinterpret_cast<int*>(lds);        // [T4]
+    float* tile = lds + a.T4;                        // [IC][tilevol]
+    const Dims& d = a.d;
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63, l16 = lane & 15, kk = lane >> 4;
+    const int TXI = TX + d.kx - 1, TYI = TY + d.ky - 1, TZI = TZ + d.kz - 1;
+    const int tilevol = TXI * TYI * TZI;
+    const int taps = d.kx * d.ky * d.kz;
+
+    const int tz = blockIdx.x % a.ntz, ty = (blockIdx.x / a.ntz) % a.nty, tx = blockIdx.x / (a.ntz * a.nty);
+    const int x0 = tx * TX, y0 = ty * TY, z0 = tz * TZ;
+    const int s = blockIdx.y;
+    const int rt0 = blockIdx.z * RTW;
+
+    for (int q = t; q < a.T4; q += 256) {
+        int dl = 0;
+        if (q < taps) {
+            const int c = q % d.kz, b = (q / d.kz) % d.ky, aa = q / (d.kz * d.ky);
+            dl = ((d.kx - 1 - aa) * TYI + (d.ky - 1 - b)) * TZI + (d.kz - 1 - c);
+        }
+        delta[q] = dl;
+    }
+    // staged voxels of this thread: offset inside an image (clamped into it)
+    int goff[DIRECT_NQ];
+#pragma unroll
+    for (int q = 0; q < DIRECT_NQ; ++q) {
+        const int e = min(t + 256 * q, tilevol - 1);
+        const int lz = e % TZI, ly = (e / TZI) % TYI, lx = e / (TZI * TYI);
+        const int gx = min(x0 + lx, d.nx - 1), gy = min(y0 + ly, d.ny - 1), gz = min(z0 + lz, d.nz - 1);
+        goff[q] = (gx * d.ny + gy) * d.nz + gz;
+    }
+    // column tiles of this wave: (tx, ty) pair and z half
+    int voxbase[CTW];
+#pragma unroll
+    for (int c = 0; c < CTW; ++c) {
+        const int ct = wave * CTW + c;
+        const int zt = ct & 1, pair = ct >> 1;
+        const int vy = pair % TY, vx = pair / TY;
+        voxbase[c] = (vx * TYI + vy) * TZI + zt * 16 + l16;
+    }
+
+    floatx4_d acc[RTW][CTW];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) acc[r][c] = floatx4_d{0.f, 0.f, 0.f, 0.f};
+
+    const size_t nvox = (size_t)d.nx * d.ny * d.nz;
+    const int steps = a.T4 >> 2;
+    for (int ic0 = 0; ic0 < a.f; ic0 += a.IC) {
+        const int icn = min(a.IC, a.f - ic0);
+        __syncthreads();                             // the previous chunk has been consumed
+        for (int il = 0; il < icn; ++il) {
+            const float* img = a.in + ((size_t)s * a.f + ic0 + il) * nvox;
+            float v[DIRECT_NQ];
+#pragma unroll
+            for (int q = 0; q < DIRECT_NQ; ++q)
+                if (256 * q < tilevol) v[q] = img[goff[q]];
+#pragma unroll
+            for (int q = 0; q < DIRECT_NQ; ++q)
+                if (t + 256 * q < tilevol) tile[il * tilevol + t + 256 * q] = v[q];
+        }
+        __syncthreads();
+        for (int il = 0; il < icn; ++il) {
+            const float* Ab = a.Wp + (((size_t)(ic0 + il) * steps) * a.RT + rt0) * 64 + lane;
+            const float* tl = tile + il * tilevol;
+            for (int st = 0; st < steps; ++st) {
+                const int dl = delta[st * 4 + kk];
+                float av[RTW], bv[CTW];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r) av[r] = Ab[((size_t)st * a.RT + r) * 64];
+#pragma unroll
+                for (int c = 0; c < CTW; ++c) bv[c] = tl[voxbase[c] + dl];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r)
+#pragma unroll
+                    for (int c = 0; c < CTW; ++c)
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[c], acc[r][c], 0, 0, 0);
+            }
+        }
+    }
+
+    // accumulator element e of lane l: output image 16*(rt0+r) + 4*(l/16) + e, voxel l%16 of the column tile
+    const size_t ovox = (size_t)d.nox * d.noy * d.noz;
+#pragma unroll
+    for (int c = 0; c < CTW; ++c) {
+        const int ct = wave * CTW + c;
+        const int zt = ct & 1, pair = ct >> 1;
+        const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zt * 16 + l16;
+        if (X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
+        const size_t vo = ((size_t)X * d.noy + Y) * d.noz + Z;
+#pragma unroll
+        for (int r = 0; r < RTW; ++r)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = (rt0 + r) * 16 + 4 * kk + e;
+                if (j >= a.fo) continue;
+                float v = acc[r][c][e] + (a.bias ? a.bias[j] : 0.f);
+                if (a.relu) v = fmaxf(v, 0.f);
+                a.out[((size_t)s * a.fo + j) * ovox + vo] = v;
+            }
+    }
+}
+
+struct DirectPlan {
+    Dims d;
+    int S, f, fo;
+    int taps, T4, RT, RTW, CTW, nmblk, IC;
+    size_t lds, wp_floats, bytes;
+};
+
+static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k[3], DirectPlan* P)
+{
+    if (!n || !k) return ZNNI_ERR_NULL;
+    if (S < 1 || f < 1 || fo < 1) return ZNNI_ERR_SHAPE;
+    for (int a = 0; a < 3; ++a)
+        if (n[a] < 1 || k[a] < 1 || k[a] > n[a]) return ZNNI_ERR_SHAPE;
+    if (S > 65535) return ZNNI_ERR_SHAPE;
+    if ((long long)n[0] * n[1] * n[2] > (1ll << 31) - 1) return ZNNI_ERR_SHAPE;
+    Dims& d = P->d;
+    d.nx = n[0]; d.ny = n[1]; d.nz = n[2];
+    d.kx = k[0]; d.ky = k[1]; d.kz = k[2];
+    d.Nx = d.Ny = d.Nz = 0; d.zc = d.ldz = 0;
+    d.nox = n[0] - k[0] + 1; d.noy = n[1] - k[1] + 1; d.noz = n[2] - k[2] + 1;
+    P->S = S; P->f = f; P->fo = fo;
+    P->taps = k[0] * k[1] * k[2];
+    P->T4 = (P->taps + 3) & ~3;
+    const int rt = (fo + 15) / 16;
+    if (rt <= 4) { P->nmblk = 1; P->RTW = rt; P->CTW = 4; }
+    else if (rt == 5) { P->nmblk = 1; P->RTW = 5; P->CTW = 2; }
+    else { P->nmblk = (rt + 3) / 4; P->RTW = (rt + P->nmblk - 1) / P->nmblk; P->CTW = 4; }
+    P->RT = P->nmblk * P->RTW;
+    if (P->nmblk > 65535) return ZNNI_ERR_SHAPE;
+    const int TX = P->CTW / 2;
+    const long long tilevol = (long long)(TX + k[0] - 1) * (DIRECT_TY + k[1] - 1) * (DIRECT_TZ + k[2] - 1);
+    if (tilevol > 256 * DIRECT_NQ) return ZNNI_ERR_UNSUPPORTED_SIZE;      // kernel too large for this primitive
+    int IC = (int)((48 * 1024 - 4 * P->T4) / (4 * tilevol));
+    if (IC < 1) return ZNNI_ERR_UNSUPPORTED_SIZE;
+    if (IC > 8) IC = 8;
+    if (IC > f) IC = f;
+    P->IC = IC;
+    P->lds = 4 * ((size_t)P->T4 + (size_t)IC * tilevol);
+    P->wp_floats = (size_t)f * P->T4 * P->RT * 16;
+    P->bytes = (P->wp_floats * 4 + 255) / 256 * 256;
+    return ZNNI_OK;
+}
+
+template <int RTW, int CTW>
+static znni_status launch_direct_t(const DirectArgs& a, const DirectPlan& P, hipStream_t st)
+{
+    constexpr int TX = CTW / 2;
+    DirectArgs b = a;
+    b.ntx = (P.d.nox + TX - 1) / TX;
+    b.nty = (P.d.noy + DIRECT_TY - 1) / DIRECT_TY;
+    b.ntz = (P.d.noz + DIRECT_TZ - 1) / DIRECT_TZ;
+    const long long tiles = (long long)b.ntx * b.nty * b.ntz;
+    if (tiles > 0x7fffffffll) return ZNNI_ERR_SHAPE;
+    k_direct<RTW, CTW><<<dim3((unsigned)tiles, (unsigned)P.S, (unsigned)P.nmblk), dim3(256), P.lds, st>>>(b);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
+}
+
+}  // namespace znni
+
+using namespace znni;
+
+extern "C" {
+
+znni_status znni_conv3d_direct_workspace_v(int S, int f, int fo, const int n[3], const int k[3], size_t* bytes)
+{
+    if (!bytes) return ZNNI_ERR_NULL;
+    DirectPlan P;
+    znni_status rc = direct_plan(S, f, fo, n, k, &P);
+    if (rc) return rc;
+    *bytes = P.bytes;
+    return ZNNI_OK;
+}
+
+znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                                 const float* w, const float* bias, float* out, unsigned flags, void* workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
+    if (flags & ~(unsigned)ZNNI_RELU) return ZNNI_ERR_FLAGS;
+    DirectPlan P;
+    znni_status rc = direct_plan(S, f, fo, n, k, &P);
+    if (rc) return rc;
+    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 3u) return ZNNI_ERR_ALIGN;
+    if ((uintptr_t)workspace & 255u) return ZNNI_ERR_ALIGN;
+    if (workspace_bytes < P.bytes) return ZNNI_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float* Wp = (float*)workspace;
+    k_direct_prep<<<dim3((unsigned)((P.wp_floats + 255) / 256)), dim3(256), 0, st>>>(
+        w, Wp, f, fo, P.taps, P.T4, P.RT, (size_t)f * P.taps, P.wp_floats);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    DirectArgs a;
+    a.in = in; a.Wp = Wp; a.bias = bias; a.out = out;
+    a.d = P.d; a.S = S; a.f = f; a.fo = fo;
+    a.T4 = P.T4; a.RT = P.RT; a.IC = P.IC;
+    a.ntx = a.nty = a.ntz = 0;
+    a.relu = (flags & ZNNI_RELU) ? 1 : 0;
+    switch (P.RTW * 10 + P.CTW) {
+        case 14: return launch_direct_t<1, 4>(a, P, st);
+        case 24: return launch_direct_t<2, 4>(a, P, st);
+        case 34: return launch_direct_t<3, 4>(a, P, st);
+        case 44: return launch_direct_t<4, 4>(a, P, st);
+        case 52: return launch_direct_t<5, 2>(a, P, st);
+    }
+    return ZNNI_ERR_SHAPE;
+}
+
+}  // extern "C"
