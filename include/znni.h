@@ -171,6 +171,25 @@ znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int
                                  unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Choice of primitive per layer (Section VII: each layer is run by whichever primitive is fastest for its shape).
+ * znni_conv3d_choose_v (host only) ranks the transform route and the direct route with a cost model whose rates
+ * were measured on MI355X and writes the pick to *primitive; est_ms, if not NULL, receives the two estimates in
+ * milliseconds (index = primitive; negative = that primitive does not take this shape).
+ * znni_conv3d_workspace_v / znni_conv3d_v are the workspace query and the layer call of the picked primitive;
+ * arguments as for znni_conv3d_fft_v (ZNNI_MAC_REFERENCE is rejected when the direct route is picked).
+ */
+enum { ZNNI_PRIMITIVE_FFT = 0, ZNNI_PRIMITIVE_DIRECT = 1 };
+
+znni_status znni_conv3d_choose_v(int S, int f, int fo, const int n[3], const int k[3], int* primitive,
+                                 float est_ms[2]);
+
+znni_status znni_conv3d_workspace_v(int S, int f, int fo, const int n[3], const int k[3], size_t* bytes);
+
+znni_status znni_conv3d_v(int S, int f, int fo, const int n[3], const int k[3],
+                          const float* in, const float* w, const float* bias, float* out,
+                          unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Max-pooling fragments (Section VI, second paragraph).  For every offset o = (ox,oy,oz), 0 <= o < p, the image
  * is max-pooled with window p = <px,py,pz> starting at o:
  *     F[o][a][b][c] = max over the p-block of I starting at (ox + px a, oy + py b, oz + pz c),   a,b,c < m,

@@ -17,7 +17,8 @@ MAC_REFERENCE = 2
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_mpf", "znni_maxpool", "znni_copy_probe")
+           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_conv3d_choose_v", "znni_conv3d_workspace_v", "znni_conv3d_v", "znni_mpf", "znni_maxpool",
+           "znni_copy_probe")
 
 _lib = None
 
@@ -64,6 +65,12 @@ def lib():
         L.znni_conv3d_direct_workspace_v.argtypes = [i, i, i, i3, i3, ctypes.POINTER(sz)]
         L.znni_conv3d_direct_v.restype = i
         L.znni_conv3d_direct_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
+        L.znni_conv3d_choose_v.restype = i
+        L.znni_conv3d_choose_v.argtypes = [i, i, i, i3, i3, i3, ctypes.POINTER(ctypes.c_float)]
+        L.znni_conv3d_workspace_v.restype = i
+        L.znni_conv3d_workspace_v.argtypes = [i, i, i, i3, i3, ctypes.POINTER(sz)]
+        L.znni_conv3d_v.restype = i
+        L.znni_conv3d_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
         for fn in (L.znni_mpf, L.znni_maxpool):
             fn.restype = i
             fn.argtypes = [i, i, i3, i3, vp, vp, vp]
@@ -210,6 +217,34 @@ def znni_conv3d_direct(inp, w, bias=None, relu=False, out=None, workspace=None, 
     _check(lib().znni_conv3d_direct_v(S, f, fo, _triple(n), _triple(k), inp.data_ptr(), w.data_ptr(),
                                       bias.data_ptr() if bias is not None else None, out.data_ptr(),
                                       RELU if relu else 0, workspace.data_ptr(), workspace.numel(), st.cuda_stream))
+    return out
+
+
+PRIMITIVES = ("fft", "direct")
+
+
+def znni_conv3d_choose(S, f, fo, n, k):
+    """(name of the primitive picked for this layer shape, {name: estimated milliseconds})."""
+    prim = ctypes.c_int(0)
+    est = (ctypes.c_float * 2)()
+    _check(lib().znni_conv3d_choose_v(int(S), int(f), int(fo), _triple(n), _triple(k), ctypes.byref(prim), est))
+    return PRIMITIVES[prim.value], {name: float(est[q]) for q, name in enumerate(PRIMITIVES)}
+
+
+def znni_conv3d(inp, w, bias=None, relu=False, out=None, stream=None):
+    """The layer by whichever primitive the library picks for its shape."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 5
+    assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 5
+    S, f, fo = inp.shape[0], inp.shape[1], w.shape[0]
+    n, k = tuple(inp.shape[2:]), tuple(w.shape[2:])
+    b = ctypes.c_size_t(0)
+    _check(lib().znni_conv3d_workspace_v(S, f, fo, _triple(n), _triple(k), ctypes.byref(b)))
+    ws = torch.empty(int(b.value), dtype=torch.uint8, device=inp.device)
+    S, f, fo, n, k, out, ws = _marshal(inp, w, bias, out, ws)
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(lib().znni_conv3d_v(S, f, fo, _triple(n), _triple(k), inp.data_ptr(), w.data_ptr(),
+                               bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                               RELU if relu else 0, ws.data_ptr(), ws.numel(), st.cuda_stream))
     return out
 
 

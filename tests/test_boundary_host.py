@@ -179,3 +179,34 @@ def test_sublayer_division_follows_the_stated_preference():
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 8, 0x100000, full, None) == -5
+
+
+def test_primitive_choice_follows_kernel_size_and_image_count():
+    # first layers (one input image) and 2^3 kernels go direct; large kernels and wide layers go through transforms
+    assert B.znni_conv3d_choose(1, 1, 48, 128, 3)[0] == "direct"
+    assert B.znni_conv3d_choose(1, 80, 80, 100, 2)[0] == "direct"
+    assert B.znni_conv3d_choose(1, 48, 48, 320, 5)[0] == "fft"
+    assert B.znni_conv3d_choose(8, 32, 32, 64, 7)[0] == "fft"
+    assert B.znni_conv3d_choose(1, 40, 40, 128, 3)[0] == "fft"
+    # a kernel the direct primitive cannot stage leaves only the transform route, and the estimate says so
+    prim, est = B.znni_conv3d_choose(1, 4, 4, 40, 9)
+    assert prim == "fft" and est["direct"] < 0 < est["fft"]
+    # estimates grow with the work
+    assert B.znni_conv3d_choose(1, 8, 8, 64, 3)[1]["direct"] < B.znni_conv3d_choose(1, 8, 8, 64, 5)[1]["direct"]
+    assert B.znni_conv3d_choose(1, 8, 8, 64, 3)[1]["fft"] < B.znni_conv3d_choose(1, 8, 8, 128, 3)[1]["fft"]
+    L = B.lib()
+    prim = ctypes.c_int(0)
+    assert L.znni_conv3d_choose_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), None, None) == -1
+    assert L.znni_conv3d_choose_v(1, 1, 1, _i3(8, 8, 8), _i3(9, 3, 3), ctypes.byref(prim), None) == -2
+    b = ctypes.c_size_t(0)
+    assert L.znni_conv3d_workspace_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), ctypes.byref(b)) == 0
+    assert b.value == B.znni_conv3d_direct_workspace(1, 1, 48, 128, 3)
+    assert L.znni_conv3d_workspace_v(1, 48, 48, _i3(64, 64, 64), _i3(5, 5, 5), ctypes.byref(b)) == 0
+    assert b.value == B.znni_conv3d_fft_workspace(1, 48, 48, 64, 5)
+    p = 0x1000
+    assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 40, None) == -5
+    assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 0, 0x100000, 16, None) == -4
+    assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), None, p, None, p, 0, 0x100000, 1 << 20, None) == -1
+    assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 20, None) == -5
+    assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p + 1, 0, 0x100000, 1 << 20, None) == -7
+    assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 0, 0x100000, 8, None) == -4

@@ -102,3 +102,21 @@ def test_direct_rejects_kernels_it_cannot_stage():
     with pytest.raises(B.ZnniError) as e:
         B.znni_conv3d_direct_workspace(1, 1, 1, (20, 20, 20), (9, 9, 9))
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("case", [(1, 1, 20, (40, 40, 40), (3, 3, 3), "direct"), (1, 16, 16, (64, 64, 64), (5, 5, 5), "fft"),
+                                  (2, 6, 6, (30, 30, 30), (2, 2, 2), "direct")],
+                         ids=lambda c: "S%d_f%dx%d_n%d_k%d_%s" % (c[0], c[1], c[2], c[3][0], c[4][0], c[5]))
+def test_auto_call_runs_the_picked_primitive_and_matches_oracle(oracle, case):
+    S, f, fo, n, k, want = case
+    assert B.znni_conv3d_choose(S, f, fo, n, k)[0] == want
+    inp, w, b = _rand(800 + f + fo, S, f, fo, n, k)
+    d = torch.device("cuda:0")
+    ti, tw, tb = (torch.from_numpy(t).to(d) for t in (inp, w, b))
+    got = B.znni_conv3d(ti, tw, tb, relu=True)
+    same = (B.znni_conv3d_direct if want == "direct" else B.znni_conv3d_fft)(ti, tw, tb, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(got, same)
+    exp = oracle.conv3d(inp, w, b, relu=True)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - exp) <= tol)
