@@ -107,6 +107,30 @@ def bench_mpf(torch, B, dev):
             "frac_hbm": gbs / HBM_PEAK_GBS, "out_voxels_per_s": out.numel() / (ms * 1e-3)}
 
 
+def bench_direct(torch, B, dev):
+    """Direct-convolution primitive against the transform route on two shapes: a first layer (one input image,
+    where direct wins) and the wide 3^3 layer of the workload list (where the transform route wins), with the
+    library's pick for each."""
+    res = []
+    for (S, f, fo, n, k) in ((1, 1, 48, 128, 3), (1, 40, 40, 128, 3)):
+        inp = torch.rand((S, f, n, n, n), device=dev) * 2 - 1
+        w = torch.randn((fo, f, k, k, k), device=dev) * (f * k ** 3) ** -0.5
+        b = torch.randn((fo,), device=dev)
+        out = torch.empty((S, fo) + (n - k + 1,) * 3, device=dev)
+        wsd = torch.empty(B.znni_conv3d_direct_workspace(S, f, fo, n, k), dtype=torch.uint8, device=dev)
+        wsf = B.alloc_workspace(S, f, fo, n, k, dev)
+        md = _time_ms(torch, lambda: B.znni_conv3d_direct(inp, w, b, relu=True, out=out, workspace=wsd), 10)
+        mf = _time_ms(torch, lambda: B.znni_conv3d_fft(inp, w, b, relu=True, out=out, workspace=wsf), 10)
+        flops = 2.0 * S * f * fo * k ** 3 * (n - k + 1) ** 3
+        pick, est = B.znni_conv3d_choose(S, f, fo, n, k)
+        res.append({"workload": f"S{S}_f{f}x{fo}_{n}c_k{k}", "direct_ms": md, "fft_ms": mf,
+                    "direct_TFLOP/s": flops / (md * 1e-3) / 1e12,
+                    "direct_frac_mfma_fp32": flops / (md * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
+                    "direct_out_GB/s": 4.0 * out.numel() / (md * 1e-3) / 1e9,
+                    "picked": pick, "estimated_ms": est})
+    return res
+
+
 def bench_sublayers(torch, B, layer, inp, w, bias, out, full_ms):
     """The benchmark layer again with half of its workspace (Section VII-A sub-layers)."""
     S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
@@ -233,6 +257,7 @@ def main():
         del ws
         torch.cuda.empty_cache()
         rec["next_rows"]["mpf"] = bench_mpf(torch, B, dev)
+        rec["next_rows"]["direct"] = bench_direct(torch, B, dev)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(layer, W)
     print(json.dumps(rec))

@@ -129,18 +129,17 @@ __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __rest
 // (image fragment times twiddle, and their sum for the three-product scheme) is prepared during step s, and
 // the three partial products are combined once, after the last step.
 template <int RTW, int CTW>
-__global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A,
-                                                  float2* __restrict__ Yt, const float2* __restrict__ twg,
-                                                  int N, int S, int f, int fo, int k, int fp, int Mp, int FC,
-                                                  int col0, int ncolblk, int nmblk, int npencils, int accumulate)
+__device__ __forceinline__ void mac_body(float2* lds, const float2* __restrict__ Xt, const float2* __restrict__ A,
+                                         float2* __restrict__ Yt, const float2* __restrict__ twg, int N, int S,
+                                         int f, int fo, int k, int fp, int Mp, int FC, int col0, int ncolblk,
+                                         int pencil, int sub, int accumulate)
 {
-    extern __shared__ float2 lds[];
     constexpr int NW = 64 * CTW;
     float2* tws = lds;              // [N]
     float2* Xs = lds + N;           // [FC][NW]
 
     MacWork w;
-    if (!mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, k, fp, Mp, col0, ncolblk, nmblk, npencils)) return;
+    mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, k, fp, Mp, col0, ncolblk, pencil, sub);
     const int l16 = w.l16, kk = w.kk, m0 = w.m0, cw0 = w.cw0, colbase = w.colbase;
     const float2* Ap = w.Ap;
 
@@ -260,6 +259,27 @@ __global__ __launch_bounds__(256, RTW * CTW <= 3 ? 3 : 2) void k_mac_mfma(const 
     mac_store<RTW, CTW>(w, p1, p2, p3, N, fo, accumulate);
 }
 
+// One launch for all column blocks of all pencils: pieces [0, n2*nmblk) of a pencil are 128-wide blocks, the rest
+// 64-wide blocks behind them.  WIDE = false leaves the 128-wide path out (row blocks too tall for it).
+template <int RTW, bool WIDE>
+__global__ __launch_bounds__(256, RTW * (WIDE ? 2 : 1) <= 3 ? 3 : 2)
+void k_mac_mfma(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
+                const float2* __restrict__ twg, int N, int S, int f, int fo, int k, int fp, int Mp, int FC, int n2,
+                int n1, int nmblk, int npencils, int accumulate)
+{
+    extern __shared__ float2 lds[];
+    int pencil, sub;
+    if (!mac_block((n2 + n1) * nmblk, npencils, pencil, sub)) return;
+    if constexpr (WIDE) {
+        if (sub < n2 * nmblk) {
+            mac_body<RTW, 2>(lds, Xt, A, Yt, twg, N, S, f, fo, k, fp, Mp, FC, 0, n2, pencil, sub, accumulate);
+            return;
+        }
+    }
+    mac_body<RTW, 1>(lds, Xt, A, Yt, twg, N, S, f, fo, k, fp, Mp, FC, n2 * 128, n1, pencil, sub - n2 * nmblk,
+                     accumulate);
+}
+
 #define ZNNI_LAUNCH_CHECK()                         \
     do {                                            \
         if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP; \
@@ -295,15 +315,10 @@ void plan_mac(LayerPlan* L)
     L->mac_nmblk = nmblk;
     L->Mp = nmblk * RTW * 16;
     const int Ct = L->S * L->d.Nx;
-    L->mac_nseg = 0;
-    int col = 0;
-    if (RTW <= 3 && Ct >= 128) {                        // room for 2 x RTW accumulator tiles per wave
-        L->mac_seg[L->mac_nseg++] = MacSegment{2, Ct / 128, 0};
-        col = (Ct / 128) * 128;
-    }
-    if (col < Ct) L->mac_seg[L->mac_nseg++] = MacSegment{1, (Ct - col + 63) / 64, col};
+    L->mac_n2 = (RTW <= 3 && Ct >= 128) ? Ct / 128 : 0;  // room for 2 x RTW accumulator tiles per wave
+    L->mac_n1 = (Ct - L->mac_n2 * 128 + 63) / 64;
     // image-spectrum block kept in LDS: about 48 KB at most, so that three workgroups share a CU
-    const int nwmax = 64 * L->mac_seg[0].CTW;
+    const int nwmax = L->mac_n2 ? 128 : 64;
     int FC = (48 * 1024) / (nwmax * (int)sizeof(float2));
     FC &= ~3;
     if (FC < 4) FC = 4;
@@ -311,19 +326,19 @@ void plan_mac(LayerPlan* L)
     L->mac_FC = FC;
 }
 
-template <int RTW, int CTW>
-static znni_status launch_mac_t(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
+template <int RTW, bool WIDE>
+static znni_status launch_mac_t(const LayerPlan& L, int accumulate, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma<RTW, CTW>;
-    const size_t lds = sizeof(float2) * ((size_t)L.d.Nx + (size_t)L.mac_FC * 64 * CTW);
+    const void* fn = (const void*)k_mac_mfma<RTW, WIDE>;
+    const size_t lds = sizeof(float2) * ((size_t)L.d.Nx + (size_t)L.mac_FC * (WIDE ? 128 : 64));
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.d.zc * L.d.Ny;
-    const int per_pencil = sg.ncolblk * L.mac_nmblk;
+    const int per_pencil = (L.mac_n2 + L.mac_n1) * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma<RTW, CTW><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.d.kx, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
+    k_mac_mfma<RTW, WIDE><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.d.kx, L.fp, L.Mp, L.mac_FC, L.mac_n2, L.mac_n1,
         L.mac_nmblk, npencils, accumulate);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
@@ -337,27 +352,23 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipSt
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
-    for (int g = 0; g < L.mac_nseg; ++g) {
-        const MacSegment& sg = L.mac_seg[g];
-        znni_status rc = ZNNI_ERR_SHAPE;
-        if (mac_k_available(L.d.kx)) {
-            rc = launch_mac_k(L, sg, accumulate, st);
-            if (rc) return rc;
-            continue;
+    if (mac_k_available(L.d.kx)) return launch_mac_k(L, accumulate, st);
+    if (L.mac_n2 > 0) {
+        switch (L.mac_RTW) {
+            case 1: return launch_mac_t<1, true>(L, accumulate, st);
+            case 2: return launch_mac_t<2, true>(L, accumulate, st);
+            case 3: return launch_mac_t<3, true>(L, accumulate, st);
         }
-        switch (L.mac_RTW * 10 + sg.CTW) {
-            case 11: rc = launch_mac_t<1, 1>(L, sg, accumulate, st); break;
-            case 12: rc = launch_mac_t<1, 2>(L, sg, accumulate, st); break;
-            case 21: rc = launch_mac_t<2, 1>(L, sg, accumulate, st); break;
-            case 22: rc = launch_mac_t<2, 2>(L, sg, accumulate, st); break;
-            case 31: rc = launch_mac_t<3, 1>(L, sg, accumulate, st); break;
-            case 32: rc = launch_mac_t<3, 2>(L, sg, accumulate, st); break;
-            case 41: rc = launch_mac_t<4, 1>(L, sg, accumulate, st); break;
-            case 51: rc = launch_mac_t<5, 1>(L, sg, accumulate, st); break;
-        }
-        if (rc) return rc;
+        return ZNNI_ERR_SHAPE;
     }
-    return ZNNI_OK;
+    switch (L.mac_RTW) {
+        case 1: return launch_mac_t<1, false>(L, accumulate, st);
+        case 2: return launch_mac_t<2, false>(L, accumulate, st);
+        case 3: return launch_mac_t<3, false>(L, accumulate, st);
+        case 4: return launch_mac_t<4, false>(L, accumulate, st);
+        case 5: return launch_mac_t<5, false>(L, accumulate, st);
+    }
+    return ZNNI_ERR_SHAPE;
 }
 
 }  // namespace znni

@@ -15,7 +15,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 //
 // blockIdx is decoded so that the workgroups sharing a pencil's A (different column blocks) and X (different
 // row blocks) are neighbours on one XCD: hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
-// so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.
+// so id = 8*slot + xcd and consecutive slots of one XCD walk (column block, row block) fastest.  One launch
+// covers every column block of every pencil: the 128-wide blocks (two column tiles per wave) and the 64-wide
+// blocks that take the remaining columns run as two code paths of the same kernel, so a pencil's A is fetched
+// from HBM once and there is no second launch with its own ramp-up and tail.
 struct MacWork {
     int pencil, colbase, m0, cw0, l16, kk, Ct;
     const float2* Xp;
@@ -23,16 +26,22 @@ struct MacWork {
     float2* Yp;
 };
 
-template <int RTW, int CTW>
-__device__ __forceinline__ bool mac_decode(MacWork& w, const float2* Xt, const float2* A, float2* Yt, int N,
-                                           int S, int f, int fo, int k, int fp, int Mp, int col0, int ncolblk,
-                                           int nmblk, int npencils)
+// Which pencil this workgroup works on and which of the pencil's (n2 + n1) * nmblk pieces; false = none.
+__device__ __forceinline__ bool mac_block(int per_pencil, int npencils, int& pencil, int& sub)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int per_pencil = ncolblk * nmblk;
-    w.pencil = (slot / per_pencil) * 8 + xcd;
-    if (w.pencil >= npencils) return false;
-    const int sub = slot % per_pencil;
+    pencil = (slot / per_pencil) * 8 + xcd;
+    sub = slot % per_pencil;
+    return pencil < npencils;
+}
+
+// Piece `sub` of a run of ncolblk column blocks of width 64*CTW starting at column col0, times nmblk row blocks.
+template <int RTW, int CTW>
+__device__ __forceinline__ void mac_decode(MacWork& w, const float2* Xt, const float2* A, float2* Yt, int N,
+                                           int S, int f, int fo, int k, int fp, int Mp, int col0, int ncolblk,
+                                           int pencil, int sub)
+{
+    w.pencil = pencil;
     const int colblk = sub % ncolblk, mblk = sub / ncolblk;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     w.l16 = lane & 15;
@@ -44,7 +53,6 @@ __device__ __forceinline__ bool mac_decode(MacWork& w, const float2* Xt, const f
     w.Xp = Xt + (size_t)w.pencil * S * f * N;
     w.Ap = A + (size_t)w.pencil * k * fp * Mp;
     w.Yp = Yt + (size_t)w.pencil * S * fo * N;
-    return true;
 }
 
 // Stage rows ic0..ic0+fc of the pencil's image spectra, columns colbase..colbase+NW, into Xs[fc][NW]
@@ -116,6 +124,6 @@ __device__ __forceinline__ void mac_store(const MacWork& w, const floatx4 (&p1)[
 
 // mac_k.hip: kernels with the number of kernel taps known at compile time (k = 3, 5, 7).
 bool mac_k_available(int k);
-znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st);
+znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st);
 
 }  // namespace znni

@@ -17,15 +17,14 @@
 namespace znni {
 
 template <int RTW, int CTW, int K>
-__global__ __launch_bounds__(256, (RTW * CTW * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
-void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
-                  const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int col0,
-                  int ncolblk, int nmblk, int npencils, int accumulate)
+__device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict__ Xt, const float2* __restrict__ A,
+                                           float2* __restrict__ Yt, const float2* __restrict__ twg, int N, int S,
+                                           int f, int fo, int fp, int Mp, int FC, int col0, int ncolblk, int pencil,
+                                           int sub, int accumulate)
 {
-    extern __shared__ float2 Xs[];          // [FC][NW]
-    constexpr int NW = 64 * CTW;
+    constexpr int NW = 64 * CTW;            // Xs: [FC][NW]
     MacWork w;
-    if (!mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, K, fp, Mp, col0, ncolblk, nmblk, npencils)) return;
+    mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, K, fp, Mp, col0, ncolblk, pencil, sub);
 
     // twiddles of this lane's columns, one per tap
     float2 T[K][CTW];
@@ -110,48 +109,74 @@ void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, f
     mac_store<RTW, CTW>(w, p1, p2, p3, N, fo, accumulate);
 }
 
+// One launch for all of a layer's column blocks: pieces [0, n2*nmblk) of a pencil are 128-wide blocks, the rest
+// 64-wide blocks behind them.  WIDE = false leaves the 128-wide path out (row blocks too tall for it).
+template <int RTW, int K, bool WIDE>
+__global__ __launch_bounds__(256, (RTW * (WIDE ? 2 : 1) * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
+void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
+                  const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int n2, int n1,
+                  int nmblk, int npencils, int accumulate)
+{
+    extern __shared__ float2 Xs[];
+    int pencil, sub;
+    if (!mac_block((n2 + n1) * nmblk, npencils, pencil, sub)) return;
+    if constexpr (WIDE) {
+        if (sub < n2 * nmblk) {
+            mac_k_body<RTW, 2, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, 0, n2, pencil, sub, accumulate);
+            return;
+        }
+    }
+    mac_k_body<RTW, 1, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, n2 * 128, n1, pencil, sub - n2 * nmblk,
+                          accumulate);
+}
+
 bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
 
-template <int RTW, int CTW, int K>
-static znni_status launch_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
+template <int RTW, int K, bool WIDE>
+static znni_status launch_k(const LayerPlan& L, int accumulate, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma_k<RTW, CTW, K>;
-    const size_t lds = sizeof(float2) * (size_t)L.mac_FC * 64 * CTW;
+    const void* fn = (const void*)k_mac_mfma_k<RTW, K, WIDE>;
+    const size_t lds = sizeof(float2) * (size_t)L.mac_FC * (WIDE ? 128 : 64);
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.d.zc * L.d.Ny;
-    const int per_pencil = sg.ncolblk * L.mac_nmblk;
+    const int per_pencil = (L.mac_n2 + L.mac_n1) * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma_k<RTW, CTW, K><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, sg.col0, sg.ncolblk,
-        L.mac_nmblk, npencils, accumulate);
+    k_mac_mfma_k<RTW, K, WIDE><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, L.mac_n2, L.mac_n1, L.mac_nmblk,
+        npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
 
 template <int K>
-static znni_status launch_tiles(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
+static znni_status launch_tiles(const LayerPlan& L, int accumulate, hipStream_t st)
 {
-    switch (L.mac_RTW * 10 + sg.CTW) {
-        case 11: return launch_k<1, 1, K>(L, sg, accumulate, st);
-        case 12: return launch_k<1, 2, K>(L, sg, accumulate, st);
-        case 21: return launch_k<2, 1, K>(L, sg, accumulate, st);
-        case 22: return launch_k<2, 2, K>(L, sg, accumulate, st);
-        case 31: return launch_k<3, 1, K>(L, sg, accumulate, st);
-        case 32: return launch_k<3, 2, K>(L, sg, accumulate, st);
-        case 41: return launch_k<4, 1, K>(L, sg, accumulate, st);
-        case 51: return launch_k<5, 1, K>(L, sg, accumulate, st);
+    if (L.mac_n2 > 0) {
+        switch (L.mac_RTW) {
+            case 1: return launch_k<1, K, true>(L, accumulate, st);
+            case 2: return launch_k<2, K, true>(L, accumulate, st);
+            case 3: return launch_k<3, K, true>(L, accumulate, st);
+        }
+        return ZNNI_ERR_SHAPE;
+    }
+    switch (L.mac_RTW) {
+        case 1: return launch_k<1, K, false>(L, accumulate, st);
+        case 2: return launch_k<2, K, false>(L, accumulate, st);
+        case 3: return launch_k<3, K, false>(L, accumulate, st);
+        case 4: return launch_k<4, K, false>(L, accumulate, st);
+        case 5: return launch_k<5, K, false>(L, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }
 
-znni_status launch_mac_k(const LayerPlan& L, const MacSegment& sg, int accumulate, hipStream_t st)
+znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     switch (L.d.kx) {
-        case 3: return launch_tiles<3>(L, sg, accumulate, st);
-        case 5: return launch_tiles<5>(L, sg, accumulate, st);
-        case 7: return launch_tiles<7>(L, sg, accumulate, st);
+        case 3: return launch_tiles<3>(L, accumulate, st);
+        case 5: return launch_tiles<5>(L, accumulate, st);
+        case 7: return launch_tiles<7>(L, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }

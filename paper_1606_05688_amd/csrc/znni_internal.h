@@ -8,12 +8,6 @@
 
 namespace znni {
 
-// A run of column blocks of the multiply-accumulate handled by one launch: CTW column tiles per wave
-// (block width 64*CTW), ncolblk blocks starting at column col0.
-struct MacSegment {
-    int CTW, ncolblk, col0;
-};
-
 // Sizes of one layer, per axis (Section IV: image size <nx,ny,nz>, kernel size <kx,ky,kz>, output size
 // n' = n - k + 1 per axis).  x is the slowest axis of the tensors, z the contiguous one.  Passed to kernels by value.
 struct Dims {
@@ -35,9 +29,9 @@ struct LayerPlan {
     int nimgo;    // S * fo
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
     int Mp;       // fo rounded up to whole row blocks of the matrix-core kernel (a multiple of 16)
-    // tiling of the matrix-core multiply-accumulate (see mac.hip)
-    int mac_RTW, mac_FC, mac_nmblk, mac_nseg;
-    MacSegment mac_seg[2];
+    // tiling of the matrix-core multiply-accumulate (see mac.hip): the S*Nx columns of a pencil are cut into
+    // mac_n2 blocks of 128 columns followed by mac_n1 blocks of 64
+    int mac_RTW, mac_FC, mac_nmblk, mac_n2, mac_n1;
     FftPlan fftx, ffty, fftz;
     // workspace carving (device pointers)
     float2* twx;  // [Nx] exp(-2 pi i q / Nx)
