@@ -47,9 +47,12 @@ typedef enum {
 /* flags */
 enum {
     ZNNI_RELU = 1u,                 /* transfer function max(0, .) (Section V); without it: identity       */
-    ZNNI_MAC_REFERENCE = 2u         /* diagnostic: run the multiply-accumulate stage with the plain one-thread- */
+    ZNNI_MAC_REFERENCE = 2u,        /* diagnostic: run the multiply-accumulate stage with the plain one-thread- */
                                     /* per-bin kernel instead of the matrix-core kernel (same result up to     */
                                     /* rounding, much slower)                                                   */
+    ZNNI_MAC_SINGLE = 4u,           /* force the multiply-accumulate form built for S = 1 (work grows with k*S) */
+    ZNNI_MAC_BATCH = 8u             /* force the form built for batches (kernel spectrum generated once per    */
+                                    /* bin, shared by the S inputs); without either flag the library picks     */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */

@@ -219,7 +219,7 @@ static znni_status validate(int S, int f, int fo, const int n[3], const int k[3]
                             size_t workspace_bytes, LayerPlan* L)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE)) return ZNNI_ERR_FLAGS;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return ZNNI_ERR_FLAGS;
     znni_status rc = make_plan(S, f, fo, n, k, workspace, L);
     if (rc) return rc;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u) return ZNNI_ERR_ALIGN;
@@ -423,7 +423,7 @@ znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const
                                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE)) return ZNNI_ERR_FLAGS;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return ZNNI_ERR_FLAGS;
     Division D;
     znni_status rc = choose_division(S, f, fo, n, k, workspace_bytes, &D);
     if (rc) return rc;

@@ -352,6 +352,9 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipSt
         ZNNI_LAUNCH_CHECK();
         return ZNNI_OK;
     }
+    if (((flags & ZNNI_MAC_BATCH) && mac_batch_available(L)) ||
+        (!(flags & ZNNI_MAC_SINGLE) && mac_batch_preferred(L)))
+        return launch_mac_batch(L, accumulate, st);
     if (mac_k_available(L.d.kx)) return launch_mac_k(L, accumulate, st);
     if (L.mac_n2 > 0) {
         switch (L.mac_RTW) {

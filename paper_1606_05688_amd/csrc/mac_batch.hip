@@ -1,0 +1,198 @@
+// mac_batch.hip -- per-bin multiply-accumulate for batches (S > 1): each kernel-spectrum value is generated once
+// per bin and reused for every input of the batch.
+//
+//     Yt[s][j](ox) = sum_i Wt[j][i](ox) * Xt[s][i](ox),      Wt[j][i](ox) = sum_{a<k} A(a,i,j) * T[a*ox]
+//
+// (one (oz,oy) pencil; A = kernel transform after its z and y stages, T[q] = exp(-2 pi i q / Nx); Section III-A's
+// last stage followed by the multiply-accumulate of Algorithm 3).  The kernels in mac.hip / mac_k.hip fold T into
+// the image operand, which makes their work proportional to k*S: the cheapest form for S = 1, the wrong one for a
+// batch.  Here both steps are matrix products on v_mfma_f32_16x16x4_f32, chained through LDS:
+//
+//   step 1, per input image i:   Wt[j][ox]   = sum_a A[j][a] * T[a][ox]        (16 j  x  k taps  x  16 ox)
+//   step 2, per bin ox:          Yt[j][s]   += sum_i Wt[j][i] * Xt[i][s]       (16 j  x  8 i per chunk  x  16 s)
+//
+// Workgroup = 4 waves = one pencil x 16 consecutive ox x 16 output images x up to 16 inputs of the batch; input
+// images are walked in chunks of 8.  Per chunk: the image values are staged in LDS ([ox][i][s]); each wave runs
+// step 1 for two of the eight images and parks real and imaginary parts in LDS ([ox][i][j], the order step 2
+// reads its left operand in); after a barrier each wave runs step 2 for four of the sixteen ox.
+// Complex products are three real ones (P1 = ar br, P2 = ai bi, P3 = (ar+ai)(br+bi)).  The result leaves through
+// LDS so that stores run along ox.
+#include "mac_common.h"
+
+namespace znni {
+
+constexpr int MB_IC = 8;              // input images per chunk
+constexpr int MB_WP = 132;            // floats between consecutive ox in the Wt arrays (8*16 + padding)
+constexpr int MB_XP = 129;            // float2 between consecutive ox in the image array (8*16 + padding)
+constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
+
+__global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
+                                                   float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
+                                                   int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
+                                                   int nsc, int npencils, int accumulate)
+{
+    // LDS: Wt as two float arrays (real, imaginary) [16 ox][MB_WP], image values float2 [16 ox][MB_XP]; the
+    // output tile (float2 [16 j][16 s][MB_OP]) reuses the same memory after the last chunk.
+    extern __shared__ float lds[];
+    float* Wr = lds;
+    float* Wi = Wr + 16 * MB_WP;
+    float2* Xl = reinterpret_cast<float2*>(Wi + 16 * MB_WP);
+
+    int pencil, sub;
+    if (!mac_block(noxt * njt * nsc, npencils, pencil, sub)) return;
+    const int oxt = sub % noxt, jt = (sub / noxt) % njt, sc = sub / (noxt * njt);
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63, l16 = lane & 15, kk = lane >> 4;
+    const int ox0 = oxt * 16, j0 = jt * 16, s0 = sc * 16;
+    const float2* Xp = Xt + (size_t)pencil * S * f * N;
+    const float2* Ap = A + (size_t)pencil * k * fp * Mp;
+    float2* Yp = Yt + (size_t)pencil * S * fo * N;
+
+    // step-1 right operand of this lane: T[a = 4*st + kk][ox = ox0 + l16], zero beyond the last tap
+    const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
+    float tr[3], ti[3], ts[3];
+    {
+        const int ox = min(ox0 + l16, N - 1);
+#pragma unroll
+        for (int st = 0; st < 3; ++st) {
+            const int a = 4 * st + kk;
+            float2 v = make_float2(0.f, 0.f);
+            if (a < k) v = twg[(int)(((long long)a * ox) % N)];
+            tr[st] = v.x; ti[st] = v.y; ts[st] = v.x + v.y;
+        }
+    }
+
+    // what this thread stages per chunk: eight image values (element e = t + 256 r of [i][s][ox]) and the step-1
+    // left operands of its wave's two images; both are requested one chunk ahead and wait in registers
+    constexpr int XR = MB_IC * 16 * 16 / 256;
+    size_t xoff[XR];                                 // offset of (s, ox) inside the pencil, image index excluded
+    float xmask[XR];
+    int xi[XR];
+#pragma unroll
+    for (int r = 0; r < XR; ++r) {
+        const int e = t + 256 * r;
+        const int oxl = e & 15, s = (e >> 4) & 15;
+        xi[r] = e >> 8;
+        const int gs = s0 + s, gox = ox0 + oxl;
+        xmask[r] = (gs < S && gox < N) ? 1.f : 0.f;
+        xoff[r] = (size_t)min(gs, S - 1) * f * N + min(gox, N - 1);
+    }
+    const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
+    float2 xreg[XR], areg[2][3];
+    auto request = [&](int ic0) {
+#pragma unroll
+        for (int r = 0; r < XR; ++r) xreg[r] = Xp[xoff[r] + (size_t)min(ic0 + xi[r], f - 1) * N];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ic = min(ic0 + 2 * wave + h, fp - 1);
+            const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
+#pragma unroll
+            for (int st = 0; st < 3; ++st)           // surplus taps meet a zero twiddle
+                areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
+        }
+    };
+    request(0);
+
+    floatx4 p1[4], p2[4], p3[4];                     // step-2 accumulators: ox = ox0 + 4*wave + q
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { p1[q] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[q] = p1[q]; p3[q] = p1[q]; }
+
+    for (int ic0 = 0; ic0 < f; ic0 += MB_IC) {
+        __syncthreads();                             // the previous chunk has been consumed
+        // ---- image values of the chunk: Xl[ox][i][s], zero outside the tensor
+#pragma unroll
+        for (int r = 0; r < XR; ++r) {
+            const int e = t + 256 * r;
+            const float mk = ic0 + xi[r] < f ? xmask[r] : 0.f;
+            Xl[(e & 15) * MB_XP + (e >> 4)] = make_float2(xreg[r].x * mk, xreg[r].y * mk);
+        }
+        // ---- step 1 for images ic0 + 2*wave, ic0 + 2*wave + 1
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int il = 2 * wave + h;
+            const float mi = ic0 + il < fp ? 1.f : 0.f;
+            floatx4 q1 = floatx4{0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
+#pragma unroll
+            for (int st = 0; st < 3; ++st) {
+                if (st < ksteps) {                   // uniform
+                    const float ar = areg[h][st].x * mi, ai = areg[h][st].y * mi;
+                    q1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar, tr[st], q1, 0, 0, 0);
+                    q2 = __builtin_amdgcn_mfma_f32_16x16x4f32(ai, ti[st], q2, 0, 0, 0);
+                    q3 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar + ai, ts[st], q3, 0, 0, 0);
+                }
+            }
+            // element e of lane: output image j0 + 4*kk + e, bin ox0 + l16
+            float4 wr, wi;
+            wr.x = q1[0] - q2[0]; wr.y = q1[1] - q2[1]; wr.z = q1[2] - q2[2]; wr.w = q1[3] - q2[3];
+            wi.x = q3[0] - q1[0] - q2[0]; wi.y = q3[1] - q1[1] - q2[1];
+            wi.z = q3[2] - q1[2] - q2[2]; wi.w = q3[3] - q1[3] - q2[3];
+            const int o = l16 * MB_WP + il * 16 + 4 * kk;
+            *reinterpret_cast<float4*>(Wr + o) = wr;
+            *reinterpret_cast<float4*>(Wi + o) = wi;
+        }
+        __syncthreads();
+        if (ic0 + MB_IC < f) request(ic0 + MB_IC);   // in flight during step 2
+        // ---- step 2 for ox = ox0 + 4*wave + q: left operand Wt[j = l16][i = 4*st + kk], right Xt[i][s = l16]
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int oxl = 4 * wave + q;
+#pragma unroll
+            for (int st = 0; st < MB_IC / 4; ++st) {
+                const int o = st * 64 + lane;
+                const float wr = Wr[oxl * MB_WP + o], wi = Wi[oxl * MB_WP + o];
+                const float2 x = Xl[oxl * MB_XP + o];
+                p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
+                p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
+                p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
+            }
+        }
+    }
+    // ---- result through LDS: Ol[j][s][ox]; accumulator element e of lane: j = 4*kk + e, s = l16
+    __syncthreads();
+    float2* Ol = reinterpret_cast<float2*>(lds);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            Ol[((4 * kk + e) * 16 + l16) * MB_OP + 4 * wave + q] =
+                make_float2(p1[q][e] - p2[q][e], p3[q][e] - p1[q][e] - p2[q][e]);
+    __syncthreads();
+    for (int e = t; e < 16 * 16 * 16; e += 256) {
+        const int oxl = e & 15, s = (e >> 4) & 15, j = e >> 8;
+        const int gs = s0 + s, gj = j0 + j, gox = ox0 + oxl;
+        if (gs >= S || gj >= fo || gox >= N) continue;
+        float2 v = Ol[(j * 16 + s) * MB_OP + oxl];
+        float2* dst = Yp + ((size_t)gs * fo + gj) * N + gox;
+        if (accumulate) {
+            const float2 old = *dst;
+            v.x += old.x;
+            v.y += old.y;
+        }
+        *dst = v;
+    }
+}
+
+// The batch form generates each kernel-spectrum value once per bin (cost independent of S) and pays one 16-column
+// matrix product per 16 inputs; the single-input form pays matrix-core work proportional to k*S.
+bool mac_batch_available(const LayerPlan& L) { return L.d.kx <= 12; }
+// Measured on MI355X (32 -> 32 and 80 -> 80 images, 32^3 .. 128^3): the batch form wins from about k*S = 32 on.
+bool mac_batch_preferred(const LayerPlan& L) { return mac_batch_available(L) && L.d.kx * L.S >= 32; }
+
+znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
+{
+    if (!mac_batch_available(L)) return ZNNI_ERR_UNSUPPORTED_SIZE;
+    const int N = L.d.Nx;
+    const size_t lds_main = sizeof(float) * 2 * 16 * MB_WP + sizeof(float2) * 16 * MB_XP;
+    const size_t lds_out = sizeof(float2) * 16 * 16 * MB_OP;
+    const size_t lds = lds_main > lds_out ? lds_main : lds_out;
+    const int noxt = (N + 15) / 16, njt = (L.fo + 15) / 16, nsc = (L.S + 15) / 16;
+    const int npencils = L.d.zc * L.d.Ny;
+    const long long blocks = (long long)((npencils + 7) / 8) * noxt * njt * nsc * 8;
+    if (blocks > 0x7fffffffll) return ZNNI_ERR_SHAPE;
+    k_mac_batch<<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo,
+                                                                  L.d.kx, L.fp, L.Mp, noxt, njt, nsc, npencils,
+                                                                  accumulate);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
+}
+
+}  // namespace znni

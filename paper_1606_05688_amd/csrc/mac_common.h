@@ -122,6 +122,11 @@ __device__ __forceinline__ void mac_store(const MacWork& w, const floatx4 (&p1)[
     }
 }
 
+// mac_batch.hip: the form for batches, kernel-spectrum values generated once per bin and shared by the S inputs.
+bool mac_batch_available(const LayerPlan& L);      // up to 12 taps along x
+bool mac_batch_preferred(const LayerPlan& L);
+znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st);
+
 // mac_k.hip: kernels with the number of kernel taps known at compile time (k = 3, 5, 7).
 bool mac_k_available(int k);
 znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st);

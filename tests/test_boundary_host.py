@@ -84,7 +84,7 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
-    assert call(flags=4) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=16) == -5 and call(flags=0x80000001) == -5
     assert call(inp=p + 4) == -7 and call(out=p + 8) == -7 and call(wsp=ws + 128) == -7
     assert call(wsb=1024) == -4
     need = B.znni_conv3d_fft_workspace(1, 1, 1, 8, 3)
@@ -178,7 +178,7 @@ def test_sublayer_division_follows_the_stated_preference():
     p = 0x1000
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
-    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 8, 0x100000, full, None) == -5
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 16, 0x100000, full, None) == -5
 
 
 def test_primitive_choice_follows_kernel_size_and_image_count():

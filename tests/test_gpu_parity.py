@@ -223,6 +223,28 @@ def test_matrix_core_mac_agrees_with_plain_mac(oracle, shape):
     assert np.all(np.abs(fast - plain) <= 0.1 * tol)
 
 
+# (S, f, fo, n, k): batch sizes below, at and above the 4-input groups, more than 16 inputs (two chunks), taps with
+# and without compile-time kernels, transform sizes that are not multiples of the 16-bin tile, one and several
+# rounds of output-image groups, image blocks that need two LDS fills.
+BATCH = [(2, 3, 5, 16, 3), (4, 4, 4, 20, 5), (5, 2, 3, 24, 2), (8, 32, 32, 16, 7), (9, 6, 40, 18, 4), (20, 3, 7, 16, 3),
+         (3, 70, 9, 16, 1), (8, 5, 70, 32, 6)]
+
+
+@pytest.mark.parametrize("shape", BATCH, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_batch_mac_form_matches_oracle_and_single_form(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand(60 + S + fo, S, f, fo, n, k)
+    _say(f"[mac/batch] {shape}")
+    batch = _run_gpu(inp, w, b, False, mac_reference="batch").cpu().numpy().astype(np.float64)
+    single = _run_gpu(inp, w, b, False, mac_reference="single").cpu().numpy().astype(np.float64)
+    exp = oracle.conv3d(inp, w, b, relu=False)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    _say(f"    max err/tol: batch {np.max(np.abs(batch - exp) / tol):.3e}, single {np.max(np.abs(single - exp) / tol):.3e}")
+    assert np.all(np.abs(batch - exp) <= tol)
+    assert np.all(np.abs(single - exp) <= tol)
+    assert np.all(np.abs(batch - single) <= 0.1 * tol)
+
+
 def test_relu_flag_and_null_bias(oracle):
     S, f, fo, n, k = 1, 2, 2, 16, 3
     inp, w, b = _rand(11, S, f, fo, n, k)

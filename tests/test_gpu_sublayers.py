@@ -70,6 +70,21 @@ def test_budgeted_layer_matches_oracle(oracle, case):
         assert torch.equal(got, whole)               # same arithmetic per input: bitwise equal
 
 
+def test_blocks_accumulate_with_either_multiply_accumulate_form(oracle):
+    S, f, fo, n, k = 1, 24, 40, (24, 20, 16), (3, 5, 2)
+    budget = int(0.25 * B.znni_conv3d_fft_workspace(S, f, fo, n, k))
+    inp, w, b = _rand(99, S, f, fo, n, k)
+    d = torch.device("cuda:0")
+    ti, tw, tb = (torch.from_numpy(t).to(d) for t in (inp, w, b))
+    ws = torch.empty(budget, dtype=torch.uint8, device=d)
+    exp = oracle.conv3d(inp, w, b, relu=True)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    for form in ("single", "batch", "reference"):
+        got = B.znni_conv3d_fft_budget(ti, tw, tb, relu=True, workspace=ws, mac_reference=form)
+        torch.cuda.synchronize()
+        assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - exp) <= tol), form
+
+
 def test_budget_too_small_is_reported_not_run():
     S, f, fo, n, k = 1, 8, 8, (32, 32, 32), (3, 3, 3)
     with pytest.raises(B.ZnniError) as e:
