@@ -75,10 +75,12 @@ int znni_version(void);
 const char* znni_status_string(znni_status st);
 
 /*
- * Transform size n~ used for an image edge n: the smallest supported size >= n.  Supported sizes are the
- * products 2^a 3^b 5^c 7^d (the family Section III-D names for GPU transforms) up to ZNNI_MAX_FFT.
- * Because the valid outputs of a circular convolution of length n~ >= n never wrap, n~ = n is used whenever
- * n itself is supported.  Returns 0 if there is none.  Host only; touches no GPU.
+ * Transform size n~ used for an image edge n.  Supported sizes are the products 2^a 3^b 5^c 7^d (the family
+ * Section III-D names for GPU transforms) up to ZNNI_MAX_FFT.  The valid outputs of a circular convolution of
+ * any length n~ >= n never wrap, so the choice is one of speed only: the smallest supported size m0 >= n is
+ * taken unless a size at most one sixth larger is served by the faster in-register pass kernels and m0 is not
+ * (e.g. 125 -> 128 rather than 126).  The result is always in [n, m0 + m0/6]; n itself whenever n is one of
+ * the in-register sizes (16, 64, 128, 256, 320, ...).  Returns 0 if there is no supported size.  Host only.
  */
 #define ZNNI_MAX_FFT 1024
 int znni_fft_size(int n);

@@ -14,12 +14,26 @@ static bool smooth7(int m)
     return m == 1;
 }
 
+// Transform size for an image edge n: a 7-smooth length >= n.  The smallest one, m0, unless a length up to
+// one sixth longer is cheaper: the pass kernels (about half of a layer's time) run 2.2 times faster per element
+// for the lengths served by the in-register kernels, and everything grows in proportion to the length, so a
+// layer costs about 1.66 units per element of a generic length against 1 of an in-register one.
 static int fft_size(int n)
 {
     if (n < 1) return 0;
+    int m0 = 0;
     for (int m = n; m <= ZNNI_MAX_FFT; ++m)
-        if (smooth7(m)) return m;
-    return 0;
+        if (smooth7(m)) { m0 = m; break; }
+    if (m0 == 0) return 0;
+    int best = m0;
+    double best_cost = m0 * (fast_pass_available(m0) ? 1.0 : 1.66);
+    const int hi = m0 + m0 / 6 < ZNNI_MAX_FFT ? m0 + m0 / 6 : ZNNI_MAX_FFT;
+    for (int m = m0 + 1; m <= hi; ++m) {
+        if (!smooth7(m)) continue;
+        const double cost = m * (fast_pass_available(m) ? 1.0 : 1.66);
+        if (cost < best_cost) { best = m; best_cost = cost; }
+    }
+    return best;
 }
 
 // Radix schedule: odd primes first, then the power of two as 8s with a 4,4 / 4 / 2 tail.
@@ -61,7 +75,9 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->S = S; L->f = f; L->fo = fo;
     d.zc = d.Nz / 2 + 1;
     d.nox = d.nx - d.kx + 1; d.noy = d.ny - d.ky + 1; d.noz = d.nz - d.kz + 1;
-    d.ldz = (d.zc + 15) & ~15;       // Y1 rows start on 128-byte boundaries
+    d.ldz = (d.zc + 15) & ~15;       // Y1, X1 and X2 rows start on 128-byte boundaries
+    d.ldy = (d.ny + 15) & ~15;
+    d.ldx = (d.nx + 15) & ~15;
     L->nimg = S * f;
     L->nimgo = S * fo;
     L->fp = (f + 3) & ~3;
@@ -75,10 +91,10 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->sz[0] = zc * d.ky * d.kx * L->fp * L->Mp * c;                                    // A1
     // A + room for the operand requests the multiply-accumulate issues one group of steps past the end
     L->sz[1] = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
-    size_t b0 = nimg * d.nx * zc * d.ny;                             // X1
+    size_t b0 = nimg * d.nx * zc * d.ldy;                            // X1
     size_t t = zc * d.Ny * nimg * d.Nx; if (t > b0) b0 = t;          // Xt
     t = nimgo * zc * d.nox * d.Ny; if (t > b0) b0 = t;               // Y2
-    size_t b1 = nimg * zc * d.Ny * d.nx;                             // X2
+    size_t b1 = nimg * zc * d.Ny * d.ldx;                            // X2
     t = nimgo * d.nox * d.noy * d.ldz; if (t > b1) b1 = t;           // Y1
     L->sz[2] = b0 * c;
     L->sz[3] = b1 * c;

@@ -96,9 +96,18 @@ template <int Ra, int Rb> struct DftCT {
     }
 };
 
+template <> struct Dft<6> { static __device__ __forceinline__ void run(float2* v) { DftCT<2, 3>::run(v); } };
+template <> struct Dft<9> { static __device__ __forceinline__ void run(float2* v) { DftCT<3, 3>::run(v); } };
 template <> struct Dft<10> { static __device__ __forceinline__ void run(float2* v) { DftCT<2, 5>::run(v); } };
+template <> struct Dft<12> { static __device__ __forceinline__ void run(float2* v) { DftCT<3, 4>::run(v); } };
+template <> struct Dft<14> { static __device__ __forceinline__ void run(float2* v) { DftCT<2, 7>::run(v); } };
+template <> struct Dft<15> { static __device__ __forceinline__ void run(float2* v) { DftCT<3, 5>::run(v); } };
 template <> struct Dft<16> { static __device__ __forceinline__ void run(float2* v) { DftCT<4, 4>::run(v); } };
+template <> struct Dft<18> { static __device__ __forceinline__ void run(float2* v) { DftCT<2, 9>::run(v); } };
 template <> struct Dft<20> { static __device__ __forceinline__ void run(float2* v) { DftCT<4, 5>::run(v); } };
+template <> struct Dft<24> { static __device__ __forceinline__ void run(float2* v) { DftCT<3, 8>::run(v); } };
+template <> struct Dft<28> { static __device__ __forceinline__ void run(float2* v) { DftCT<4, 7>::run(v); } };
+template <> struct Dft<30> { static __device__ __forceinline__ void run(float2* v) { DftCT<5, 6>::run(v); } };
 template <> struct Dft<32> { static __device__ __forceinline__ void run(float2* v) { DftCT<4, 8>::run(v); } };
 
 }  // namespace znni

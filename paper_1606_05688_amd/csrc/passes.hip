@@ -14,8 +14,8 @@
 // Layouts (image <nx,ny,nz>, transform sizes <Nx,Ny,Nz>, zc = Nz/2+1, valid outputs <nox,noy,noz>,
 // img = s*f + i, imgo = s*f' + j; all complex interleaved fp32):
 //   in  [img][x<nx][y<ny][z<nz]             real
-//   X1  [img][x<nx][oz<zc][y<ny]            after z
-//   X2  [img][oz][oy<Ny][x<nx]              after y
+//   X1  [img][x<nx][oz<zc][y<ny (ldy)]      after z     (ldy, ldx, ldz: row pitches rounded up to 16 elements,
+//   X2  [img][oz][oy<Ny][x<nx (ldx)]        after y      so that every row starts on a 128-byte boundary)
 //   Xt  [oz][oy][img][ox<Nx]                after x   ("pencil" order: one (oz,oy) pair holds all images)
 //   Yt  [oz][oy][imgo][ox<Nx]               accumulated output spectra
 //   Y2  [imgo][oz][xo<nox][oy<Ny]           after inverse x, cropped to valid x
@@ -75,14 +75,14 @@ __global__ void k_fwd_z(const float* __restrict__ in, float2* __restrict__ X1, c
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, nl, L.ld, P);
-    float2* dst = X1 + ((size_t)img * d.nx + x) * zc * ny + y0;
+    float2* dst = X1 + ((size_t)img * d.nx + x) * zc * d.ldy + y0;
     for (int e = threadIdx.x; e < zc * TL; e += blockDim.x) {
         const int l = e & (TL - 1), oz = e / TL;
         if (l >= nvalid) continue;
         const float2* row = r + (l >> 1) * L.ld;
         const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
         const float2 v = (l & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f) : cscale(cadd(z1, z2), 0.5f);
-        dst[(size_t)oz * ny + l] = v;
+        dst[(size_t)oz * d.ldy + l] = v;
     }
 }
 
@@ -99,15 +99,15 @@ __global__ void k_fwd_y(const float2* __restrict__ X1, float2* __restrict__ X2, 
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, y = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid && y < ny) v = X1[(((size_t)img * nx + x0 + l) * zc + oz) * ny + y];
+        if (l < nvalid && y < ny) v = X1[(((size_t)img * nx + x0 + l) * zc + oz) * d.ldy + y];
         L.a[l * L.ld + y] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = X2 + ((size_t)img * zc + oz) * N * nx + x0;
+    float2* dst = X2 + ((size_t)img * zc + oz) * N * d.ldx + x0;
     for (int e = threadIdx.x; e < N * TL; e += blockDim.x) {
         const int l = e & (TL - 1), oy = e / TL;
-        if (l < nvalid) dst[(size_t)oy * nx + l] = r[l * L.ld + oy];
+        if (l < nvalid) dst[(size_t)oy * d.ldx + l] = r[l * L.ld + oy];
     }
 }
 
@@ -121,11 +121,11 @@ __global__ void k_fwd_x(const float2* __restrict__ X2, float2* __restrict__ Xt, 
     const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
     const int nx = d.nx, Ny = d.Ny, zc = d.zc;
     const int nvalid = min(TL, Ny - oy0);
-    const float2* src = X2 + (((size_t)img * zc + oz) * Ny + oy0) * nx;
+    const float2* src = X2 + (((size_t)img * zc + oz) * Ny + oy0) * d.ldx;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, x = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid && x < nx) v = src[(size_t)l * nx + x];
+        if (l < nvalid && x < nx) v = src[(size_t)l * d.ldx + x];
         L.a[l * L.ld + x] = v;
     }
     __syncthreads();

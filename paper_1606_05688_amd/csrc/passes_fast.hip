@@ -1,5 +1,6 @@
 // passes_fast.hip -- the six transform passes for transform lengths N = R1*R2 with both factors small enough
-// for an in-register DFT (16, 64, 128, 256, 320).  Same layouts, pruning and results as passes.hip.
+// for an in-register DFT (31 lengths from 16 to 512, listed in launch_kind).  Same layouts, pruning and results
+// as passes.hip.
 //
 // One workgroup transforms a tile of 16 lines (passes along z: 16 pairs of real lines).  Each line is done in
 // two steps.  Step A: thread (line, j < R2) loads the R1 samples j, j+R2, j+2R2, ... straight from HBM into
@@ -77,12 +78,12 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     int nvalid = 0, lin = N;
     if constexpr (KIND == P_FWD_Y) {          // tile: 16 x of one (img, oz); lines along y in X1
         const int x0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)img * d.nx + x0) * zc + oz) * d.ny;
-        lpitch = (size_t)zc * d.ny; nvalid = min(16, d.nx - x0); lin = d.ny;
+        src = (const float2*)a.src + (((size_t)img * d.nx + x0) * zc + oz) * d.ldy;
+        lpitch = (size_t)zc * d.ldy; nvalid = min(16, d.nx - x0); lin = d.ny;
     } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
         const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.nx;
-        lpitch = d.nx; nvalid = min(16, d.Ny - oy0); lin = d.nx;
+        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.ldx;
+        lpitch = d.ldx; nvalid = min(16, d.Ny - oy0); lin = d.nx;
     } else if constexpr (KIND == P_INV_X) {   // tile: 16 oy of one (oz, imgo); lines along ox in Yt
         const int oy0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)oz * d.Ny + oy0) * a.nimg + img) * N;
@@ -178,9 +179,9 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     if constexpr (KIND == P_FWD_Y) {
         // X2[img][oz][oy][x0 + lb]
         if (q < R1 && lb < nvalid) {
-            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * N * d.nx + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * N * d.ldx + tile * 16 + lb;
 #pragma unroll
-            for (int r = 0; r < R2; ++r) o[(size_t)(q + R1 * r) * d.nx] = u[r];
+            for (int r = 0; r < R2; ++r) o[(size_t)(q + R1 * r) * d.ldx] = u[r];
         }
     } else if constexpr (KIND == P_INV_X) {
         // Y2[imgo][oz][xo][oy0 + lb], xo = element - (kx-1) in [0, nox)
@@ -221,13 +222,13 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             // untangle the two real lines and store X1[img][x][oz][y0 + ll], ll < 32 fastest across lanes
             const int y0 = tile * 32;
             const int ny = d.ny;
-            float2* o = (float2*)a.dst + ((size_t)img * d.nx + mid) * zc * ny + y0;
+            float2* o = (float2*)a.dst + ((size_t)img * d.nx + mid) * zc * d.ldy + y0;
             const int ll = t & 31;
             if (y0 + ll < ny) {
                 const float2* row = buf + (ll >> 1) * P;
                 for (int oz = t >> 5; oz < zc; oz += NTH / 32) {
                     const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
-                    o[(size_t)oz * ny + ll] = (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
+                    o[(size_t)oz * d.ldy + ll] = (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
                                                       : cscale(cadd(z1, z2), 0.5f);
                 }
             }
@@ -267,17 +268,64 @@ static znni_status launch_one(const PassArgs& a, dim3 grid, hipStream_t st)
 template <int KIND>
 static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t st)
 {
+    // N = R1 * R2; R2 is even (step B reads its samples in pairs) and 16 where possible (step A then loads
+    // 128-byte runs)
+    if constexpr (KIND == P_FWD_Z) {
+        // the real-to-complex pass loads two rows per thread in step A, 2*R1 values: with R1 above 20 that is more
+        // than a wave keeps in flight, so the long lengths are split the other way round
+        switch (N) {
+            case 384: return launch_one<16, 24, KIND>(a, grid, st);
+            case 448: return launch_one<16, 28, KIND>(a, grid, st);
+            case 480: return launch_one<16, 30, KIND>(a, grid, st);
+            case 512: return launch_one<16, 32, KIND>(a, grid, st);
+        }
+    }
     switch (N) {
         case 16: return launch_one<4, 4, KIND>(a, grid, st);
+        case 20: return launch_one<5, 4, KIND>(a, grid, st);
+        case 24: return launch_one<6, 4, KIND>(a, grid, st);
+        case 28: return launch_one<7, 4, KIND>(a, grid, st);
+        case 32: return launch_one<4, 8, KIND>(a, grid, st);
+        case 36: return launch_one<9, 4, KIND>(a, grid, st);
+        case 40: return launch_one<5, 8, KIND>(a, grid, st);
+        case 48: return launch_one<6, 8, KIND>(a, grid, st);
+        case 56: return launch_one<7, 8, KIND>(a, grid, st);
         case 64: return launch_one<8, 8, KIND>(a, grid, st);
+        case 72: return launch_one<9, 8, KIND>(a, grid, st);
+        case 80: return launch_one<5, 16, KIND>(a, grid, st);
+        case 96: return launch_one<6, 16, KIND>(a, grid, st);
+        case 100: return launch_one<10, 10, KIND>(a, grid, st);
+        case 112: return launch_one<7, 16, KIND>(a, grid, st);
+        case 120: return launch_one<15, 8, KIND>(a, grid, st);
         case 128: return launch_one<8, 16, KIND>(a, grid, st);
+        case 144: return launch_one<9, 16, KIND>(a, grid, st);
+        case 160: return launch_one<10, 16, KIND>(a, grid, st);
+        case 192: return launch_one<12, 16, KIND>(a, grid, st);
+        case 200: return launch_one<20, 10, KIND>(a, grid, st);
+        case 224: return launch_one<14, 16, KIND>(a, grid, st);
+        case 240: return launch_one<15, 16, KIND>(a, grid, st);
         case 256: return launch_one<16, 16, KIND>(a, grid, st);
+        case 288: return launch_one<18, 16, KIND>(a, grid, st);
         case 320: return launch_one<20, 16, KIND>(a, grid, st);
+        case 384: return launch_one<24, 16, KIND>(a, grid, st);
+        case 400: return launch_one<20, 20, KIND>(a, grid, st);
+        case 448: return launch_one<28, 16, KIND>(a, grid, st);
+        case 480: return launch_one<30, 16, KIND>(a, grid, st);
+        case 512: return launch_one<32, 16, KIND>(a, grid, st);
     }
     return ZNNI_ERR_UNSUPPORTED_SIZE;
 }
 
-bool fast_pass_available(int N) { return N == 16 || N == 64 || N == 128 || N == 256 || N == 320; }
+bool fast_pass_available(int N)
+{
+    switch (N) {
+        case 16: case 20: case 24: case 28: case 32: case 36: case 40: case 48: case 56: case 64: case 72: case 80:
+        case 96: case 100: case 112: case 120: case 128: case 144: case 160: case 192: case 200: case 224: case 240:
+        case 256: case 288: case 320: case 384: case 400: case 448: case 480: case 512:
+            return true;
+    }
+    return false;
+}
 
 static PassArgs base_args(const LayerPlan& L, const void* src, void* dst, const float2* tw, int nimg)
 {

@@ -17,6 +17,7 @@ struct Dims {
     int zc;               // Nz/2 + 1 bins along the halved axis
     int nox, noy, noz;    // output n - k + 1
     int ldz;              // row stride of Y1 (zc rounded up to a multiple of 16 complex = 128 bytes)
+    int ldy, ldx;         // row strides of X1 and X2 (ny and nx rounded up the same way)
 };
 
 // Everything one call needs: sizes, the radix schedules, and where each buffer lives in the workspace.

@@ -36,16 +36,23 @@ def test_status_strings():
     assert L.znni_status_string(-99) == b"unknown status"
 
 
-def test_fft_size_is_smallest_7_smooth():
+def test_fft_size_is_7_smooth_and_close_to_the_smallest():
     def smooth(m):
         for p in (2, 3, 5, 7):
             while m % p == 0:
                 m //= p
         return m == 1
+    picked_larger = 0
     for n in range(1, 1025):
         m = B.znni_fft_size(n)
-        assert m >= n and smooth(m)
-        assert all(not smooth(t) for t in range(n, m))
+        m0 = next(t for t in range(n, 1025) if smooth(t))
+        assert smooth(m) and m0 <= m <= m0 + m0 // 6
+        picked_larger += m > m0
+    assert 0 < picked_larger < 700      # the preference for in-register sizes is used, and not everywhere
+    assert B.znni_fft_size(125) == 128 and B.znni_fft_size(126) == 128 and B.znni_fft_size(243) == 256
+    assert B.znni_fft_size(17) == 20 and B.znni_fft_size(21) == 24
+    for n in (8, 12, 540, 700, 1000):         # no in-register size within reach: the smallest size itself
+        assert B.znni_fft_size(n) == n
     for n in (16, 64, 128, 320):
         assert B.znni_fft_size(n) == n          # the benchmark layers transform at their own size
     assert B.znni_fft_size(0) == 0 and B.znni_fft_size(-3) == 0 and B.znni_fft_size(1025) == 0

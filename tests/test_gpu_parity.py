@@ -133,6 +133,40 @@ def test_anisotropic_delta_kernel_moves_each_axis_by_its_own_offset():
     assert np.abs(got[0, 0] - exp).max() <= 1e-4
 
 
+# Every transform length served by the in-register pass kernels, once along each axis (so every pass kind runs at
+# every length), at the length itself and one below it (padded lines).
+FAST_N = [16, 20, 24, 28, 32, 36, 40, 48, 56, 64, 72, 80, 96, 100, 112, 120, 128, 144, 160, 192, 200, 224, 240, 256,
+          288, 320, 384, 400, 448, 480, 512]
+
+
+@pytest.mark.parametrize("N", FAST_N)
+def test_in_register_pass_lengths_along_each_axis(oracle, N):
+    assert B.znni_fft_size(N) == N and B.znni_fft_size(N - 1) == N
+    for axis in range(3):
+        for n_ax in (N, N - 1):
+            n = [12, 12, 12]
+            n[axis] = n_ax
+            k = [2, 3, 2]
+            k[axis] = 3
+            inp, w, b = _rand_v(1000 + N + axis, 1, 2, 2, n, k)
+            _check_full(oracle, inp, w, b, True, f"in-register length {N} on axis {axis}, n = {n}")
+
+
+# Lengths left to the generic pass kernels: below 16, and long ones with no in-register length within reach;
+# every radix (2, 3, 4, 5, 7, 8) occurs.
+GENERIC = [(1, 2, 2, (2, 3, 5), (1, 2, 3)), (2, 1, 2, (7, 9, 10), (3, 3, 3)), (1, 2, 1, (12, 10, 6), (2, 5, 4)),
+           (1, 1, 2, (540, 6, 10), (3, 2, 2)), (1, 2, 1, (6, 700, 9), (2, 3, 2)), (1, 1, 1, (10, 6, 1000), (2, 2, 5)),
+           (1, 1, 1, (9, 525, 8), (1, 7, 1))]
+
+
+@pytest.mark.parametrize("shape", GENERIC, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
+def test_generic_pass_lengths_full_compare(oracle, shape):
+    S, f, fo, n, k = shape
+    assert [B.znni_fft_size(t) for t in n] == list(n)
+    inp, w, b = _rand_v(1100 + sum(n), S, f, fo, n, k)
+    _check_full(oracle, inp, w, b, True, f"generic {shape}")
+
+
 # Transform lengths served by the two-step in-register passes (16, 64, 128, 256, 320), at the length itself
 # and just below it (zero-padded lines, ragged tiles of lines).
 TWO_STEP = [(2, 2, 3, 16, 3), (1, 2, 2, 15, 2), (1, 3, 2, 64, 5), (2, 1, 2, 61, 4), (1, 2, 1, 128, 3),
