@@ -53,11 +53,15 @@ __global__ void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1, 
 // (i < fp, j < Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
 // One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once and the twiddle
 // index advances by b per oy, so the kernel is bound by its 8-byte stores.
-constexpr int KPREP_OY = 8;
-__global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A, const float2* __restrict__ tw,
-                          int N, int k, int ky, int fp, int Mp, int per, float scale)
+constexpr int KPREP_OY = 32;
+__global__ __launch_bounds__(256) void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A,
+                                                 const float2* __restrict__ tw, int N, int k, int ky, int fp, int Mp,
+                                                 int per, float scale)
 {
     // N = Ny, k = kx (taps left for the multiply-accumulate), ky = taps summed here, per = kx*fp*Mp
+    extern __shared__ float2 tws[];                            // [N] copy of the twiddle table
+    for (int q = threadIdx.x; q < N; q += 256) tws[q] = tw[q];
+    __syncthreads();
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j) as laid out in A1
     const int oy0 = blockIdx.y * KPREP_OY, oz = blockIdx.z;
     if (idx >= per) return;
@@ -71,7 +75,7 @@ __global__ void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A,
         const int step = b % N;
 #pragma unroll
         for (int o = 0; o < KPREP_OY; ++o) {
-            acc[o] = cadd(acc[o], cmul(v, tw[q]));
+            acc[o] = cadd(acc[o], cmul(v, tws[q]));
             q += step;
             if (q >= N) q -= N;
         }
@@ -294,7 +298,8 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_str
                                                                     wj_stride);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)d.Nx * d.Ny * d.Nz));
-    k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256), 0, st>>>(
+    k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256),
+                sizeof(float2) * (size_t)d.Ny, st>>>(
         L.A1, L.A, L.twy, d.Ny, d.kx, d.ky, L.fp, L.Mp, per, scale);
     ZNNI_LAUNCH_CHECK();
     // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)

@@ -115,7 +115,7 @@ template <int RTW, int K, bool WIDE>
 __global__ __launch_bounds__(256, (RTW * (WIDE ? 2 : 1) * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
 void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
                   const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int n2, int n1,
-                  int nmblk, int npencils, int accumulate)
+                  int col1, int nmblk, int npencils, int accumulate)
 {
     extern __shared__ float2 Xs[];
     int pencil, sub;
@@ -126,14 +126,14 @@ void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, f
             return;
         }
     }
-    mac_k_body<RTW, 1, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, n2 * 128, n1, pencil, sub - n2 * nmblk,
+    mac_k_body<RTW, 1, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, col1, n1, pencil, sub - n2 * nmblk,
                           accumulate);
 }
 
 bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
 
 template <int RTW, int K, bool WIDE>
-static znni_status launch_k(const LayerPlan& L, int accumulate, hipStream_t st)
+static znni_status launch_k(const LayerPlan& L, int n2, int n1, int accumulate, hipStream_t st)
 {
     const void* fn = (const void*)k_mac_mfma_k<RTW, K, WIDE>;
     const size_t lds = sizeof(float2) * (size_t)L.mac_FC * (WIDE ? 128 : 64);
@@ -141,32 +141,38 @@ static znni_status launch_k(const LayerPlan& L, int accumulate, hipStream_t st)
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return ZNNI_ERR_HIP;
     const int npencils = L.d.zc * L.d.Ny;
-    const int per_pencil = (L.mac_n2 + L.mac_n1) * L.mac_nmblk;
+    const int per_pencil = (n2 + n1) * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
     k_mac_mfma_k<RTW, K, WIDE><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, L.mac_n2, L.mac_n1, L.mac_nmblk,
-        npencils, accumulate);
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, n2, n1, L.mac_n2 * 128,
+        L.mac_nmblk, npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
 
 template <int K>
+static znni_status launch_narrow(const LayerPlan& L, int accumulate, hipStream_t st)
+{
+    switch (L.mac_RTW) {
+        case 1: return launch_k<1, K, false>(L, 0, L.mac_n1, accumulate, st);
+        case 2: return launch_k<2, K, false>(L, 0, L.mac_n1, accumulate, st);
+        case 3: return launch_k<3, K, false>(L, 0, L.mac_n1, accumulate, st);
+        case 4: return launch_k<4, K, false>(L, 0, L.mac_n1, accumulate, st);
+        case 5: return launch_k<5, K, false>(L, 0, L.mac_n1, accumulate, st);
+    }
+    return ZNNI_ERR_SHAPE;
+}
+
+template <int K>
 static znni_status launch_tiles(const LayerPlan& L, int accumulate, hipStream_t st)
 {
-    if (L.mac_n2 > 0) {
-        switch (L.mac_RTW) {
-            case 1: return launch_k<1, K, true>(L, accumulate, st);
-            case 2: return launch_k<2, K, true>(L, accumulate, st);
-            case 3: return launch_k<3, K, true>(L, accumulate, st);
-        }
-        return ZNNI_ERR_SHAPE;
-    }
+    if (L.mac_n2 == 0) return launch_narrow<K>(L, accumulate, st);
+    // one launch for both block widths (two launches were measured 2 % faster for the multiply-accumulate at the
+    // 320-wide workload, because the narrow blocks then run three to a CU; not worth a second kernel per call)
     switch (L.mac_RTW) {
-        case 1: return launch_k<1, K, false>(L, accumulate, st);
-        case 2: return launch_k<2, K, false>(L, accumulate, st);
-        case 3: return launch_k<3, K, false>(L, accumulate, st);
-        case 4: return launch_k<4, K, false>(L, accumulate, st);
-        case 5: return launch_k<5, K, false>(L, accumulate, st);
+        case 1: return launch_k<1, K, true>(L, L.mac_n2, L.mac_n1, accumulate, st);
+        case 2: return launch_k<2, K, true>(L, L.mac_n2, L.mac_n1, accumulate, st);
+        case 3: return launch_k<3, K, true>(L, L.mac_n2, L.mac_n1, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }
