@@ -75,9 +75,9 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->S = S; L->f = f; L->fo = fo;
     d.zc = d.Nz / 2 + 1;
     d.nox = d.nx - d.kx + 1; d.noy = d.ny - d.ky + 1; d.noz = d.nz - d.kz + 1;
-    d.ldz = (d.zc + 15) & ~15;       // Y1, X1 and X2 rows start on 128-byte boundaries
-    d.ldy = (d.ny + 15) & ~15;
+    d.ldy = (d.ny + 15) & ~15;       // X1, X2 and Y1 rows start on 128-byte boundaries
     d.ldx = (d.nx + 15) & ~15;
+    d.ldo = (d.noy + 15) & ~15;
     L->nimg = S * f;
     L->nimgo = S * fo;
     L->fp = (f + 3) & ~3;
@@ -95,7 +95,7 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     size_t t = zc * d.Ny * nimg * d.Nx; if (t > b0) b0 = t;          // Xt
     t = nimgo * zc * d.nox * d.Ny; if (t > b0) b0 = t;               // Y2
     size_t b1 = nimg * zc * d.Ny * d.ldx;                            // X2
-    t = nimgo * d.nox * d.noy * d.ldz; if (t > b1) b1 = t;           // Y1
+    t = nimgo * d.nox * zc * d.ldo; if (t > b1) b1 = t;              // Y1
     L->sz[2] = b0 * c;
     L->sz[3] = b1 * c;
     L->sz[4] = zc * d.Ny * nimgo * d.Nx * c;                         // Yt

@@ -185,7 +185,7 @@ static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k
     Dims& d = P->d;
     d.nx = n[0]; d.ny = n[1]; d.nz = n[2];
     d.kx = k[0]; d.ky = k[1]; d.kz = k[2];
-    d.Nx = d.Ny = d.Nz = 0; d.zc = d.ldz = d.ldy = d.ldx = 0;
+    d.Nx = d.Ny = d.Nz = 0; d.zc = d.ldy = d.ldx = d.ldo = 0;
     d.nox = n[0] - k[0] + 1; d.noy = n[1] - k[1] + 1; d.noz = n[2] - k[2] + 1;
     P->S = S; P->f = f; P->fo = fo;
     P->taps = k[0] * k[1] * k[2];

@@ -14,12 +14,12 @@
 // Layouts (image <nx,ny,nz>, transform sizes <Nx,Ny,Nz>, zc = Nz/2+1, valid outputs <nox,noy,noz>,
 // img = s*f + i, imgo = s*f' + j; all complex interleaved fp32):
 //   in  [img][x<nx][y<ny][z<nz]             real
-//   X1  [img][x<nx][oz<zc][y<ny (ldy)]      after z     (ldy, ldx, ldz: row pitches rounded up to 16 elements,
+//   X1  [img][x<nx][oz<zc][y<ny (ldy)]      after z     (ldy, ldx, ldo: row pitches rounded up to 16 elements,
 //   X2  [img][oz][oy<Ny][x<nx (ldx)]        after y      so that every row starts on a 128-byte boundary)
 //   Xt  [oz][oy][img][ox<Nx]                after x   ("pencil" order: one (oz,oy) pair holds all images)
 //   Yt  [oz][oy][imgo][ox<Nx]               accumulated output spectra
 //   Y2  [imgo][oz][xo<nox][oy<Ny]           after inverse x, cropped to valid x
-//   Y1  [imgo][xo][yo<noy][oz<zc (ldz)]     after inverse y, cropped to valid y
+//   Y1  [imgo][xo][oz<zc][yo<noy (ldo)]     after inverse y, cropped to valid y
 //   out [imgo][xo][yo][zo<noz]              real, after inverse z + bias + transfer function
 #include "znni_internal.h"
 
@@ -164,32 +164,35 @@ __global__ void k_inv_x(const float2* __restrict__ Yt, float2* __restrict__ Y2, 
     }
 }
 
-// ---- inverse, axis y; keeps y in [ky-1, ny-1]; only lines with valid x exist
+// ---- inverse, axis y; keeps y in [ky-1, ny-1]; only lines with valid x exist.  Tile: TL consecutive xo of one
+// (imgo, oz), which lie next to each other in Y2; each transformed line is written as it is (yo contiguous).
 __global__ void k_inv_y(const float2* __restrict__ Y2, float2* __restrict__ Y1, const float2* __restrict__ twg,
                         FftPlan P, Dims d, int TL)
 {
     extern __shared__ float2 lds[];
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
-    const int oz0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
-    const int zc = d.zc, nox = d.nox, noy = d.noy, ldz = d.ldz;
-    const int nvalid = min(TL, zc - oz0);
+    const int xo0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
+    const int zc = d.zc, nox = d.nox, noy = d.noy;
+    const int nvalid = min(TL, nox - xo0);
+    const float2* src = Y2 + (((size_t)img * zc + oz) * nox + xo0) * N;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, oy = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid) v = cconj(Y2[(((size_t)img * zc + oz0 + l) * nox + xo) * N + oy]);
+        if (l < nvalid) v = cconj(src[(size_t)l * N + oy]);
         L.a[l * L.ld + oy] = v;
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = Y1 + ((size_t)img * nox + xo) * noy * ldz + oz0;
-    for (int e = threadIdx.x; e < noy * TL; e += blockDim.x) {
-        const int l = e & (TL - 1), yo = e / TL;
-        if (l < nvalid) dst[(size_t)yo * ldz + l] = cconj(r[l * L.ld + yo + d.ky - 1]);
+    for (int e = threadIdx.x; e < TL * noy; e += blockDim.x) {
+        const int l = e / noy, yo = e - l * noy;
+        if (l < nvalid)
+            Y1[(((size_t)img * nox + xo0 + l) * zc + oz) * d.ldo + yo] = cconj(r[l * L.ld + yo + d.ky - 1]);
     }
 }
 
-// ---- inverse, axis z: complex -> real for two lines at once; keeps z in [kz-1, nz-1]; bias + transfer
+// ---- inverse, axis z: complex -> real for two lines at once; keeps z in [kz-1, nz-1]; bias + transfer.
+// Tile: TL consecutive yo of one (imgo, xo); in Y1 they are adjacent elements of every oz row.
 __global__ void k_inv_z(const float2* __restrict__ Y1, float* __restrict__ out, const float* __restrict__ bias,
                         const float2* __restrict__ twg, FftPlan P, Dims d, int fo, int relu, int TL)
 {
@@ -197,16 +200,19 @@ __global__ void k_inv_z(const float2* __restrict__ Y1, float* __restrict__ out, 
     const int N = P.N, nl = TL >> 1;
     Lds L = carve(lds, N, nl, twg);
     const int yo0 = blockIdx.x * TL, xo = blockIdx.y, img = blockIdx.z;
-    const int zc = d.zc, nox = d.nox, noy = d.noy, noz = d.noz, ldz = d.ldz;
+    const int zc = d.zc, nox = d.nox, noy = d.noy, noz = d.noz;
     const int nvalid = min(TL, noy - yo0);
-    const float2* src = Y1 + (((size_t)img * nox + xo) * noy + yo0) * ldz;
+    const float2* src = Y1 + (((size_t)img * nox + xo) * zc) * d.ldo + yo0;
     for (int e = threadIdx.x; e < nl * N; e += blockDim.x) {
-        const int p = e / N, o = e - p * N;
+        const int p = e % nl, o = e / nl;          // the line pair fastest: neighbouring lanes read neighbouring yo
         const bool direct = o < zc;
         const int oo = direct ? o : N - o;
+        // rows are 128-byte aligned and yo0 + 2p is even: the pair (A, B) is one aligned 16-byte load; the pitch
+        // covers the element behind an odd last line
+        const float4 ab = *reinterpret_cast<const float4*>(src + (size_t)oo * d.ldo + 2 * p);
         float2 A = make_float2(0.f, 0.f), B = A;
-        if (2 * p < nvalid) A = src[(size_t)(2 * p) * ldz + oo];
-        if (2 * p + 1 < nvalid) B = src[(size_t)(2 * p + 1) * ldz + oo];
+        if (2 * p < nvalid) A = make_float2(ab.x, ab.y);
+        if (2 * p + 1 < nvalid) B = make_float2(ab.z, ab.w);
         if (!direct) { A = cconj(A); B = cconj(B); }
         // Z = A + iB carries line 2p in its real part and line 2p+1 in its imaginary part after the
         // inverse transform; stored conjugated for the forward-transform route.
@@ -327,7 +333,7 @@ znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
     const size_t lds = pass_lds_bytes(d.Ny, TL);
     znni_status rc = allow_lds((const void*)k_inv_y, lds);
     if (rc) return rc;
-    dim3 grid((d.zc + TL - 1) / TL, d.nox, L.nimgo);
+    dim3 grid((d.nox + TL - 1) / TL, d.zc, L.nimgo);
     k_inv_y<<<grid, dim3(256), lds, st>>>(L.buf0, L.buf1, L.twy, L.ffty, d, TL);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;

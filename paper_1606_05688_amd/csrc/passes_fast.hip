@@ -88,10 +88,10 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         const int oy0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)oz * d.Ny + oy0) * a.nimg + img) * N;
         lpitch = (size_t)a.nimg * N; nvalid = min(16, d.Ny - oy0);
-    } else if constexpr (KIND == P_INV_Y) {   // tile: 16 oz of one (imgo, xo); lines along oy in Y2
-        const int oz0 = tile * 16, xo = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz0) * d.nox + xo) * N;
-        lpitch = (size_t)d.nox * N; nvalid = min(16, zc - oz0);
+    } else if constexpr (KIND == P_INV_Y) {   // tile: 16 xo of one (imgo, oz); lines along oy, adjacent in Y2
+        const int xo0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.nox + xo0) * N;
+        lpitch = N; nvalid = min(16, d.nox - xo0);
     }
 
     // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
@@ -131,26 +131,28 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         }
     }
     if constexpr (KIND == P_INV_Z) {
-        // The 32 lines yo0.. of one (imgo, xo) are read from HBM once, as they lie (zc values each), into LDS.
-        // Thread (ja, la) then assembles Z = A + iB for lines A = yo0+2*la, B = A+1, extended to all N bins by
-        // Hermitian symmetry and conjugated for the inverse-by-forward route.
+        // The 32 lines yo0.. of one (imgo, xo) are read from HBM once into LDS: in Y1 they are 32 neighbouring
+        // elements (256 bytes) of each of the zc rows.  Thread (ja, la) then assembles Z = A + iB for lines
+        // A = yo0+2*la, B = A+1, extended to all N bins by Hermitian symmetry and conjugated for the
+        // inverse-by-forward route.
         constexpr int ZC = N / 2 + 1;
         const int yo0 = tile * 32, xo = mid;
         const int rows = min(32, d.noy - yo0);
-        const float2* chunk = (const float2*)a.src + (((size_t)img * d.nox + xo) * d.noy + yo0) * d.ldz;
+        const float2* chunk = (const float2*)a.src + (((size_t)img * d.nox + xo) * ZC) * d.ldo + yo0;
         constexpr int ITER = (32 * ZC + NTH - 1) / NTH;
         float2 raw[ITER];
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {       // all requests first ...
             const int e = min(t + it * NTH, 32 * ZC - 1);
-            const int r = e / ZC, o = e - r * ZC;
-            raw[it] = chunk[(size_t)min(r, rows - 1) * d.ldz + o];
+            const int r = e & 31, o = e >> 5;
+            raw[it] = chunk[(size_t)o * d.ldo + min(r, rows - 1)];
         }
 #pragma unroll
-        for (int it = 0; it < ITER; ++it) {       // ... then the LDS stores
+        for (int it = 0; it < ITER; ++it) {       // ... then the LDS stores, one row of ZC values per line
             const int e = t + it * NTH;
-            const float mk = e / ZC < rows ? 1.f : 0.f;
-            if (e < 32 * ZC) buf[e] = make_float2(raw[it].x * mk, raw[it].y * mk);
+            const int r = e & 31, o = e >> 5;
+            const float mk = r < rows ? 1.f : 0.f;
+            if (e < 32 * ZC) buf[r * ZC + o] = make_float2(raw[it].x * mk, raw[it].y * mk);
         }
         __syncthreads();
         if (in_a) {
@@ -193,16 +195,6 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
                 if (xo >= 0 && xo < d.nox) o[(size_t)xo * d.Ny] = cconj(u[r]);
             }
         }
-    } else if constexpr (KIND == P_INV_Y) {
-        // Y1[imgo][xo][yo][oz0 + lb]
-        if (q < R1 && lb < nvalid) {
-            float2* o = (float2*)a.dst + ((size_t)img * d.nox + mid) * d.noy * d.ldz + tile * 16 + lb;
-#pragma unroll
-            for (int r = 0; r < R2; ++r) {
-                const int yo = q + R1 * r - (d.ky - 1);
-                if (yo >= 0 && yo < d.noy) o[(size_t)yo * d.ldz] = cconj(u[r]);
-            }
-        }
     } else {
         // second trip through LDS: natural order per line
         __syncthreads();
@@ -217,6 +209,14 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
                 float2* o = (float2*)a.dst + (((size_t)mid * d.Ny + oy0 + l) * a.nimg + img) * N;
                 for (int e = t % 64; e < N; e += 64) o[e] = buf[l * P + e];
+            }
+        } else if constexpr (KIND == P_INV_Y) {
+            // Y1[imgo][xo0 + l][oz][yo]: the valid part of each line, contiguous
+            const int xo0 = tile * 16;
+            for (int l = t / 64; l < nvalid; l += NTH / 64) {
+                float2* o = (float2*)a.dst + (((size_t)img * d.nox + xo0 + l) * zc + mid) * d.ldo;
+                const float2* row = buf + l * P + (d.ky - 1);
+                for (int e = t % 64; e < d.noy; e += 64) o[e] = cconj(row[e]);
             }
         } else if constexpr (KIND == P_FWD_Z) {
             // untangle the two real lines and store X1[img][x][oz][y0 + ll], ll < 32 fastest across lanes
@@ -363,7 +363,7 @@ znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
     return launch_kind<P_INV_Y>(d.Ny, base_args(L, L.buf0, L.buf1, L.twy, L.nimgo),
-                                dim3((d.zc + 15) / 16, d.nox, L.nimgo), st);
+                                dim3((d.nox + 15) / 16, d.zc, L.nimgo), st);
 }
 znni_status launch_fast_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {

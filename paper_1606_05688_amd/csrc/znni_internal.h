@@ -16,8 +16,8 @@ struct Dims {
     int Nx, Ny, Nz;       // transform sizes n~ >= n
     int zc;               // Nz/2 + 1 bins along the halved axis
     int nox, noy, noz;    // output n - k + 1
-    int ldz;              // row stride of Y1 (zc rounded up to a multiple of 16 complex = 128 bytes)
-    int ldy, ldx;         // row strides of X1 and X2 (ny and nx rounded up the same way)
+    int ldy, ldx, ldo;    // row strides of X1, X2 and Y1: ny, nx and noy rounded up to a multiple of 16 complex
+                          // (128 bytes)
 };
 
 // Everything one call needs: sizes, the radix schedules, and where each buffer lives in the workspace.

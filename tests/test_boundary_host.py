@@ -158,17 +158,17 @@ def test_sublayer_division_follows_the_stated_preference():
     assert B.znni_conv3d_fft_sublayers(S, f, fo, n, k, full) == ((S, f, fo), full)
     assert B.znni_conv3d_fft_sublayers(S, f, fo, n, k, 10 * full) == ((S, f, fo), full)
     prev = None
-    for frac in (0.9, 0.6, 0.4, 0.29):              # sub-batches while at least one whole input fits
-        sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, int(frac * full))
-        assert sub[1:] == (f, fo) and 1 <= sub[0] < S and need <= frac * full
+    one = B.znni_conv3d_fft_workspace(1, f, fo, n, k)
+    for frac in (0.9, 0.6, 0.4, one / full):        # sub-batches while at least one whole input fits
+        sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, int(frac * full) + 1)
+        assert sub[1:] == (f, fo) and 1 <= sub[0] < S and need <= frac * full + 1
         assert prev is None or sub[0] <= prev
         prev = sub[0]
         # one more input per sub-batch would not fit
         L = B.lib()
         sub3 = (ctypes.c_int * 3)()
         b = ctypes.c_size_t(0)
-        assert B.znni_conv3d_fft_workspace(sub[0] + 1, f, fo, n, k) > frac * full
-    one = B.znni_conv3d_fft_workspace(1, f, fo, n, k)
+        assert B.znni_conv3d_fft_workspace(sub[0] + 1, f, fo, n, k) > frac * full + 1
     sub, need = B.znni_conv3d_fft_sublayers(S, f, fo, n, k, one - 1)
     assert sub[0] == 1 and (sub[1] < f or sub[2] < fo) and need <= one - 1
     # smallest division; below it the query fails and reports what that division needs
