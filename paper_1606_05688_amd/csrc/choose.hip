@@ -16,12 +16,13 @@
 namespace znni {
 
 // measured rates (MI355X)
-constexpr double kPassBytesPerSecFast = 4.6e12;     // in-register pass kernels
+constexpr double kPassBytesPerSecFast = 5.0e12;     // in-register pass kernels
 constexpr double kPassBytesPerSecGeneric = 2.0e12;  // generic LDS pass kernels
 constexpr double kPrepBytesPerSec = 3.0e12;         // kernel preparation (write-bound)
-constexpr double kMacFlopsPerSec = 105e12;          // issued matrix-core flops of the multiply-accumulate
+constexpr double kMacFlopsPerSec = 105e12;          // issued matrix-core flops of the multiply-accumulate (S = 1 form)
+constexpr double kMacBatchSecPerValue = 2.3e-12;    // batch form: per kernel-spectrum value and 16 inputs
 constexpr double kDirectFlopsPerSec = 80e12;        // direct convolution, large contractions
-constexpr double kDirectWriteBytesPerSec = 1.3e12;  // direct convolution, output-bound shapes
+constexpr double kDirectWriteBytesPerSec = 1.7e12;  // direct convolution, output-bound shapes
 constexpr double kLaunchSec = 3.5e-6;
 
 static double fft_seconds(int S, int f, int fo, const int n[3], const int k[3])
@@ -42,8 +43,12 @@ static double fft_seconds(int S, int f, int fo, const int n[3], const int k[3])
     for (auto& p : pass) t += p.bytes / (fast_pass_available(p.N) ? kPassBytesPerSecFast : kPassBytesPerSecGeneric);
     const double fp = (f + 3) / 4 * 4, Mp = (fo + 15) / 16 * 16;
     t += c * zc * Ny * k[0] * fp * Mp / kPrepBytesPerSec;
-    // three real matrix products per complex one, contraction over (input image, x tap), every column
-    t += 6.0 * k[0] * fp * Mp * (double)S * Nx * Ny * zc / kMacFlopsPerSec;
+    // S = 1 form: three real matrix products per complex one, contraction over (input image, x tap), every
+    // column; batch form (taken from k*S = 32 on): cost per kernel-spectrum value, once per 16 inputs
+    if (k[0] * S >= 32 && k[0] <= 12)
+        t += kMacBatchSecPerValue * fp * Mp * Nx * Ny * zc * ((S + 15) / 16);
+    else
+        t += 6.0 * k[0] * fp * Mp * (double)S * Nx * Ny * zc / kMacFlopsPerSec;
     return t;
 }
 

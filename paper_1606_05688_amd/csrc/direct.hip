@@ -56,7 +56,7 @@ __global__ void k_direct_prep(const float* __restrict__ w, float* __restrict__ W
     const int st = q % steps;
     const int i = (int)(q / steps);
     const int j = rt * 16 + r, tap = st * 4 + kk;
-    Wp[idx] = (j < fo && tap < taps) ? w[(size_t)j * wj_stride + (size_t)i * taps + tap] : 0.f;
+    Wp[idx] = (i < f && j < fo && tap < taps) ? w[(size_t)j * wj_stride + (size_t)i * taps + tap] : 0.f;
 }
 
 template <int RTW, int CTW>
@@ -126,44 +126,61 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
                 if (t + 256 * q < tilevol) tile[il * tilevol + t + 256 * q] = v[q];
         }
         __syncthreads();
-        for (int il = 0; il < icn; ++il) {
-            const float* Ab = a.Wp + (((size_t)(ic0 + il) * steps) * a.RT + rt0) * 64 + lane;
-            const float* tl = tile + il * tilevol;
-            for (int st = 0; st < steps; ++st) {
-                const int dl = delta[st * 4 + kk];
-                float av[RTW], bv[CTW];
+        // all steps of the chunk in one flat loop; the kernel values of the next step are requested before the
+        // matrix instructions of the current one (past the last step this reads the following image's values or
+        // the padding behind the bank; they are not used)
+        const float* Ab = a.Wp + (((size_t)ic0 * steps) * a.RT + rt0) * 64 + lane;
+        const int nst = icn * steps;
+        float an[RTW];
 #pragma unroll
-                for (int r = 0; r < RTW; ++r) av[r] = Ab[((size_t)st * a.RT + r) * 64];
+        for (int r = 0; r < RTW; ++r) an[r] = Ab[r * 64];
+        int st = 0, tbase = 0;                       // step inside the image, start of the image's tile
+        for (int g = 0; g < nst; ++g) {
+            float av[RTW], bv[CTW];
 #pragma unroll
-                for (int c = 0; c < CTW; ++c) bv[c] = tl[voxbase[c] + dl];
+            for (int r = 0; r < RTW; ++r) av[r] = an[r];
+            const float* nxt = Ab + (size_t)(g + 1) * a.RT * 64;
 #pragma unroll
-                for (int r = 0; r < RTW; ++r)
+            for (int r = 0; r < RTW; ++r) an[r] = nxt[r * 64];
+            const int dl = delta[st * 4 + kk] + tbase;
 #pragma unroll
-                    for (int c = 0; c < CTW; ++c)
-                        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[c], acc[r][c], 0, 0, 0);
-            }
+            for (int c = 0; c < CTW; ++c) bv[c] = tile[voxbase[c] + dl];
+#pragma unroll
+            for (int r = 0; r < RTW; ++r)
+#pragma unroll
+                for (int c = 0; c < CTW; ++c)
+                    acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[c], acc[r][c], 0, 0, 0);
+            if (++st == steps) { st = 0; tbase += tilevol; }
         }
     }
 
-    // accumulator element e of lane l: output image 16*(rt0+r) + 4*(l/16) + e, voxel l%16 of the column tile
+    // Result through LDS, one row tile (16 output images) at a time, so that stores run along z:
+    // Ol[j<16][pair][z<32] (the tile's voxels of one output image are TX*4 runs of 32 z).  Accumulator element e
+    // of lane l: output image 16*r + 4*(l/16) + e of the block, voxel l%16 of the column tile.
+    float* Ol = lds;
+    constexpr int NPAIR = TX * TY, OP = NPAIR * TZ + 1;     // floats per output image in the tile (+1: banks)
     const size_t ovox = (size_t)d.nox * d.noy * d.noz;
+    const int zl = t & 31;
 #pragma unroll
-    for (int c = 0; c < CTW; ++c) {
-        const int ct = wave * CTW + c;
-        const int zt = ct & 1, pair = ct >> 1;
-        const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zt * 16 + l16;
-        if (X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
-        const size_t vo = ((size_t)X * d.noy + Y) * d.noz + Z;
+    for (int r = 0; r < RTW; ++r) {
+        __syncthreads();
 #pragma unroll
-        for (int r = 0; r < RTW; ++r)
+        for (int c = 0; c < CTW; ++c) {
+            const int ct = wave * CTW + c;
+            const int zt = ct & 1, pair = ct >> 1;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = (rt0 + r) * 16 + 4 * kk + e;
-                if (j >= a.fo) continue;
-                float v = acc[r][c][e] + (a.bias ? a.bias[j] : 0.f);
-                if (a.relu) v = fmaxf(v, 0.f);
-                a.out[((size_t)s * a.fo + j) * ovox + vo] = v;
-            }
+            for (int e = 0; e < 4; ++e) Ol[(4 * kk + e) * OP + pair * TZ + zt * 16 + l16] = acc[r][c][e];
+        }
+        __syncthreads();
+        for (int row = t >> 5; row < 16 * NPAIR; row += 8) {        // one (output image, x, y) run per 32 lanes
+            const int jl = row / NPAIR, pair = row - jl * NPAIR;
+            const int j = (rt0 + r) * 16 + jl;
+            const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zl;
+            if (j >= a.fo || X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
+            float v = Ol[jl * OP + pair * TZ + zl] + (a.bias ? a.bias[j] : 0.f);
+            if (a.relu) v = fmaxf(v, 0.f);
+            a.out[((size_t)s * a.fo + j) * ovox + ((size_t)X * d.noy + Y) * d.noz + Z] = v;
+        }
     }
 }
 
@@ -205,8 +222,11 @@ static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k
     if (IC > f) IC = f;
     P->IC = IC;
     P->lds = 4 * ((size_t)P->T4 + (size_t)IC * tilevol);
+    const size_t out_tile = 4 * (size_t)16 * (TX * DIRECT_TY * DIRECT_TZ + 1);
+    if (out_tile > P->lds) P->lds = out_tile;
     P->wp_floats = (size_t)f * P->T4 * P->RT * 16;
-    P->bytes = (P->wp_floats * 4 + 255) / 256 * 256;
+    // + one step of padding: the kernel requests its kernel values one step ahead
+    P->bytes = ((P->wp_floats + (size_t)P->RT * 64) * 4 + 255) / 256 * 256;
     return ZNNI_OK;
 }
 
@@ -220,6 +240,10 @@ static znni_status launch_direct_t(const DirectArgs& a, const DirectPlan& P, hip
     b.ntz = (P.d.noz + DIRECT_TZ - 1) / DIRECT_TZ;
     const long long tiles = (long long)b.ntx * b.nty * b.ntz;
     if (tiles > 0x7fffffffll) return ZNNI_ERR_SHAPE;
+    if (P.lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)k_direct<RTW, CTW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)P.lds) != hipSuccess)
+        return ZNNI_ERR_HIP;
     k_direct<RTW, CTW><<<dim3((unsigned)tiles, (unsigned)P.S, (unsigned)P.nmblk), dim3(256), P.lds, st>>>(b);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
@@ -255,8 +279,9 @@ znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int
     if (workspace_bytes < P.bytes) return ZNNI_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     float* Wp = (float*)workspace;
-    k_direct_prep<<<dim3((unsigned)((P.wp_floats + 255) / 256)), dim3(256), 0, st>>>(
-        w, Wp, f, fo, P.taps, P.T4, P.RT, (size_t)f * P.taps, P.wp_floats);
+    const size_t wp_all = P.wp_floats + (size_t)P.RT * 64;        // the look-ahead padding is zeroed too
+    k_direct_prep<<<dim3((unsigned)((wp_all + 255) / 256)), dim3(256), 0, st>>>(
+        w, Wp, f, fo, P.taps, P.T4, P.RT, (size_t)f * P.taps, wp_all);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     DirectArgs a;
     a.in = in; a.Wp = Wp; a.bias = bias; a.out = out;
