@@ -233,6 +233,11 @@ def main():
         # above), so the matrix pipes are busy for 3/4 of the algorithmic rate
         roof["issued_TFLOP/s"] = 0.75 * roof["achieved"]
         roof["issued_frac"] = 0.75 * roof["frac"]
+        # the multiply-accumulate proper, without the kernel-spectrum generation that replaces a stored bank:
+        # 8 flops per (input of the batch, input image, output image, bin)
+        mac_only = 8.0 * S * f * fo * (N // 2 + 1) * N * N
+        roof["mac_only_TFLOP/s"] = mac_only / t / 1e12
+        roof["mac_only_frac"] = mac_only / t / 1e12 / MFMA_FP32_PEAK_TFLOPS
     fft_bytes = sum(work[s_][1] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
     fft_ms = sum(stage_ms[s_] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
 
