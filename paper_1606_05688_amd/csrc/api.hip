@@ -289,7 +289,6 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
     znni_status rc;
     const size_t nvox = (size_t)n[0] * n[1] * n[2], kvol = (size_t)k[0] * k[1] * k[2];
     const size_t ovox = (size_t)(n[0] - k[0] + 1) * (n[1] - k[1] + 1) * (n[2] - k[2] + 1);
-    bool tw_done = false;
     for (int s0 = 0; s0 < S; s0 += D.Si) {
         const int Sc = S - s0 < D.Si ? S - s0 : D.Si;
         for (int j0 = 0; j0 < fo; j0 += D.foi) {
@@ -303,7 +302,7 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 for (int q = 0; q < 5; ++q)
                     if (L.sz[q] > D.sz[q]) return ZNNI_ERR_WORKSPACE;
                 place_plan(&L, workspace, D.sz, D.own_yt);
-                if (!tw_done) { ZNNI_DO(launch_twiddles(L, st)); tw_done = true; }
+                ZNNI_DO(launch_twiddles(L, st));      // also zeroes the padding behind this chunk's A
                 ZNNI_DO(launch_kernel_prep(L, w + ((size_t)j0 * f + i0) * kvol, (size_t)f * kvol, st));
                 ZNNI_DO(launch_fwd_z(L, in + ((size_t)s0 * f + i0) * nvox, st));
                 ZNNI_DO(launch_fwd_y(L, st));

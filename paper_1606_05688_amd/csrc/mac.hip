@@ -87,12 +87,6 @@ __global__ __launch_bounds__(256) void k_kprep_y(const float2* __restrict__ A1, 
         if (oy0 + o < N) d[(size_t)o * per] = cscale(acc[o], scale);
 }
 
-__global__ void k_zero(float2* p, size_t count)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = make_float2(0.f, 0.f);
-}
-
 // Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
 // a diagnostic path (flag ZNNI_MAC_REFERENCE) the matrix-core kernel can be compared with.
 __global__ void k_mac_simple(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
@@ -301,10 +295,6 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_str
     k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256),
                 sizeof(float2) * (size_t)d.Ny, st>>>(
         L.A1, L.A, L.twy, d.Ny, d.kx, d.ky, L.fp, L.Mp, per, scale);
-    ZNNI_LAUNCH_CHECK();
-    // the multiply-accumulate reads a little past the last pencil (values multiplied by zero at most)
-    const size_t pad = (size_t)(L.fp + 64) * L.Mp;
-    k_zero<<<dim3((unsigned)((pad + 255) / 256)), dim3(256), 0, st>>>(L.A + (size_t)d.zc * d.Ny * per, pad);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }

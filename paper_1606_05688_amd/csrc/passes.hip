@@ -25,10 +25,18 @@
 
 namespace znni {
 
-__global__ void k_twiddles(float2* tw, int N)
+// The three twiddle tables exp(-2 pi i q / N) of a layer (x, y, z axis) in one launch; blockIdx.y picks the axis.
+// A's zeroed padding behind the last pencil (pad elements at `padp`) is written by the same launch.
+__global__ void k_twiddles(float2* twx, int Nx, float2* twy, int Ny, float2* twz, int Nz, float2* padp, size_t pad)
 {
-    int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q < N) {
+    const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 3) {
+        if (q < pad) padp[q] = make_float2(0.f, 0.f);
+        return;
+    }
+    float2* tw = blockIdx.y == 0 ? twx : (blockIdx.y == 1 ? twy : twz);
+    const int N = blockIdx.y == 0 ? Nx : (blockIdx.y == 1 ? Ny : Nz);
+    if (q < (size_t)N) {
         double s, c;
         sincospi(2.0 * (double)q / (double)N, &s, &c);
         tw[q] = make_float2((float)c, (float)(-s));
@@ -260,11 +268,15 @@ static znni_status allow_lds(const void* fn, size_t bytes)
 znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    k_twiddles<<<dim3((d.Nx + 255) / 256), dim3(256), 0, st>>>(L.twx, d.Nx);
-    ZNNI_LAUNCH_CHECK();
-    k_twiddles<<<dim3((d.Ny + 255) / 256), dim3(256), 0, st>>>(L.twy, d.Ny);
-    ZNNI_LAUNCH_CHECK();
-    k_twiddles<<<dim3((d.Nz + 255) / 256), dim3(256), 0, st>>>(L.twz, d.Nz);
+    // the multiply-accumulate reads a little past A's last pencil (values multiplied by zero at most): that
+    // padding is zeroed here
+    const size_t pad = (size_t)(L.fp + 64) * L.Mp;
+    const size_t per = (size_t)d.kx * L.fp * L.Mp;
+    size_t most = pad;
+    for (int N : {d.Nx, d.Ny, d.Nz})
+        if ((size_t)N > most) most = N;
+    k_twiddles<<<dim3((unsigned)((most + 255) / 256), 4), dim3(256), 0, st>>>(
+        L.twx, d.Nx, L.twy, d.Ny, L.twz, d.Nz, L.A + (size_t)d.zc * d.Ny * per, pad);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
 }
