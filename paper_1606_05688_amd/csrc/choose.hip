@@ -22,7 +22,7 @@ constexpr double kPrepBytesPerSec = 3.0e12;         // kernel preparation (write
 constexpr double kMacFlopsPerSec = 105e12;          // issued matrix-core flops of the multiply-accumulate (S = 1 form)
 constexpr double kMacBatchSecPerValue = 2.3e-12;    // batch form: per kernel-spectrum value and 16 inputs
 constexpr double kDirectFlopsPerSec = 80e12;        // direct convolution, large contractions
-constexpr double kDirectWriteBytesPerSec = 1.7e12;  // direct convolution, output-bound shapes
+constexpr double kDirectWriteBytesPerSec = 2.0e12;  // direct convolution, output-bound shapes
 constexpr double kLaunchSec = 3.5e-6;
 
 static double fft_seconds(int S, int f, int fo, const int n[3], const int k[3])

@@ -11,8 +11,11 @@
 // parallel and over i serially, convolving whole images, here the parallel unit is a tile of output voxels for
 // all output images at once, so every staged input voxel is used by all f' kernels and all taps.
 //
-// Workgroup = 4 waves = one tile of TX x 4 x 32 output voxels (TX = 1 or 2) of one input s, one block of 16*RTW
-// output images.  A wave owns CTW column tiles (16 consecutive z each) and all RTW row tiles.  The contraction
+// Workgroup = 4 waves = one tile of output voxels of one input s, one block of 16*RTW output images.  Two tile
+// shapes: compact, TX x 4 x 32 voxels (TX = 1 or 2), whose staged image tile has the smallest halo, for layers
+// with many input images; and long, 1 x TY x 128 (TY = 1 or 2), for layers with so little arithmetic per output
+// voxel (first layers: one input image) that the output write is the bound, where it makes stores run along whole
+// z rows.  A wave owns CTW column tiles (16 consecutive z each) and all RTW row tiles.  The contraction
 // walks input images in chunks of IC (their tiles, with a halo of k-1, are staged in LDS), and inside an image
 // the taps in steps of four (tap count padded to a multiple of four with zero weights).  Per step a lane reads
 // its tap's offset inside the tile from a small table, one image value per column tile from LDS, and its kernel
@@ -27,7 +30,12 @@ namespace znni {
 typedef float floatx4_d __attribute__((ext_vector_type(4)));
 
 constexpr int DIRECT_NQ = 12;     // staged voxels per thread and image, at most
-constexpr int DIRECT_TY = 4, DIRECT_TZ = 32;
+// tile shape for CTW column tiles per wave (16 or 8 column tiles per workgroup), compact or long
+template <int CTW, bool LONGZ> struct DirectTile {
+    static constexpr int TZ = LONGZ ? 128 : 32, ZT = TZ / 16;
+    static constexpr int TY = LONGZ ? CTW / 2 : 4;
+    static constexpr int TX = LONGZ ? 1 : CTW / 2;
+};
 
 struct DirectArgs {
     const float* in;
@@ -59,10 +67,11 @@ __global__ void k_direct_prep(const float* __restrict__ w, float* __restrict__ W
     Wp[idx] = (i < f && j < fo && tap < taps) ? w[(size_t)j * wj_stride + (size_t)i * taps + tap] : 0.f;
 }
 
-template <int RTW, int CTW>
+template <int RTW, int CTW, bool LONGZ>
 __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
 {
-    constexpr int TX = CTW / 2, TY = DIRECT_TY, TZ = DIRECT_TZ;
+    using TL = DirectTile<CTW, LONGZ>;
+    constexpr int TX = TL::TX, TY = TL::TY, TZ = TL::TZ, ZT = TL::ZT;
     extern __shared__ float lds[];
     int* delta = reinterpret_cast<int*>(lds);        // [T4]
     float* tile = lds + a.T4;                        // [IC][tilevol]
@@ -89,17 +98,20 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
     int goff[DIRECT_NQ];
 #pragma unroll
     for (int q = 0; q < DIRECT_NQ; ++q) {
-        const int e = min(t + 256 * q, tilevol - 1);
-        const int lz = e % TZI, ly = (e / TZI) % TYI, lx = e / (TZI * TYI);
-        const int gx = min(x0 + lx, d.nx - 1), gy = min(y0 + ly, d.ny - 1), gz = min(z0 + lz, d.nz - 1);
-        goff[q] = (gx * d.ny + gy) * d.nz + gz;
+        goff[q] = 0;
+        if (256 * q < tilevol) {                     // uniform: small kernels need only the first few
+            const int e = min(t + 256 * q, tilevol - 1);
+            const int lz = e % TZI, ly = (e / TZI) % TYI, lx = e / (TZI * TYI);
+            const int gx = min(x0 + lx, d.nx - 1), gy = min(y0 + ly, d.ny - 1), gz = min(z0 + lz, d.nz - 1);
+            goff[q] = (gx * d.ny + gy) * d.nz + gz;
+        }
     }
-    // column tiles of this wave: (tx, ty) pair and z half
+    // column tiles of this wave: (tx, ty) pair and 16-voxel piece of the z run
     int voxbase[CTW];
 #pragma unroll
     for (int c = 0; c < CTW; ++c) {
         const int ct = wave * CTW + c;
-        const int zt = ct & 1, pair = ct >> 1;
+        const int zt = ct % ZT, pair = ct / ZT;
         const int vy = pair % TY, vx = pair / TY;
         voxbase[c] = (vx * TYI + vy) * TZI + zt * 16 + l16;
     }
@@ -109,6 +121,15 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
     for (int r = 0; r < RTW; ++r)
 #pragma unroll
         for (int c = 0; c < CTW; ++c) acc[r][c] = floatx4_d{0.f, 0.f, 0.f, 0.f};
+    // biases of the output images this lane's accumulator elements belong to (requested now, used at the end)
+    float bj[RTW][4];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = (rt0 + r) * 16 + 4 * kk + e;
+            bj[r][e] = (a.bias && j < a.fo) ? a.bias[j] : 0.f;
+        }
 
     const size_t nvox = (size_t)d.nx * d.ny * d.nz;
     const int steps = a.T4 >> 2;
@@ -155,31 +176,33 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
     }
 
     // Result through LDS, one row tile (16 output images) at a time, so that stores run along z:
-    // Ol[j<16][pair][z<32] (the tile's voxels of one output image are TX*4 runs of 32 z).  Accumulator element e
-    // of lane l: output image 16*r + 4*(l/16) + e of the block, voxel l%16 of the column tile.
+    // Ol[j<16][pair][z<TZ] (the tile's voxels of one output image are TX*TY runs of TZ voxels).  Accumulator
+    // element e of lane l: output image 16*r + 4*(l/16) + e of the block, voxel l%16 of the column tile.
     float* Ol = lds;
     constexpr int NPAIR = TX * TY, OP = NPAIR * TZ + 1;     // floats per output image in the tile (+1: banks)
     const size_t ovox = (size_t)d.nox * d.noy * d.noz;
-    const int zl = t & 31;
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
         __syncthreads();
 #pragma unroll
         for (int c = 0; c < CTW; ++c) {
             const int ct = wave * CTW + c;
-            const int zt = ct & 1, pair = ct >> 1;
+            const int zt = ct % ZT, pair = ct / ZT;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) Ol[(4 * kk + e) * OP + pair * TZ + zt * 16 + l16] = acc[r][c][e];
+            for (int e = 0; e < 4; ++e) {
+                float v = acc[r][c][e] + bj[r][e];
+                if (a.relu) v = fmaxf(v, 0.f);
+                Ol[(4 * kk + e) * OP + pair * TZ + zt * 16 + l16] = v;
+            }
         }
         __syncthreads();
-        for (int row = t >> 5; row < 16 * NPAIR; row += 8) {        // one (output image, x, y) run per 32 lanes
+        for (int e = t; e < 16 * NPAIR * TZ; e += 256) {            // lanes along z, then (x, y), then output image
+            const int zl = e % TZ, row = e / TZ;
             const int jl = row / NPAIR, pair = row - jl * NPAIR;
             const int j = (rt0 + r) * 16 + jl;
             const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zl;
             if (j >= a.fo || X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
-            float v = Ol[jl * OP + pair * TZ + zl] + (a.bias ? a.bias[j] : 0.f);
-            if (a.relu) v = fmaxf(v, 0.f);
-            a.out[((size_t)s * a.fo + j) * ovox + ((size_t)X * d.noy + Y) * d.noz + Z] = v;
+            a.out[((size_t)s * a.fo + j) * ovox + ((size_t)X * d.noy + Y) * d.noz + Z] = Ol[jl * OP + pair * TZ + zl];
         }
     }
 }
@@ -188,6 +211,7 @@ struct DirectPlan {
     Dims d;
     int S, f, fo;
     int taps, T4, RT, RTW, CTW, nmblk, IC;
+    bool longz;      // tile shape
     size_t lds, wp_floats, bytes;
 };
 
@@ -213,8 +237,12 @@ static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k
     else { P->nmblk = (rt + 3) / 4; P->RTW = (rt + P->nmblk - 1) / P->nmblk; P->CTW = 4; }
     P->RT = P->nmblk * P->RTW;
     if (P->nmblk > 65535) return ZNNI_ERR_SHAPE;
-    const int TX = P->CTW / 2;
-    const long long tilevol = (long long)(TX + k[0] - 1) * (DIRECT_TY + k[1] - 1) * (DIRECT_TZ + k[2] - 1);
+    // long tiles when a voxel of output costs little arithmetic (few input images x taps) and the longer halo
+    // still fits the staging registers
+    const long long vol_long = (long long)k[0] * (P->CTW / 2 + k[1] - 1) * (128 + k[2] - 1);
+    P->longz = (long long)f * P->T4 <= 128 && vol_long <= 256 * DIRECT_NQ;
+    const int TX = P->longz ? 1 : P->CTW / 2, TY = P->longz ? P->CTW / 2 : 4, TZ = P->longz ? 128 : 32;
+    const long long tilevol = (long long)(TX + k[0] - 1) * (TY + k[1] - 1) * (TZ + k[2] - 1);
     if (tilevol > 256 * DIRECT_NQ) return ZNNI_ERR_UNSUPPORTED_SIZE;      // kernel too large for this primitive
     int IC = (int)((48 * 1024 - 4 * P->T4) / (4 * tilevol));
     if (IC < 1) return ZNNI_ERR_UNSUPPORTED_SIZE;
@@ -222,7 +250,7 @@ static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k
     if (IC > f) IC = f;
     P->IC = IC;
     P->lds = 4 * ((size_t)P->T4 + (size_t)IC * tilevol);
-    const size_t out_tile = 4 * (size_t)16 * (TX * DIRECT_TY * DIRECT_TZ + 1);
+    const size_t out_tile = 4 * (size_t)16 * (TX * TY * TZ + 1);
     if (out_tile > P->lds) P->lds = out_tile;
     P->wp_floats = (size_t)f * P->T4 * P->RT * 16;
     // + one step of padding: the kernel requests its kernel values one step ahead
@@ -230,23 +258,29 @@ static znni_status direct_plan(int S, int f, int fo, const int n[3], const int k
     return ZNNI_OK;
 }
 
-template <int RTW, int CTW>
-static znni_status launch_direct_t(const DirectArgs& a, const DirectPlan& P, hipStream_t st)
+template <int RTW, int CTW, bool LONGZ>
+static znni_status launch_direct_s(const DirectArgs& a, const DirectPlan& P, hipStream_t st)
 {
-    constexpr int TX = CTW / 2;
+    using TL = DirectTile<CTW, LONGZ>;
     DirectArgs b = a;
-    b.ntx = (P.d.nox + TX - 1) / TX;
-    b.nty = (P.d.noy + DIRECT_TY - 1) / DIRECT_TY;
-    b.ntz = (P.d.noz + DIRECT_TZ - 1) / DIRECT_TZ;
+    b.ntx = (P.d.nox + TL::TX - 1) / TL::TX;
+    b.nty = (P.d.noy + TL::TY - 1) / TL::TY;
+    b.ntz = (P.d.noz + TL::TZ - 1) / TL::TZ;
     const long long tiles = (long long)b.ntx * b.nty * b.ntz;
     if (tiles > 0x7fffffffll) return ZNNI_ERR_SHAPE;
     if (P.lds > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)k_direct<RTW, CTW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipFuncSetAttribute((const void*)k_direct<RTW, CTW, LONGZ>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)P.lds) != hipSuccess)
         return ZNNI_ERR_HIP;
-    k_direct<RTW, CTW><<<dim3((unsigned)tiles, (unsigned)P.S, (unsigned)P.nmblk), dim3(256), P.lds, st>>>(b);
+    k_direct<RTW, CTW, LONGZ><<<dim3((unsigned)tiles, (unsigned)P.S, (unsigned)P.nmblk), dim3(256), P.lds, st>>>(b);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
+}
+
+template <int RTW, int CTW>
+static znni_status launch_direct_t(const DirectArgs& a, const DirectPlan& P, hipStream_t st)
+{
+    return P.longz ? launch_direct_s<RTW, CTW, true>(a, P, st) : launch_direct_s<RTW, CTW, false>(a, P, st);
 }
 
 }  // namespace znni
