@@ -76,8 +76,9 @@ __device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict_
         _Pragma("unroll") for (int a = 0; a < K; ++a) {                                                   \
             float2 b_[CTW]; float bs_[CTW];                                                               \
             _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                             \
-                b_[c] = make_float2(XC[c].x * T[a][c].x - XC[c].y * T[a][c].y,                            \
-                                    XC[c].x * T[a][c].y + XC[c].y * T[a][c].x);                           \
+                b_[c] = a == 0 ? XC[c] /* T[0] = 1 */                                                     \
+                               : make_float2(XC[c].x * T[a][c].x - XC[c].y * T[a][c].y,                   \
+                                             XC[c].x * T[a][c].y + XC[c].y * T[a][c].x);                  \
                 bs_[c] = b_[c].x + b_[c].y;                                                               \
             }                                                                                             \
             _Pragma("unroll") for (int r = 0; r < RTW; ++r) {                                             \
