@@ -1,5 +1,5 @@
 // passes_fast.hip -- the six transform passes for transform lengths N = R1*R2 with both factors small enough
-// for an in-register DFT (31 lengths from 16 to 512, listed in launch_kind).  Same layouts, pruning and results
+// for an in-register DFT (35 lengths from 8 to 512, listed in launch_kind).  Same layouts, pruning and results
 // as passes.hip.
 //
 // One workgroup transforms a tile of 16 lines (passes along z: 16 pairs of real lines).  Each line is done in
@@ -281,6 +281,10 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
         }
     }
     switch (N) {
+        case 8: return launch_one<2, 4, KIND>(a, grid, st);
+        case 10: return launch_one<5, 2, KIND>(a, grid, st);
+        case 12: return launch_one<3, 4, KIND>(a, grid, st);
+        case 14: return launch_one<7, 2, KIND>(a, grid, st);
         case 16: return launch_one<4, 4, KIND>(a, grid, st);
         case 20: return launch_one<5, 4, KIND>(a, grid, st);
         case 24: return launch_one<6, 4, KIND>(a, grid, st);
@@ -319,6 +323,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
 bool fast_pass_available(int N)
 {
     switch (N) {
+        case 8: case 10: case 12: case 14:
         case 16: case 20: case 24: case 28: case 32: case 36: case 40: case 48: case 56: case 64: case 72: case 80:
         case 96: case 100: case 112: case 120: case 128: case 144: case 160: case 192: case 200: case 224: case 240:
         case 256: case 288: case 320: case 384: case 400: case 448: case 480: case 512:

@@ -135,7 +135,7 @@ def test_anisotropic_delta_kernel_moves_each_axis_by_its_own_offset():
 
 # Every transform length served by the in-register pass kernels, once along each axis (so every pass kind runs at
 # every length), at the length itself and one below it (padded lines).
-FAST_N = [16, 20, 24, 28, 32, 36, 40, 48, 56, 64, 72, 80, 96, 100, 112, 120, 128, 144, 160, 192, 200, 224, 240, 256,
+FAST_N = [8, 10, 12, 14, 16, 20, 24, 28, 32, 36, 40, 48, 56, 64, 72, 80, 96, 100, 112, 120, 128, 144, 160, 192, 200, 224, 240, 256,
           288, 320, 384, 400, 448, 480, 512]
 
 
@@ -152,11 +152,11 @@ def test_in_register_pass_lengths_along_each_axis(oracle, N):
             _check_full(oracle, inp, w, b, True, f"in-register length {N} on axis {axis}, n = {n}")
 
 
-# Lengths left to the generic pass kernels: below 16, and long ones with no in-register length within reach;
+# Lengths left to the generic pass kernels: below 8, and long ones with no in-register length within reach;
 # every radix (2, 3, 4, 5, 7, 8) occurs.
-GENERIC = [(1, 2, 2, (2, 3, 5), (1, 2, 3)), (2, 1, 2, (7, 9, 10), (3, 3, 3)), (1, 2, 1, (12, 10, 6), (2, 5, 4)),
-           (1, 1, 2, (540, 6, 10), (3, 2, 2)), (1, 2, 1, (6, 700, 9), (2, 3, 2)), (1, 1, 1, (10, 6, 1000), (2, 2, 5)),
-           (1, 1, 1, (9, 525, 8), (1, 7, 1))]
+GENERIC = [(1, 2, 2, (2, 3, 5), (1, 2, 3)), (2, 1, 2, (6, 4, 5), (3, 3, 3)), (1, 2, 1, (3, 6, 4), (2, 5, 4)),
+           (1, 1, 2, (540, 6, 10), (3, 2, 2)), (1, 2, 1, (6, 700, 5), (2, 3, 2)), (1, 1, 1, (10, 6, 1000), (2, 2, 5)),
+           (1, 1, 1, (5, 525, 8), (1, 7, 1))]
 
 
 @pytest.mark.parametrize("shape", GENERIC, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
