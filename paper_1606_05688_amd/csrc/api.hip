@@ -272,10 +272,12 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_DO(launch_mac(L, flags, 0, st));
     ZNNI_MARK(ZNNI_STAGE_INV_X);
     ZNNI_DO(launch_inv_x(L, st));
+    const bool fused_yz = fused_inv_yz_available(L);       // then the y stage's time covers both
     ZNNI_MARK(ZNNI_STAGE_INV_Y);
-    ZNNI_DO(launch_inv_y(L, st));
+    if (fused_yz) ZNNI_DO(launch_inv_yz(L, bias, out, flags, st));
+    else ZNNI_DO(launch_inv_y(L, st));
     ZNNI_MARK(ZNNI_STAGE_INV_Z);
-    ZNNI_DO(launch_inv_z(L, bias, out, flags, st));
+    if (!fused_yz) ZNNI_DO(launch_inv_z(L, bias, out, flags, st));
     ZNNI_MARK(ZNNI_NUM_STAGES);
 #undef ZNNI_MARK
     return ZNNI_OK;
@@ -310,8 +312,14 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 ZNNI_DO(launch_mac(L, flags, i0 > 0, st));
             }
             ZNNI_DO(launch_inv_x(L, st));
-            ZNNI_DO(launch_inv_y(L, st));
-            ZNNI_DO(launch_inv_z(L, bias ? bias + j0 : nullptr, out + ((size_t)s0 * fo + j0) * ovox, flags, st));
+            const float* bsub = bias ? bias + j0 : nullptr;
+            float* osub = out + ((size_t)s0 * fo + j0) * ovox;
+            if (fused_inv_yz_available(L)) {
+                ZNNI_DO(launch_inv_yz(L, bsub, osub, flags, st));
+            } else {
+                ZNNI_DO(launch_inv_y(L, st));
+                ZNNI_DO(launch_inv_z(L, bsub, osub, flags, st));
+            }
         }
     }
     return ZNNI_OK;

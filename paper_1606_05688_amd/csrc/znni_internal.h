@@ -68,6 +68,10 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
 
+// Inverse y and z transforms in one kernel when a (oz, oy) plane fits LDS (passes_fused.hip); reads Y2 from buf0.
+bool fused_inv_yz_available(const LayerPlan& L);
+znni_status launch_inv_yz(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
+
 // Two-step in-register passes for selected transform lengths (passes_fast.hip).
 bool fast_pass_available(int N);
 znni_status launch_fast_fwd_z(const LayerPlan& L, const float* in, hipStream_t st);
