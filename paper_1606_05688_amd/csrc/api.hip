@@ -262,12 +262,15 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_DO(launch_twiddles(L, st));
     ZNNI_MARK(ZNNI_STAGE_KERNEL_PREP);
     ZNNI_DO(launch_kernel_prep(L, w, (size_t)L.f * L.d.kx * L.d.ky * L.d.kz, st));
+    const bool fused_zy = fused_fwd_zy_available(L);       // then the z stage's time covers z and y
     ZNNI_MARK(ZNNI_STAGE_FWD_Z);
-    ZNNI_DO(launch_fwd_z(L, in, st));
+    if (fused_zy) ZNNI_DO(launch_fwd_zy(L, in, st));
+    else ZNNI_DO(launch_fwd_z(L, in, st));
     ZNNI_MARK(ZNNI_STAGE_FWD_Y);
-    ZNNI_DO(launch_fwd_y(L, st));
+    if (!fused_zy) ZNNI_DO(launch_fwd_y(L, st));
     ZNNI_MARK(ZNNI_STAGE_FWD_X);
-    ZNNI_DO(launch_fwd_x(L, st));
+    if (fused_zy) ZNNI_DO(launch_fast_fwd_xt(L, st));
+    else ZNNI_DO(launch_fwd_x(L, st));
     ZNNI_MARK(ZNNI_STAGE_MAC);
     ZNNI_DO(launch_mac(L, flags, 0, st));
     ZNNI_MARK(ZNNI_STAGE_INV_X);
@@ -306,9 +309,15 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 place_plan(&L, workspace, D.sz, D.own_yt);
                 ZNNI_DO(launch_twiddles(L, st));      // also zeroes the padding behind this chunk's A
                 ZNNI_DO(launch_kernel_prep(L, w + ((size_t)j0 * f + i0) * kvol, (size_t)f * kvol, st));
-                ZNNI_DO(launch_fwd_z(L, in + ((size_t)s0 * f + i0) * nvox, st));
-                ZNNI_DO(launch_fwd_y(L, st));
-                ZNNI_DO(launch_fwd_x(L, st));
+                const float* isub = in + ((size_t)s0 * f + i0) * nvox;
+                if (fused_fwd_zy_available(L)) {
+                    ZNNI_DO(launch_fwd_zy(L, isub, st));
+                    ZNNI_DO(launch_fast_fwd_xt(L, st));
+                } else {
+                    ZNNI_DO(launch_fwd_z(L, isub, st));
+                    ZNNI_DO(launch_fwd_y(L, st));
+                    ZNNI_DO(launch_fwd_x(L, st));
+                }
                 ZNNI_DO(launch_mac(L, flags, i0 > 0, st));
             }
             ZNNI_DO(launch_inv_x(L, st));

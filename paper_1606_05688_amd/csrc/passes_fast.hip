@@ -16,7 +16,10 @@
 
 namespace znni {
 
-enum PassKind { P_FWD_Z, P_FWD_Y, P_FWD_X, P_INV_X, P_INV_Y, P_INV_Z };
+// P_FWD_XT: the forward x pass reading the layout the fused z+y kernel leaves, X2'[img][x][oz][oy]: the 16 lines
+// of a tile (neighbouring oy) are adjacent elements of every x row, so the pass loads 128-byte runs with the line
+// index fastest across lanes (a transposing load instead of the transposing store of the pass before it).
+enum PassKind { P_FWD_Z, P_FWD_Y, P_FWD_X, P_INV_X, P_INV_Y, P_INV_Z, P_FWD_XT };
 
 struct PassArgs {
     const void* src;
@@ -44,12 +47,16 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
 
     // ---- where the 16 lines of this tile start, how far apart they are, how many exist, how long they are
     const float2* src = nullptr;      // complex passes
-    size_t lpitch = 0;
+    size_t lpitch = 0, epitch = 1;    // from line to line, from element to element
     int nvalid = 0, lin = N;
     if constexpr (KIND == P_FWD_Y) {          // tile: 16 x of one (img, oz); lines along y in X1
         const int x0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * d.nx + x0) * zc + oz) * d.ldy;
         lpitch = (size_t)zc * d.ldy; nvalid = min(16, d.nx - x0); lin = d.ny;
+    } else if constexpr (KIND == P_FWD_XT) {  // tile: 16 oy of one (img, oz); element x of line l at x*epitch + l
+        const int oy0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + ((size_t)img * d.nx * zc + oz) * d.Ny + oy0;
+        lpitch = 1; epitch = (size_t)zc * d.Ny; nvalid = min(16, d.Ny - oy0); lin = d.nx;
     } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
         const int oy0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.ldx;
@@ -65,7 +72,8 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     }
 
     // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
-    const int ja = t % R2, la = t / R2;       // la < 16 only for t < 16*R2
+    // step A thread = (line la, sample offset ja); samples fastest across lanes, except for the transposing load
+    const int ja = KIND == P_FWD_XT ? t >> 4 : t % R2, la = KIND == P_FWD_XT ? t & 15 : t / R2;
     const bool in_a = t < 16 * R2;
     float2 v[R1];
     // Every load is issued unconditionally from a clamped (always valid, so finite) address and multiplied by
@@ -95,7 +103,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
                 const float mk = e < lin ? ml : 0.f;
-                const float2 x = ls[min(e, lin - 1)];
+                const float2 x = ls[(size_t)min(e, lin - 1) * epitch];
                 v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y) ? -(x.y * mk) : x.y * mk);
             }
         }
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int r = 0; r < R2; ++r) buf[lb * P + q + R1 * r] = u[r];
         }
         __syncthreads();
-        if constexpr (KIND == P_FWD_X) {
+        if constexpr (KIND == P_FWD_X || KIND == P_FWD_XT) {
             // Xt[oz][oy0 + l][img][ox]: whole lines, contiguous
             const int oy0 = tile * 16;
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
@@ -327,6 +335,12 @@ znni_status launch_fast_fwd_x(const LayerPlan& L, hipStream_t st)
     const Dims& d = L.d;
     return launch_kind<P_FWD_X>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimg),
                                 dim3((d.Ny + 15) / 16, d.zc, L.nimg), st);
+}
+znni_status launch_fast_fwd_xt(const LayerPlan& L, hipStream_t st)
+{
+    const Dims& d = L.d;
+    return launch_kind<P_FWD_XT>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimg),
+                                 dim3((d.Ny + 15) / 16, d.zc, L.nimg), st);
 }
 znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
 {

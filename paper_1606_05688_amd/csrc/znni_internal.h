@@ -68,6 +68,12 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
 
+// Forward z and y transforms in one kernel when a (oz, oy) plane fits LDS (passes_fused.hip): in -> X2' in buf1,
+// laid out [img][x][oz][oy]; launch_fast_fwd_xt is the x pass that reads it (buf1 -> Xt in buf0).
+bool fused_fwd_zy_available(const LayerPlan& L);
+znni_status launch_fwd_zy(const LayerPlan& L, const float* in, hipStream_t st);
+znni_status launch_fast_fwd_xt(const LayerPlan& L, hipStream_t st);
+
 // Inverse y and z transforms in one kernel when a (oz, oy) plane fits LDS (passes_fused.hip); reads Y2 from buf0.
 bool fused_inv_yz_available(const LayerPlan& L);
 znni_status launch_inv_yz(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
