@@ -71,9 +71,13 @@ def cpu_baseline(layer, workloads):
     t0 = time.perf_counter()
     out = ref.conv3d(inp, w, b, relu=layer.relu)
     dt = time.perf_counter() - t0
+    # the same oracle on one thread, on one output image of the same crop (a few seconds)
+    t0 = time.perf_counter()
+    out1 = ref.conv3d(inp[:1], w[:1], b[:1], relu=layer.relu, nthreads=1)
+    dt1 = time.perf_counter() - t0
     return {
         "value": out.size / dt, "unit": "output voxels/s", "cores": min(threads, layer.S * fo_s),
-        "kind": "oracle",
+        "kind": "oracle", "value_1_thread": out1.size / dt1,
         "sample": f"fp64 direct convolution of a {n_s}^3 crop, S={layer.S}, f={layer.f}, {fo_s} of {layer.fo} "
                   f"output images, k={layer.k} ({out.size} output voxels in {dt:.1f} s; cost per output voxel "
                   f"is uniform: f*k^3 multiply-adds)",
@@ -147,8 +151,8 @@ def bench_sublayers(torch, B, layer, inp, w, bias, out, full_ms):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",

@@ -5,24 +5,24 @@
 //     Yt[j][col] = sum_{(i,a)} A(a,i,j) * ( T[a*ox(col)] * X[i][col] ).
 //
 // With K fixed, one loop iteration covers one group of four input images (i/4) and all K taps, fully unrolled:
-// the K twiddles of a lane's columns live in registers for the whole kernel, the image fragment is read from LDS
-// once per iteration instead of once per step, there is no per-step bookkeeping, and the A operands of the next
-// iteration are requested, into the other of two register sets, before the current iteration's arithmetic.
+// the K twiddles of a lane's columns live in registers for the whole kernel, the image fragment is read once per
+// iteration instead of once per step (straight from global memory: no LDS, no barrier), there is no per-step
+// bookkeeping, and the A operands and image fragment of the next iteration are requested, into the other of two
+// register sets, before the current iteration's arithmetic.
 // Every instruction a wave issues costs matrix-core time on this hardware, so per 9*K (or 18*K) matrix
 // instructions the iteration carries only the 5 vector instructions per step and column tile that form the
 // right operand (complex product and real+imaginary sum), RTW additions per step for the left operand's
-// real+imaginary sum, the A loads and one LDS read.
+// real+imaginary sum, and the A and image loads.
 #include "mac_common.h"
 
 namespace znni {
 
 template <int RTW, int CTW, int K>
-__device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict__ Xt, const float2* __restrict__ A,
+__device__ __forceinline__ void mac_k_body(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                            float2* __restrict__ Yt, const float2* __restrict__ twg, int N, int S,
-                                           int f, int fo, int fp, int Mp, int FC, int col0, int ncolblk, int pencil,
+                                           int f, int fo, int fp, int Mp, int col0, int ncolblk, int pencil,
                                            int sub, int accumulate)
 {
-    constexpr int NW = 64 * CTW;            // Xs: [FC][NW]
     MacWork w;
     mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, K, fp, Mp, col0, ncolblk, pencil, sub);
 
@@ -51,27 +51,33 @@ __device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict_
     const size_t jstride = (size_t)4 * Mp;              // one step (one tap of one group of four images)
     const size_t istride = (size_t)K * jstride;         // one iteration
 
-    for (int ic0 = 0; ic0 < fp; ic0 += FC) {
-        const int fc = min(FC, fp - ic0);               // multiple of 4
-        __syncthreads();
-        mac_stage_x<NW>(Xs, w, ic0, fc, f, N);
-        __syncthreads();
-
-        const int nI = fc >> 2;
-        const float2* Ab = w.Ap + ((size_t)(ic0 >> 2) * K * 4 + w.kk) * Mp + w.m0 + w.l16;
-        const float2* Xw = Xs + w.kk * NW + w.cw0 + w.l16;
+    {
+        // The image fragment of a lane -- rows 4*I4 + kk, its own CTW columns -- comes straight from global
+        // memory, one iteration ahead like the A operands: no wave reads another wave's columns, so there is
+        // nothing to share through LDS, and without the staging a workgroup starts its arithmetic after one
+        // memory round trip and never meets a barrier.  Rows beyond f are clamped to the last one (their A
+        // operands are zero); columns beyond Ct are clamped too and never stored.
+        const int nI = fp >> 2;
+        const float2* Ab = w.Ap + (size_t)w.kk * Mp + w.m0 + w.l16;
+        const float2* Xc[CTW];
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) {
+            const int col = min(w.colbase + w.cw0 + c * 16 + w.l16, w.Ct - 1);
+            const int sI = col / N, ox = col - sI * N;
+            Xc[c] = w.Xp + (size_t)sI * f * N + ox;
+        }
 
         // One iteration: image rows 4*I4..4*I4+3, all K taps, A operands in CUR.  First the A operands of the
         // following iteration are requested into NXT (past the last iteration this reads the next pencil or the
         // zeroed padding behind A; the values are never used) and the image fragment of the following
-        // iteration is read into XN.
+        // iteration into XN.
 #define ZNNI_MAC_ITER(CUR, NXT, XC, XN, I4)                                                               \
     {                                                                                                     \
         const float2* an_ = Ab + (size_t)((I4) + 1) * istride;                                            \
         _Pragma("unroll") for (int a = 0; a < K; ++a)                                                     \
             _Pragma("unroll") for (int r = 0; r < RTW; ++r) NXT[a][r] = an_[(size_t)a * jstride + r * 16];\
-        const float2* xr_ = Xw + min((I4) + 1, nI - 1) * 4 * NW;                                          \
-        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XN[c] = xr_[c * 16];                              \
+        const size_t xo_ = (size_t)min(4 * min((I4) + 1, nI - 1) + w.kk, f - 1) * N;                      \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) XN[c] = Xc[c][xo_];                               \
         __builtin_amdgcn_sched_barrier(0);                                                                \
         _Pragma("unroll") for (int a = 0; a < K; ++a) {                                                   \
             float2 b_[CTW]; float bs_[CTW];                                                               \
@@ -97,8 +103,11 @@ __device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict_
         for (int a = 0; a < K; ++a)
 #pragma unroll
             for (int r = 0; r < RTW; ++r) ga[a][r] = Ab[(size_t)a * jstride + r * 16];
+        {
+            const size_t xo0 = (size_t)min(w.kk, f - 1) * N;
 #pragma unroll
-        for (int c = 0; c < CTW; ++c) xa[c] = Xw[c * 16];
+            for (int c = 0; c < CTW; ++c) xa[c] = Xc[c][xo0];
+        }
         int i4 = 0;
         for (; i4 + 2 <= nI; i4 += 2) {
             ZNNI_MAC_ITER(ga, gb, xa, xb, i4)
@@ -115,19 +124,18 @@ __device__ __forceinline__ void mac_k_body(float2* Xs, const float2* __restrict_
 template <int RTW, int K, bool WIDE>
 __global__ __launch_bounds__(256, (RTW * (WIDE ? 2 : 1) * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
 void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
-                  const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int FC, int n2, int n1,
+                  const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int n2, int n1,
                   int col1, int nmblk, int npencils, int accumulate)
 {
-    extern __shared__ float2 Xs[];
     int pencil, sub;
     if (!mac_block((n2 + n1) * nmblk, npencils, pencil, sub)) return;
     if constexpr (WIDE) {
         if (sub < n2 * nmblk) {
-            mac_k_body<RTW, 2, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, 0, n2, pencil, sub, accumulate);
+            mac_k_body<RTW, 2, K>(Xt, A, Yt, twg, N, S, f, fo, fp, Mp, 0, n2, pencil, sub, accumulate);
             return;
         }
     }
-    mac_k_body<RTW, 1, K>(Xs, Xt, A, Yt, twg, N, S, f, fo, fp, Mp, FC, col1, n1, pencil, sub - n2 * nmblk,
+    mac_k_body<RTW, 1, K>(Xt, A, Yt, twg, N, S, f, fo, fp, Mp, col1, n1, pencil, sub - n2 * nmblk,
                           accumulate);
 }
 
@@ -136,16 +144,11 @@ bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
 template <int RTW, int K, bool WIDE>
 static znni_status launch_k(const LayerPlan& L, int n2, int n1, int accumulate, hipStream_t st)
 {
-    const void* fn = (const void*)k_mac_mfma_k<RTW, K, WIDE>;
-    const size_t lds = sizeof(float2) * (size_t)L.mac_FC * (WIDE ? 128 : 64);
-    if (lds > 48 * 1024 &&
-        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return ZNNI_ERR_HIP;
     const int npencils = L.d.zc * L.d.Ny;
     const int per_pencil = (n2 + n1) * L.mac_nmblk;
     const long long blocks = (long long)((npencils + 7) / 8) * per_pencil * 8;
-    k_mac_mfma_k<RTW, K, WIDE><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(
-        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, L.mac_FC, n2, n1, L.mac_n2 * 128,
+    k_mac_mfma_k<RTW, K, WIDE><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
+        L.buf0, L.A, L.Yt, L.twx, L.d.Nx, L.S, L.f, L.fo, L.fp, L.Mp, n2, n1, L.mac_n2 * 128,
         L.mac_nmblk, npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
