@@ -350,7 +350,7 @@ znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipSt
     if (((flags & ZNNI_MAC_BATCH) && mac_batch_available(L)) ||
         (!(flags & ZNNI_MAC_SINGLE) && mac_batch_preferred(L)))
         return launch_mac_batch(L, accumulate, st);
-    if (mac_k_available(L.d.kx)) return launch_mac_k(L, accumulate, st);
+    if (mac_k_available(L)) return launch_mac_k(L, accumulate, st);
     if (L.mac_n2 > 0) {
         switch (L.mac_RTW) {
             case 1: return launch_mac_t<1, true>(L, accumulate, st);

@@ -127,8 +127,8 @@ bool mac_batch_available(const LayerPlan& L);      // up to 12 taps along x
 bool mac_batch_preferred(const LayerPlan& L);
 znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st);
 
-// mac_k.hip: kernels with the number of kernel taps known at compile time (k = 3, 5, 7).
-bool mac_k_available(int k);
+// mac_k.hip: kernels with the number of kernel taps known at compile time (2 to 9).
+bool mac_k_available(const LayerPlan& L);
 znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st);
 
 }  // namespace znni

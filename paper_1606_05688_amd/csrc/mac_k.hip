@@ -25,6 +25,8 @@ __device__ __forceinline__ void mac_k_body(const float2* __restrict__ Xt, const 
 {
     MacWork w;
     mac_decode<RTW, CTW>(w, Xt, A, Yt, N, S, f, fo, K, fp, Mp, col0, ncolblk, pencil, sub);
+    // (A wave whose columns are all padding still runs: letting it return early was measured slower, because the
+    // waves of a workgroup sit on fixed SIMDs and the padding waves' SIMDs then idle while the others work.)
 
     // twiddles of this lane's columns, one per tap
     float2 T[K][CTW];
@@ -139,7 +141,13 @@ void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, f
                           accumulate);
 }
 
-bool mac_k_available(int k) { return k == 3 || k == 5 || k == 7; }
+// 2 to 9 taps (the kernel sizes of the benchmarked networks); the tallest row block with 9 taps would
+// spill registers and is left to the general kernel
+bool mac_k_available(const LayerPlan& L)
+{
+    const int k = L.d.kx;
+    return k >= 2 && k <= 9 && !(k == 9 && L.mac_RTW == 5);
+}
 
 template <int RTW, int K, bool WIDE>
 static znni_status launch_k(const LayerPlan& L, int n2, int n1, int accumulate, hipStream_t st)
@@ -184,9 +192,14 @@ static znni_status launch_tiles(const LayerPlan& L, int accumulate, hipStream_t 
 znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     switch (L.d.kx) {
+        case 2: return launch_tiles<2>(L, accumulate, st);
         case 3: return launch_tiles<3>(L, accumulate, st);
+        case 4: return launch_tiles<4>(L, accumulate, st);
         case 5: return launch_tiles<5>(L, accumulate, st);
+        case 6: return launch_tiles<6>(L, accumulate, st);
         case 7: return launch_tiles<7>(L, accumulate, st);
+        case 8: return launch_tiles<8>(L, accumulate, st);
+        case 9: return launch_tiles<9>(L, accumulate, st);
     }
     return ZNNI_ERR_SHAPE;
 }
