@@ -19,6 +19,25 @@ struct FftPlan {
     int radix[kMaxStages];    // product of radix[0..nstages) == N
 };
 
+// Streaming (non-temporal) global accesses for tensors that are written once by one kernel and read once by the
+// next and are far larger than the caches.  Measured on the 320^3 workload: the middle four transform passes
+// gain 2 to 7 % with both, the first pass only with streaming stores (its input lines are touched by several
+// instructions and must stay cached), the last only with streaming loads (its unaligned output rows are merged
+// in L2 when stored normally).
+typedef float znni_v2f __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void st_stream(float2* p, float2 v)
+{
+    znni_v2f w; w.x = v.x; w.y = v.y;
+    __builtin_nontemporal_store(w, reinterpret_cast<znni_v2f*>(p));
+}
+__device__ __forceinline__ void st_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ float2 ld_stream(const float2* p)
+{
+    const znni_v2f w = __builtin_nontemporal_load(reinterpret_cast<const znni_v2f*>(p));
+    return make_float2(w.x, w.y);
+}
+__device__ __forceinline__ float ld_stream(const float* p) { return __builtin_nontemporal_load(p); }
+
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
 __device__ __forceinline__ float2 cmul(float2 a, float2 b)

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void k_kprep_y(const float2* __restrict__ A1, 
     float2* d = A + ((size_t)oz * N + oy0) * per + (size_t)(((i >> 2) * k + a) * 4 + (i & 3)) * Mp + j;
 #pragma unroll
     for (int o = 0; o < KPREP_OY; ++o)
-        if (oy0 + o < N) d[(size_t)o * per] = cscale(acc[o], scale);
+        if (oy0 + o < N) st_stream(d + (size_t)o * per, cscale(acc[o], scale));
 }
 
 // Plain multiply-accumulate, one workgroup per (oz, oy) pencil, one thread per ox.  Slow and simple; kept as
