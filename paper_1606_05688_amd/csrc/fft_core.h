@@ -37,6 +37,18 @@ __device__ __forceinline__ float2 ld_stream(const float2* p)
     return make_float2(w.x, w.y);
 }
 __device__ __forceinline__ float ld_stream(const float* p) { return __builtin_nontemporal_load(p); }
+template <bool STREAM, typename T>
+__device__ __forceinline__ T ldg(const T* p)
+{
+    if constexpr (STREAM) return ld_stream(p);
+    else return *p;
+}
+template <bool STREAM, typename T>
+__device__ __forceinline__ void stg(T* p, T v)
+{
+    if constexpr (STREAM) st_stream(p, v);
+    else *p = v;
+}
 
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }

@@ -39,6 +39,10 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     extern __shared__ float2 lds[];
     float2* tws = lds;
     float2* buf = lds + N;
+    // Streaming accesses only where a lane group moves whole 128-byte lines per instruction (R2 = 16 samples of a
+    // line in step A): with shorter runs a cache line is shared by several instructions and must stay cached
+    // (measured: lengths 48, 100 and 120 lose up to 40 % on the x passes with streaming loads).
+    constexpr bool STREAM = (R2 % 16 == 0);
     const int t = threadIdx.x;
     for (int q = t; q < N; q += NTH) tws[q] = a.tw[q];
 
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
                 const float mk = e < lin ? ml : 0.f;
-                const float2 x = ld_stream(ls + (size_t)min(e, lin - 1) * epitch);
+                const float2 x = ldg<STREAM && KIND != P_FWD_XT>(ls + (size_t)min(e, lin - 1) * epitch);
                 v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y) ? -(x.y * mk) : x.y * mk);
             }
         }
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         for (int it = 0; it < ITER; ++it) {       // all requests first ...
             const int e = min(t + it * NTH, 32 * ZC - 1);
             const int r = e & 31, o = e >> 5;
-            raw[it] = ld_stream(chunk + (size_t)o * d.ldo + min(r, rows - 1));
+            raw[it] = ldg<STREAM>(chunk + (size_t)o * d.ldo + min(r, rows - 1));
         }
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {       // ... then the LDS stores, one row of ZC values per line
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         if (q < R1 && lb < nvalid) {
             float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * N * d.ldx + tile * 16 + lb;
 #pragma unroll
-            for (int r = 0; r < R2; ++r) st_stream(o + (size_t)(q + R1 * r) * d.ldx, u[r]);
+            for (int r = 0; r < R2; ++r) stg<STREAM>(o + (size_t)(q + R1 * r) * d.ldx, u[r]);
         }
     } else if constexpr (KIND == P_INV_X) {
         // Y2[imgo][oz][xo][oy0 + lb], xo = element - (kx-1) in [0, nox)
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
 #pragma unroll
             for (int r = 0; r < R2; ++r) {
                 const int xo = q + R1 * r - (d.kx - 1);
-                if (xo >= 0 && xo < d.nox) st_stream(o + (size_t)xo * d.Ny, cconj(u[r]));
+                if (xo >= 0 && xo < d.nox) stg<STREAM>(o + (size_t)xo * d.Ny, cconj(u[r]));
             }
         }
     } else {
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             const int oy0 = tile * 16;
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
                 float2* o = (float2*)a.dst + (((size_t)mid * d.Ny + oy0 + l) * a.nimg + img) * N;
-                for (int e = t % 64; e < N; e += 64) st_stream(o + e, buf[l * P + e]);
+                for (int e = t % 64; e < N; e += 64) stg<STREAM>(o + e, buf[l * P + e]);
             }
         } else if constexpr (KIND == P_INV_Y) {
             // Y1[imgo][xo0 + l][oz][yo]: the valid part of each line, contiguous
@@ -195,7 +199,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
                 float2* o = (float2*)a.dst + (((size_t)img * d.nox + xo0 + l) * zc + mid) * d.ldo;
                 const float2* row = buf + l * P + (d.ky - 1);
-                for (int e = t % 64; e < d.noy; e += 64) st_stream(o + e, cconj(row[e]));
+                for (int e = t % 64; e < d.noy; e += 64) stg<STREAM>(o + e, cconj(row[e]));
             }
         } else if constexpr (KIND == P_FWD_Z) {
             // untangle the two real lines and store X1[img][x][oz][y0 + ll], ll < 32 fastest across lanes
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
                 const float2* row = buf + (ll >> 1) * P;
                 for (int oz = t >> 5; oz < zc; oz += NTH / 32) {
                     const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
-                    st_stream(o + (size_t)oz * d.ldy + ll, (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
+                    stg<STREAM>(o + (size_t)oz * d.ldy + ll, (ll & 1) ? cscale(mul_mi(csub(z1, z2)), 0.5f)
                                                                : cscale(cadd(z1, z2), 0.5f));
                 }
             }
