@@ -26,7 +26,7 @@ VALU_FP32_UNPACKED_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by
 # what the same counters report for the library's plain copy kernel; see profiles/.  Keyed by (workload, stage).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5_320c_f48x48_k5", "mac"): 17.85e9,      # 11.52 GB fetched + 6.33 GB written
+    ("cfg5_320c_f48x48_k5", "mac"): 17.84e9,      # 11.51 GB fetched + 6.33 GB written
 }
 
 
