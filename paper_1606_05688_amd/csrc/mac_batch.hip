@@ -15,8 +15,10 @@
 // images are walked in chunks of 8.  Per chunk: the image values are staged in LDS ([ox][i][s]); each wave runs
 // step 1 for two of the eight images and parks real and imaginary parts in LDS ([ox][i][j], the order step 2
 // reads its left operand in); after a barrier each wave runs step 2 for four of the sixteen ox.
-// Complex products are three real ones (P1 = ar br, P2 = ai bi, P3 = (ar+ai)(br+bi)).  The result leaves through
-// LDS so that stores run along ox.
+// Complex products are three real ones (P1 = ar br, P2 = ai bi, P3 = (ar+ai)(br+bi)).  When at most 8 inputs
+// make up the whole batch, step 2 instead puts real and imaginary parts side by side in the 16 columns of the
+// tile: [Yr | Yi] += Wr [Xr | Xi] + Wi [-Xi | Xr], two full products instead of three half-empty ones, and no
+// combination afterwards.  The result leaves through LDS so that stores run along ox.
 #include "mac_common.h"
 
 namespace znni {
@@ -26,6 +28,7 @@ constexpr int MB_WP = 132;            // floats between consecutive ox in the Wt
 constexpr int MB_XP = 129;            // float2 between consecutive ox in the image array (8*16 + padding)
 constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
 
+template <bool PACKED>
 __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
@@ -95,6 +98,9 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     floatx4 p1[4], p2[4], p3[4];                     // step-2 accumulators: ox = ox0 + 4*wave + q
 #pragma unroll
     for (int q = 0; q < 4; ++q) { p1[q] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[q] = p1[q]; p3[q] = p1[q]; }
+    // PACKED (at most 8 inputs; the host picks the kernel): columns 0..7 of the tile carry the real parts of
+    // s = 0..7, columns 8..15 the imaginary parts; p1 collects the Wr products, p2 the Wi products, p3 is unused
+    const bool lowcol = l16 < 8;
 
     for (int ic0 = 0; ic0 < f; ic0 += MB_IC) {
         __syncthreads();                             // the previous chunk has been consumed
@@ -132,29 +138,56 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
         __syncthreads();
         if (ic0 + MB_IC < f) request(ic0 + MB_IC);   // in flight during step 2
         // ---- step 2 for ox = ox0 + 4*wave + q: left operand Wt[j = l16][i = 4*st + kk], right Xt[i][s = l16]
+        // all operands of the chunk first, then the products: the matrix instructions of one bin wait for nothing
+        float wr_[4][MB_IC / 4], wi_[4][MB_IC / 4];
+        float2 x_[4][MB_IC / 4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int oxl = 4 * wave + q;
 #pragma unroll
             for (int st = 0; st < MB_IC / 4; ++st) {
                 const int o = st * 64 + lane;
-                const float wr = Wr[oxl * MB_WP + o], wi = Wi[oxl * MB_WP + o];
-                const float2 x = Xl[oxl * MB_XP + o];
-                p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
-                p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
-                p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
+                wr_[q][st] = Wr[oxl * MB_WP + o];
+                wi_[q][st] = Wi[oxl * MB_WP + o];
+                x_[q][st] = Xl[oxl * MB_XP + (PACKED ? (o & ~8) : o)];   // packed: input s = l16 & 7
+            }
+        }
+#pragma unroll
+        for (int st = 0; st < MB_IC / 4; ++st) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float wr = wr_[q][st], wi = wi_[q][st];
+                const float2 x = x_[q][st];
+                if constexpr (PACKED) {
+                    p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, lowcol ? x.x : x.y, p1[q], 0, 0, 0);
+                    p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, lowcol ? -x.y : x.x, p2[q], 0, 0, 0);
+                } else {
+                    p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
+                    p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
+                    p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
+                }
             }
         }
     }
     // ---- result through LDS: Ol[j][s][ox]; accumulator element e of lane: j = 4*kk + e, s = l16
     __syncthreads();
     float2* Ol = reinterpret_cast<float2*>(lds);
+    if constexpr (PACKED) {                          // this lane holds one component of input s = l16 & 7
+        float* Of = lds;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            Ol[((4 * kk + e) * 16 + l16) * MB_OP + 4 * wave + q] =
-                make_float2(p1[q][e] - p2[q][e], p3[q][e] - p1[q][e] - p2[q][e]);
+            for (int e = 0; e < 4; ++e)
+                Of[2 * (((4 * kk + e) * 16 + (l16 & 7)) * MB_OP + 4 * wave + q) + (lowcol ? 0 : 1)] =
+                    p1[q][e] + p2[q][e];
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                Ol[((4 * kk + e) * 16 + l16) * MB_OP + 4 * wave + q] =
+                    make_float2(p1[q][e] - p2[q][e], p3[q][e] - p1[q][e] - p2[q][e]);
+    }
     __syncthreads();
     for (int e = t; e < 16 * 16 * 16; e += 256) {
         const int oxl = e & 15, s = (e >> 4) & 15, j = e >> 8;
@@ -188,9 +221,14 @@ znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
     const int npencils = L.d.zc * L.d.Ny;
     const long long blocks = (long long)((npencils + 7) / 8) * noxt * njt * nsc * 8;
     if (blocks > 0x7fffffffll) return ZNNI_ERR_SHAPE;
-    k_mac_batch<<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo,
-                                                                  L.d.kx, L.fp, L.Mp, noxt, njt, nsc, npencils,
-                                                                  accumulate);
+    if (L.S <= 8)
+        k_mac_batch<true><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f,
+                                                                            L.fo, L.d.kx, L.fp, L.Mp, noxt, njt, nsc,
+                                                                            npencils, accumulate);
+    else
+        k_mac_batch<false><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f,
+                                                                             L.fo, L.d.kx, L.fp, L.Mp, noxt, njt, nsc,
+                                                                             npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
