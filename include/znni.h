@@ -52,7 +52,10 @@ enum {
                                     /* rounding, much slower)                                                   */
     ZNNI_MAC_SINGLE = 4u,           /* force the multiply-accumulate form built for S = 1 (work grows with k*S) */
     ZNNI_MAC_BATCH = 8u             /* force the form built for batches (kernel spectrum generated once per    */
-                                    /* bin, shared by the S inputs); without either flag the library picks     */
+                                    /* bin, shared by the S inputs; ignored where that form does not exist:    */
+                                    /* more than 12 kernel taps, or up to 8 inputs with an odd transform       */
+                                    /* length along x); without                                                 */
+                                    /* either flag the library picks                                            */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */

@@ -12,13 +12,21 @@
 //   step 2, per bin ox:          Yt[j][s]   += sum_i Wt[j][i] * Xt[i][s]       (16 j  x  8 i per chunk  x  16 s)
 //
 // Workgroup = 4 waves = one pencil x 16 consecutive ox x 16 output images x up to 16 inputs of the batch; input
-// images are walked in chunks of 8.  Per chunk: the image values are staged in LDS ([ox][i][s]); each wave runs
-// step 1 for two of the eight images and parks real and imaginary parts in LDS ([ox][i][j], the order step 2
-// reads its left operand in); after a barrier each wave runs step 2 for four of the sixteen ox.
-// Complex products are three real ones (P1 = ar br, P2 = ai bi, P3 = (ar+ai)(br+bi)).  When at most 8 inputs
-// make up the whole batch, step 2 instead puts real and imaginary parts side by side in the 16 columns of the
-// tile: [Yr | Yi] += Wr [Xr | Xi] + Wi [-Xi | Xr], two full products instead of three half-empty ones, and no
-// combination afterwards.  The result leaves through LDS so that stores run along ox.
+// images are walked in chunks of 8.  Per chunk each wave runs step 1 for two of the eight images and parks real
+// and imaginary parts in LDS ([ox][i][j], the order step 2 reads its left operand in); after a barrier each wave
+// runs step 2 for four of the sixteen ox.  Step 1's complex products are three real ones (P1 = ar br, P2 = ai bi,
+// P3 = (ar+ai)(br+bi)).  The result leaves through LDS so that stores run along ox.
+//
+// Two kernels, by batch size:
+//  * k_mac_batch (more than 8 inputs): the image values of a chunk are staged in LDS ([ox][i][s]) with coalesced
+//    loads; step 2 uses three real products per complex one.
+//  * k_mac_batch8 (at most 8 inputs): real and imaginary parts sit side by side in the 16 columns of the step-2
+//    tile, [Yr | Yi] += Wr [Xr | Xi] + Wi [-Xi | Xr]: two full products instead of three half-empty ones and no
+//    combination afterwards.  Lane (i, s) needs Xt[i][s] at the wave's four consecutive ox, 32 contiguous bytes,
+//    and loads them straight from global memory one chunk ahead (lanes 8 columns apart share an address), so the
+//    image values never touch LDS; the Wt arrays are double-buffered and one barrier per chunk is left.  (With
+//    16 different inputs per wave the same direct loads touch 64 cache lines per instruction and were measured
+//    13 % slower than staging, so the larger batches keep the staging kernel.)
 #include "mac_common.h"
 
 namespace znni {
@@ -27,8 +35,8 @@ constexpr int MB_IC = 8;              // input images per chunk
 constexpr int MB_WP = 132;            // floats between consecutive ox in the Wt arrays (8*16 + padding)
 constexpr int MB_XP = 129;            // float2 between consecutive ox in the image array (8*16 + padding)
 constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
+constexpr int MB_WB = 2 * 16 * MB_WP; // floats per Wt buffer (real array, then imaginary array)
 
-template <bool PACKED>
 __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
@@ -98,9 +106,6 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     floatx4 p1[4], p2[4], p3[4];                     // step-2 accumulators: ox = ox0 + 4*wave + q
 #pragma unroll
     for (int q = 0; q < 4; ++q) { p1[q] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[q] = p1[q]; p3[q] = p1[q]; }
-    // PACKED (at most 8 inputs; the host picks the kernel): columns 0..7 of the tile carry the real parts of
-    // s = 0..7, columns 8..15 the imaginary parts; p1 collects the Wr products, p2 the Wi products, p3 is unused
-    const bool lowcol = l16 < 8;
 
     for (int ic0 = 0; ic0 < f; ic0 += MB_IC) {
         __syncthreads();                             // the previous chunk has been consumed
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
                 const int o = st * 64 + lane;
                 wr_[q][st] = Wr[oxl * MB_WP + o];
                 wi_[q][st] = Wi[oxl * MB_WP + o];
-                x_[q][st] = Xl[oxl * MB_XP + (PACKED ? (o & ~8) : o)];   // packed: input s = l16 & 7
+                x_[q][st] = Xl[oxl * MB_XP + o];
             }
         }
 #pragma unroll
@@ -158,10 +163,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
             for (int q = 0; q < 4; ++q) {
                 const float wr = wr_[q][st], wi = wi_[q][st];
                 const float2 x = x_[q][st];
-                if constexpr (PACKED) {
-                    p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, lowcol ? x.x : x.y, p1[q], 0, 0, 0);
-                    p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, lowcol ? -x.y : x.x, p2[q], 0, 0, 0);
-                } else {
+                {
                     p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
                     p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
                     p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
@@ -172,15 +174,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     // ---- result through LDS: Ol[j][s][ox]; accumulator element e of lane: j = 4*kk + e, s = l16
     __syncthreads();
     float2* Ol = reinterpret_cast<float2*>(lds);
-    if constexpr (PACKED) {                          // this lane holds one component of input s = l16 & 7
-        float* Of = lds;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                Of[2 * (((4 * kk + e) * 16 + (l16 & 7)) * MB_OP + 4 * wave + q) + (lowcol ? 0 : 1)] =
-                    p1[q][e] + p2[q][e];
-    } else {
+    {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -204,9 +198,170 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     }
 }
 
+__global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ Xt, const float2* __restrict__ A,
+                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
+                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
+                                                    int nsc, int npencils, int accumulate)
+{
+    // LDS: two Wt buffers, each two float arrays (real, imaginary) [16 ox][MB_WP]; the output tile
+    // (float2 [16 j][16 s][MB_OP]) reuses the same memory after the last chunk.
+    extern __shared__ float lds[];
+
+    int pencil, sub;
+    if (!mac_block(noxt * njt * nsc, npencils, pencil, sub)) return;
+    const int oxt = sub % noxt, jt = (sub / noxt) % njt, sc = sub / (noxt * njt);
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63, l16 = lane & 15, kk = lane >> 4;
+    const int ox0 = oxt * 16, j0 = jt * 16, s0 = sc * 16;
+    const float2* Xp = Xt + (size_t)pencil * S * f * N;
+    const float2* Ap = A + (size_t)pencil * k * fp * Mp;
+    float2* Yp = Yt + (size_t)pencil * S * fo * N;
+
+    // step-1 right operand of this lane: T[a = 4*st + kk][ox = ox0 + l16], zero beyond the last tap
+    const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
+    float tr[3], ti[3], ts[3];
+    {
+        const int ox = min(ox0 + l16, N - 1);
+#pragma unroll
+        for (int st = 0; st < 3; ++st) {
+            const int a = 4 * st + kk;
+            float2 v = make_float2(0.f, 0.f);
+            if (a < k) v = twg[(int)(((long long)a * ox) % N)];
+            tr[st] = v.x; ti[st] = v.y; ts[st] = v.x + v.y;
+        }
+    }
+
+    // step-2 right operand of this lane: input s = l16 & 7 (columns 0..7 of the tile carry the real parts of
+    // s = 0..7, columns 8..15 the imaginary parts), image row ic0 + 4*st + kk, bins ox0 + 4*wave + 0..3 as two
+    // 16-byte pairs.  Inputs, image rows and bins beyond the tensor are clamped to valid ones: their
+    // products land in tile columns, or meet zero Wt values, or belong to bins that are never stored.
+    const bool lowcol = l16 < 8;
+    const float2* xs = Xp + (size_t)min(s0 + (l16 & 7), S - 1) * f * N;
+    const int oxa = min(ox0 + 4 * wave, N - 2), oxb = min(ox0 + 4 * wave + 2, N - 2);     // N is even
+    auto request_x = [&](float4 (&x)[MB_IC / 4][2], int ic0) {
+#pragma unroll
+        for (int st = 0; st < MB_IC / 4; ++st) {
+            const float2* row = xs + (size_t)min(ic0 + 4 * st + kk, f - 1) * N;
+            x[st][0] = *reinterpret_cast<const float4*>(row + oxa);
+            x[st][1] = *reinterpret_cast<const float4*>(row + oxb);
+        }
+    };
+    // step-1 left operands of this wave's two images
+    const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
+    float2 areg[2][3];
+    auto request_a = [&](int ic0) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ic = min(ic0 + 2 * wave + h, fp - 1);
+            const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
+#pragma unroll
+            for (int st = 0; st < 3; ++st)           // surplus taps meet a zero twiddle
+                areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
+        }
+    };
+
+    floatx4 p1[4], p2[4];                            // step-2 accumulators, ox = ox0 + 4*wave + q: p1 collects the
+#pragma unroll                                       // Wr products, p2 the Wi products
+    for (int q = 0; q < 4; ++q) { p1[q] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[q] = p1[q]; }
+
+    const int nch = (f + MB_IC - 1) / MB_IC;
+    float4 xA[MB_IC / 4][2], xB[MB_IC / 4][2];
+    request_a(0);
+    request_x(xA, 0);
+
+    // One chunk: XC holds its image values; those of the next chunk are requested into XN first.
+#define ZNNI_MB_CHUNK(C, XC, XN)                                                                          \
+    {                                                                                                     \
+        const int ic0 = (C) * MB_IC;                                                                      \
+        float* Wr = lds + ((C) & 1) * MB_WB;                                                              \
+        float* Wi = Wr + 16 * MB_WP;                                                                      \
+        if ((C) + 1 < nch) request_x(XN, ic0 + MB_IC);                                                    \
+        /* ---- step 1 for images ic0 + 2*wave, ic0 + 2*wave + 1 */                                       \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                   \
+            const int il = 2 * wave + h;                                                                  \
+            const float mi = ic0 + il < fp ? 1.f : 0.f;                                                   \
+            floatx4 q1 = floatx4{0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;                                   \
+            _Pragma("unroll") for (int st = 0; st < 3; ++st) {                                            \
+                if (st < ksteps) { /* uniform */                                                          \
+                    const float ar = areg[h][st].x * mi, ai = areg[h][st].y * mi;                         \
+                    q1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar, tr[st], q1, 0, 0, 0);                   \
+                    q2 = __builtin_amdgcn_mfma_f32_16x16x4f32(ai, ti[st], q2, 0, 0, 0);                   \
+                    q3 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar + ai, ts[st], q3, 0, 0, 0);              \
+                }                                                                                         \
+            }                                                                                             \
+            /* element e of lane: output image j0 + 4*kk + e, bin ox0 + l16 */                            \
+            float4 wr, wi;                                                                                \
+            wr.x = q1[0] - q2[0]; wr.y = q1[1] - q2[1]; wr.z = q1[2] - q2[2]; wr.w = q1[3] - q2[3];       \
+            wi.x = q3[0] - q1[0] - q2[0]; wi.y = q3[1] - q1[1] - q2[1];                                   \
+            wi.z = q3[2] - q1[2] - q2[2]; wi.w = q3[3] - q1[3] - q2[3];                                   \
+            const int o = l16 * MB_WP + il * 16 + 4 * kk;                                                 \
+            *reinterpret_cast<float4*>(Wr + o) = wr;                                                      \
+            *reinterpret_cast<float4*>(Wi + o) = wi;                                                      \
+        }                                                                                                 \
+        if ((C) + 1 < nch) request_a(ic0 + MB_IC);   /* in flight during step 2 */                        \
+        /* The only barrier of the chunk.  This buffer was last read in step 2 of chunk C-2, which every */\
+        /* wave finished before it arrived at the barrier of chunk C-1.                                  */\
+        __syncthreads();                                                                                  \
+        /* ---- step 2 for ox = ox0 + 4*wave + q: left operand Wt[j = l16][i = 4*st + kk]; all operands */ \
+        /* first, then the products                                                                      */\
+        float wr_[4][MB_IC / 4], wi_[4][MB_IC / 4];                                                       \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
+            const int oxl = 4 * wave + q;                                                                 \
+            _Pragma("unroll") for (int st = 0; st < MB_IC / 4; ++st) {                                    \
+                wr_[q][st] = Wr[oxl * MB_WP + st * 64 + lane];                                            \
+                wi_[q][st] = Wi[oxl * MB_WP + st * 64 + lane];                                            \
+            }                                                                                             \
+        }                                                                                                 \
+        _Pragma("unroll") for (int st = 0; st < MB_IC / 4; ++st) {                                        \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                               \
+                const float wr = wr_[q][st], wi = wi_[q][st];                                             \
+                const float4 xp = XC[st][q >> 1];                                                         \
+                const float2 x = (q & 1) ? make_float2(xp.z, xp.w) : make_float2(xp.x, xp.y);             \
+                p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, lowcol ? x.x : x.y, p1[q], 0, 0, 0);     \
+                p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, lowcol ? -x.y : x.x, p2[q], 0, 0, 0);    \
+            }                                                                                             \
+        }                                                                                                 \
+    }
+    int c = 0;
+    for (; c + 2 <= nch; c += 2) {
+        ZNNI_MB_CHUNK(c, xA, xB)
+        ZNNI_MB_CHUNK(c + 1, xB, xA)
+    }
+    if (c < nch) ZNNI_MB_CHUNK(c, xA, xB)
+#undef ZNNI_MB_CHUNK
+
+    // ---- result through LDS: Ol[j][s][ox]; accumulator element e of lane: j = 4*kk + e, one component (real for
+    // columns 0..7, imaginary for 8..15) of input s = l16 & 7
+    __syncthreads();
+    float2* Ol = reinterpret_cast<float2*>(lds);
+    {
+        float* Of = lds;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                Of[2 * (((4 * kk + e) * 16 + (l16 & 7)) * MB_OP + 4 * wave + q) + (lowcol ? 0 : 1)] =
+                    p1[q][e] + p2[q][e];
+    }
+    __syncthreads();
+    for (int e = t; e < 16 * 16 * 16; e += 256) {
+        const int oxl = e & 15, s = (e >> 4) & 15, j = e >> 8;
+        const int gs = s0 + s, gj = j0 + j, gox = ox0 + oxl;
+        if (gs >= S || gj >= fo || gox >= N) continue;
+        float2 v = Ol[(j * 16 + s) * MB_OP + oxl];
+        float2* dst = Yp + ((size_t)gs * fo + gj) * N + gox;
+        if (accumulate) {
+            const float2 old = *dst;
+            v.x += old.x;
+            v.y += old.y;
+        }
+        *dst = v;
+    }
+}
+
 // The batch form generates each kernel-spectrum value once per bin (cost independent of S) and pays one 16-column
 // matrix product per 16 inputs; the single-input form pays matrix-core work proportional to k*S.
-bool mac_batch_available(const LayerPlan& L) { return L.d.kx <= 12; }
+// (up to 8 inputs: even lengths along x only, the image values are fetched in 16-byte pairs of neighbouring bins)
+bool mac_batch_available(const LayerPlan& L) { return L.d.kx <= 12 && (L.S > 8 || (L.d.Nx & 1) == 0); }
 // Measured on MI355X (32 -> 32 and 80 -> 80 images, 32^3 .. 128^3): the batch form wins from about k*S = 32 on.
 bool mac_batch_preferred(const LayerPlan& L) { return mac_batch_available(L) && L.d.kx * L.S >= 32; }
 
@@ -214,21 +369,17 @@ znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     if (!mac_batch_available(L)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const int N = L.d.Nx;
-    const size_t lds_main = sizeof(float) * 2 * 16 * MB_WP + sizeof(float2) * 16 * MB_XP;
+    const size_t lds_main = L.S <= 8 ? sizeof(float) * 2 * MB_WB
+                                     : sizeof(float) * MB_WB + sizeof(float2) * 16 * MB_XP;
     const size_t lds_out = sizeof(float2) * 16 * 16 * MB_OP;
     const size_t lds = lds_main > lds_out ? lds_main : lds_out;
     const int noxt = (N + 15) / 16, njt = (L.fo + 15) / 16, nsc = (L.S + 15) / 16;
     const int npencils = L.d.zc * L.d.Ny;
     const long long blocks = (long long)((npencils + 7) / 8) * noxt * njt * nsc * 8;
     if (blocks > 0x7fffffffll) return ZNNI_ERR_SHAPE;
-    if (L.S <= 8)
-        k_mac_batch<true><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f,
-                                                                            L.fo, L.d.kx, L.fp, L.Mp, noxt, njt, nsc,
-                                                                            npencils, accumulate);
-    else
-        k_mac_batch<false><<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f,
-                                                                             L.fo, L.d.kx, L.fp, L.Mp, noxt, njt, nsc,
-                                                                             npencils, accumulate);
+    auto* kernel = L.S <= 8 ? k_mac_batch8 : k_mac_batch;
+    kernel<<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo, L.d.kx, L.fp,
+                                                           L.Mp, noxt, njt, nsc, npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
