@@ -259,9 +259,11 @@ def test_matrix_core_mac_agrees_with_plain_mac(oracle, shape):
 
 # (S, f, fo, n, k): batch sizes below, at and above the 4-input groups, more than 16 inputs (two chunks), taps with
 # and without compile-time kernels, transform sizes that are not multiples of the 16-bin tile, one and several
-# rounds of output-image groups, image blocks that need two LDS fills.
+# rounds of output-image groups, image blocks that need two LDS fills; an odd transform length with at most 8
+# inputs (no batch kernel there: the flag is ignored) and with more; a last bin tile of 8 and of 10 bins with a
+# partial second chunk of input images.
 BATCH = [(2, 3, 5, 16, 3), (4, 4, 4, 20, 5), (5, 2, 3, 24, 2), (8, 32, 32, 16, 7), (9, 6, 40, 18, 4), (20, 3, 7, 16, 3),
-         (3, 70, 9, 16, 1), (8, 5, 70, 32, 6)]
+         (3, 70, 9, 16, 1), (8, 5, 70, 32, 6), (4, 3, 3, 5, 2), (12, 3, 3, 5, 2), (8, 9, 5, 22, 5), (7, 12, 4, 10, 3)]
 
 
 @pytest.mark.parametrize("shape", BATCH, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
