@@ -123,8 +123,21 @@ __device__ __forceinline__ void mac_k_body(const float2* __restrict__ Xt, const 
 
 // One launch for all of a layer's column blocks: pieces [0, n2*nmblk) of a pencil are 128-wide blocks, the rest
 // 64-wide blocks behind them.  WIDE = false leaves the 128-wide path out (row blocks too tall for it).
+// Workgroups per CU the register allocation is held to.  Two instantiations sit a few registers above an
+// occupancy step and are pushed below it: three row tiles x 5 taps, wide (171 -> 168 registers, 12 bytes of
+// scratch, three waves per SIMD instead of two: 4 % faster on the 320-wide workload) and three row tiles x 2 taps,
+// wide (129 -> 128, no scratch).  Wherever the step is further away the spills cost more than the occupancy
+// gains (tried: 5 tiles x 5 taps, 5 x 3, 3 x 3 wide: 30 % slower).
 template <int RTW, int K, bool WIDE>
-__global__ __launch_bounds__(256, (RTW * (WIDE ? 2 : 1) * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2)
+constexpr int mac_k_min_blocks()
+{
+    if (RTW == 3 && K == 5 && WIDE) return 3;
+    if (RTW == 3 && K == 2 && WIDE) return 4;
+    return (RTW * (WIDE ? 2 : 1) * (K > 5 ? 2 : 1)) <= 3 ? 3 : 2;
+}
+
+template <int RTW, int K, bool WIDE>
+__global__ __launch_bounds__(256, (mac_k_min_blocks<RTW, K, WIDE>()))
 void k_mac_mfma_k(const float2* __restrict__ Xt, const float2* __restrict__ A, float2* __restrict__ Yt,
                   const float2* __restrict__ twg, int N, int S, int f, int fo, int fp, int Mp, int n2, int n1,
                   int col1, int nmblk, int npencils, int accumulate)
