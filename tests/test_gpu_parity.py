@@ -103,6 +103,10 @@ ANISO = [
     (1, 3, 3, (30, 1, 25), (3, 1, 5)),
     (1, 2, 2, (28, 36, 1), (5, 3, 1)),
     (1, 48, 20, (16, 20, 24), (5, 3, 3)),     # many input images: several chunks / row blocks in the multiply-accumulate
+    (2, 3, 2, (20, 62, 60), (3, 5, 3)),       # y and z share one transform length (64) with different extents and taps:
+                                              # the fused z+y kernels, both sides
+    (1, 2, 3, (81, 30, 31), (3, 2, 5)),       # ... with a generic x length (81): fused inverse, separate forward
+    (3, 2, 2, (24, 111, 109), (2, 3, 4)),     # ... at the longest fused length (112), odd extents
 ]
 
 
