@@ -7,8 +7,9 @@
 //   transform route:  bytes moved by the six transform passes and the kernel preparation over the HBM rate those
 //                     kernels reach (lower for transform lengths served by the generic pass kernel), plus the
 //                     multiply-accumulate's matrix-core work, plus a fixed cost for its dozen launches;
-//   direct route:     its matrix-core work over the rate the kernel reaches, or the output write, whichever is
-//                     larger, plus two launches.
+//   direct route:     its matrix-core work over the rate the kernel reaches (lower for windows of fewer than 27
+//                     taps, where staging the image tiles weighs more per product) plus the output write, plus
+//                     two launches.
 //
 // The model only has to rank the two; it is not used for anything else.
 #include "znni_internal.h"
@@ -16,13 +17,14 @@
 namespace znni {
 
 // measured rates (MI355X)
-constexpr double kPassBytesPerSecFast = 5.0e12;     // in-register pass kernels
+constexpr double kPassBytesPerSecFast = 5.3e12;     // in-register pass kernels
 constexpr double kPassBytesPerSecGeneric = 2.0e12;  // generic LDS pass kernels
-constexpr double kPrepBytesPerSec = 3.0e12;         // kernel preparation (write-bound)
-constexpr double kMacFlopsPerSec = 105e12;          // issued matrix-core flops of the multiply-accumulate (S = 1 form)
-constexpr double kMacBatchSecPerValue = 2.3e-12;    // batch form: per kernel-spectrum value and 16 inputs
-constexpr double kDirectFlopsPerSec = 80e12;        // direct convolution, large contractions
-constexpr double kDirectWriteBytesPerSec = 2.0e12;  // direct convolution, output-bound shapes
+constexpr double kPrepBytesPerSec = 4.5e12;         // kernel preparation (write-bound)
+constexpr double kMacFlopsPerSec = 110e12;          // issued matrix-core flops of the multiply-accumulate (S = 1 form)
+constexpr double kMacBatchSecPerValue = 2.1e-12;    // batch form: per kernel-spectrum value and 16 inputs
+constexpr double kDirectFlopsPerSec = 80e12;        // direct convolution, windows of 27 taps and more
+constexpr double kDirectFlopsPerSecSmall = 60e12;   // ... of fewer taps
+constexpr double kDirectWriteBytesPerSec = 2.0e12;  // direct convolution, output write
 constexpr double kLaunchSec = 3.5e-6;
 
 static double fft_seconds(int S, int f, int fo, const int n[3], const int k[3])
@@ -58,8 +60,8 @@ static double direct_seconds(int S, int f, int fo, const int n[3], const int k[3
     const double taps4 = (k[0] * k[1] * k[2] + 3) / 4 * 4, Mp = (fo + 15) / 16 * 16;
     const double flops = 2.0 * S * f * taps4 * Mp * ovox;
     const double wr = 4.0 * S * fo * ovox;
-    const double a = flops / kDirectFlopsPerSec, b = wr / kDirectWriteBytesPerSec;
-    return (a > b ? a : b) + 2 * kLaunchSec;
+    const double rate = k[0] * k[1] * k[2] >= 27 ? kDirectFlopsPerSec : kDirectFlopsPerSecSmall;
+    return flops / rate + wr / kDirectWriteBytesPerSec + 2 * kLaunchSec;
 }
 
 }  // namespace znni

@@ -189,9 +189,11 @@ def test_sublayer_division_follows_the_stated_preference():
 
 
 def test_primitive_choice_follows_kernel_size_and_image_count():
-    # first layers (one input image) and 2^3 kernels go direct; large kernels and wide layers go through transforms
+    # first layers (one or a few input images) and narrow layers with 2^3 kernels go direct; large kernels and wide
+    # layers go through transforms
     assert B.znni_conv3d_choose(1, 1, 48, 128, 3)[0] == "direct"
-    assert B.znni_conv3d_choose(1, 80, 80, 100, 2)[0] == "direct"
+    assert B.znni_conv3d_choose(1, 8, 80, 200, 2)[0] == "direct"
+    assert B.znni_conv3d_choose(1, 16, 16, 128, 2)[0] == "direct"
     assert B.znni_conv3d_choose(1, 48, 48, 320, 5)[0] == "fft"
     assert B.znni_conv3d_choose(8, 32, 32, 64, 7)[0] == "fft"
     assert B.znni_conv3d_choose(1, 40, 40, 128, 3)[0] == "fft"
