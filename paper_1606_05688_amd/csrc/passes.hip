@@ -18,7 +18,7 @@
 //   X2  [img][oz][oy<Ny][x<nx (ldx)]        after y      so that every row starts on a 128-byte boundary)
 //   Xt  [oz][oy][img][ox<Nx]                after x   ("pencil" order: one (oz,oy) pair holds all images)
 //   Yt  [oz][oy][imgo][ox<Nx]               accumulated output spectra
-//   Y2  [imgo][oz][xo<nox][oy<Ny]           after inverse x, cropped to valid x
+//   Y2  [imgo][oz][xo<nox][oy<Ny]           after inverse x, cropped to valid x (row pitch ldn)
 //   Y1  [imgo][xo][oz<zc][yo<noy (ldo)]     after inverse y, cropped to valid y
 //   out [imgo][xo][yo][zo<noz]              real, after inverse z + bias + transfer function
 #include "znni_internal.h"
@@ -165,10 +165,10 @@ __global__ void k_inv_x(const float2* __restrict__ Yt, float2* __restrict__ Y2, 
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = Y2 + ((size_t)img * zc + oz) * nox * Ny + oy0;
+    float2* dst = Y2 + ((size_t)img * zc + oz) * nox * d.ldn + oy0;
     for (int e = threadIdx.x; e < nox * TL; e += blockDim.x) {
         const int l = e & (TL - 1), xo = e / TL;
-        if (l < nvalid) dst[(size_t)xo * Ny + l] = cconj(r[l * L.ld + xo + d.kx - 1]);
+        if (l < nvalid) dst[(size_t)xo * d.ldn + l] = cconj(r[l * L.ld + xo + d.kx - 1]);
     }
 }
 
@@ -183,11 +183,11 @@ __global__ void k_inv_y(const float2* __restrict__ Y2, float2* __restrict__ Y1, 
     const int xo0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
     const int zc = d.zc, nox = d.nox, noy = d.noy;
     const int nvalid = min(TL, nox - xo0);
-    const float2* src = Y2 + (((size_t)img * zc + oz) * nox + xo0) * N;
+    const float2* src = Y2 + (((size_t)img * zc + oz) * nox + xo0) * d.ldn;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, oy = e - l * N;
         float2 v = make_float2(0.f, 0.f);
-        if (l < nvalid) v = cconj(src[(size_t)l * N + oy]);
+        if (l < nvalid) v = cconj(src[(size_t)l * d.ldn + oy]);
         L.a[l * L.ld + oy] = v;
     }
     __syncthreads();

@@ -72,8 +72,8 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         lpitch = (size_t)a.nimg * N; nvalid = min(16, d.Ny - oy0);
     } else if constexpr (KIND == P_INV_Y) {   // tile: 16 xo of one (imgo, oz); lines along oy, adjacent in Y2
         const int xo0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.nox + xo0) * N;
-        lpitch = N; nvalid = min(16, d.nox - xo0);
+        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.nox + xo0) * d.ldn;
+        lpitch = d.ldn; nvalid = min(16, d.nox - xo0);
     }
 
     // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
@@ -171,11 +171,11 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     } else if constexpr (KIND == P_INV_X) {
         // Y2[imgo][oz][xo][oy0 + lb], xo = element - (kx-1) in [0, nox)
         if (q < R1 && lb < nvalid) {
-            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * d.nox * d.Ny + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * d.nox * d.ldn + tile * 16 + lb;
 #pragma unroll
             for (int r = 0; r < R2; ++r) {
                 const int xo = q + R1 * r - (d.kx - 1);
-                if (xo >= 0 && xo < d.nox) stg<STREAM>(o + (size_t)xo * d.Ny, cconj(u[r]));
+                if (xo >= 0 && xo < d.nox) stg<STREAM>(o + (size_t)xo * d.ldn, cconj(u[r]));
             }
         }
     } else {

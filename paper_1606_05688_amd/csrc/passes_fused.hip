@@ -61,7 +61,7 @@ __global__ __launch_bounds__(1024) void k_inv_yz(FusedArgs a)
 
     // ---- inverse along y: the rows oz of the plane, conj . forward . conj
     if (in_a) {
-        const float2* row = a.src + (((size_t)img * ZC + la) * nox + xo) * N;
+        const float2* row = a.src + (((size_t)img * ZC + la) * nox + xo) * d.ldn;
 #pragma unroll
         for (int m = 0; m < R1; ++m) {
             const float2 x = row[ja + R2 * m];

@@ -17,6 +17,7 @@ struct Dims {
     int zc;               // Nz/2 + 1 bins along the halved axis
     int nox, noy, noz;    // output n - k + 1
     int ldy, ldx, ldo;    // row strides of X1, X2 and Y1: ny, nx and noy rounded up to a multiple of 16 complex
+    int ldn;              // row stride of Y2: Ny, rounded up likewise where Ny is not a multiple of 8
                           // (128 bytes)
 };
 
