@@ -101,7 +101,7 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
  *   w         [fo][f][k][k][k]         device, read-only
  *   bias      [fo] device, read-only, or NULL for zero bias
  *   out       [S][fo][n-k+1]^3         device, written (every element)
- *   flags     bitwise OR of ZNNI_RELU / ZNNI_MAC_REFERENCE, or 0
+ *   flags     bitwise OR of ZNNI_RELU and at most one of ZNNI_MAC_REFERENCE / ZNNI_MAC_SINGLE / ZNNI_MAC_BATCH, or 0
  *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
  *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
  *             not overlap in time.
@@ -113,7 +113,9 @@ znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k,
 /*
  * Same computation, with a HIP event recorded on `stream` between stages; synchronises `stream` before
  * returning and writes the elapsed milliseconds of each stage to stage_ms[ZNNI_NUM_STAGES] (HOST pointer).
- * Meant for measurement: creates and destroys its events on every call.
+ * Meant for measurement: creates and destroys its events on every call.  For small images the z and y
+ * transforms of each side run as one kernel; its time is then reported under ZNNI_STAGE_FWD_Z (forward) and
+ * ZNNI_STAGE_INV_Y (inverse), and ZNNI_STAGE_FWD_Y / ZNNI_STAGE_INV_Z read about zero.
  */
 znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
                                     const float* in, const float* w, const float* bias, float* out,
