@@ -81,6 +81,7 @@ __device__ __forceinline__ void mac_k_body(const float2* __restrict__ Xt, const 
         const size_t xo_ = (size_t)min(4 * min((I4) + 1, nI - 1) + w.kk, f - 1) * N;                      \
         _Pragma("unroll") for (int c = 0; c < CTW; ++c) XN[c] = Xc[c][xo_];                               \
         __builtin_amdgcn_sched_barrier(0);                                                                \
+        __builtin_amdgcn_iglp_opt(0); /* interleave matrix and other instructions: 3-8 % for tall row blocks */ \
         _Pragma("unroll") for (int a = 0; a < K; ++a) {                                                   \
             float2 b_[CTW]; float bs_[CTW];                                                               \
             _Pragma("unroll") for (int c = 0; c < CTW; ++c) {                                             \
