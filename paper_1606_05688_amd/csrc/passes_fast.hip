@@ -16,7 +16,6 @@
 
 namespace znni {
 
-
 // P_FWD_XT: the forward x pass reading the layout the fused z+y kernel leaves, X2'[img][x][oz][oy]: the 16 lines
 // of a tile (neighbouring oy) are adjacent elements of every x row, so the pass loads 128-byte runs with the line
 // index fastest across lanes (a transposing load instead of the transposing store of the pass before it).
