@@ -243,6 +243,37 @@ def test_runs_on_a_side_stream_and_profile_matches():
     assert set(ms) == set(B.STAGES) and all(v >= 0 for v in ms.values())
 
 
+@pytest.mark.parametrize("shape", [(1, 8, 8, 64, 5), (8, 4, 4, 22, 3), (1, 3, 2, 118, 3)],
+                         ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_layer_call_can_be_captured_in_a_graph_and_replayed(shape):
+    """The layer call only enqueues kernels on the caller's stream (no allocation, no synchronisation, no memset),
+    so a launch-bound small layer can be captured once and replayed.  Every replay, with eager work and
+    synchronisations in between and new input values each time, must equal the eager result bit for bit.
+    (The last shape uses the fused kernels with more than 48 KB of LDS, whose launch sets a function attribute.)"""
+    S, f, fo, n, k = shape
+    d = torch.device("cuda:0")
+    inp, w, b = (torch.from_numpy(t).to(d) for t in _rand(31 + n, S, f, fo, n, k))
+    ws_g, ws_e = B.alloc_workspace(S, f, fo, n, k, d), B.alloc_workspace(S, f, fo, n, k, d)
+    out_g = torch.empty((S, fo) + (n - k + 1,) * 3, device=d)
+    out_e = torch.empty_like(out_g)
+    _say(f"[graph] {shape}: warm-up")
+    B.znni_conv3d_fft(inp, w, b, relu=True, out=out_g, workspace=ws_g)        # first-use set-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    _say(f"[graph] {shape}: capture")
+    with torch.cuda.graph(g):
+        B.znni_conv3d_fft(inp, w, b, relu=True, out=out_g, workspace=ws_g)
+    for rep in range(4):
+        inp.uniform_(-1, 1)                        # eager work between replays
+        out_g.fill_(float("nan"))
+        B.znni_conv3d_fft(inp, w, b, relu=True, out=out_e, workspace=ws_e)
+        torch.cuda.synchronize()
+        _say(f"[graph] {shape}: replay {rep}")
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay {rep} differs from the eager call"
+
+
 @pytest.mark.parametrize("shape", [(1, 2, 3, 16, 3), (2, 5, 7, 24, 5), (1, 48, 48, 40, 5), (3, 6, 20, 20, 2),
                                    (1, 80, 100, 16, 3)],
                          ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
