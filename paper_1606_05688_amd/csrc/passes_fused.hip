@@ -254,16 +254,20 @@ __global__ __launch_bounds__(1024) void k_fwd_zy(FusedFwdArgs a)
 }
 
 // ------------------------------------------------------------------------------------------- host side
-struct FusedShape { int QP, RP, nth; size_t lds; };
+struct FusedShape { int R1, R2, QP, RP, nth; size_t lds; };
 
-// The in-register split of each supported length: R1 x R2 as in the separate passes, except that R2 stays at 8
-// for the long lengths (fewer, fatter threads would not cover a plane's lines in one round).
-static bool fused_split(int N, int* R1, int* R2)
+// The in-register split of each supported length, measured best per length (32 -> 32 images, batches of 1.5 GB):
+// mostly R1 x 8 -- fewer, fatter threads than the separate passes use would not cover a plane's lines in one
+// round --, with the squarer splits 6 x 6, 8 x 10 and 8 x 12 10 to 15 % ahead at 36, 80 and 96.  At 120 the inverse
+// kernel runs two workgroups per CU with 10 x 12 (12 threads per line) and only one with 15 x 8: 40 % faster; the
+// forward kernel is 12 % slower with it and keeps 15 x 8.
+static bool fused_split(int N, bool forward, int* R1, int* R2)
 {
     static const int tab[][3] = {{8, 2, 4},    {10, 5, 2},  {12, 3, 4},  {14, 7, 2},  {16, 4, 4},  {20, 5, 4},
-                                 {24, 6, 4},   {28, 7, 4},  {32, 4, 8},  {36, 9, 4},  {40, 5, 8},  {48, 6, 8},
-                                 {56, 7, 8},   {64, 8, 8},  {72, 9, 8},  {80, 10, 8}, {96, 12, 8}, {100, 10, 10},
-                                 {112, 14, 8}, {120, 15, 8}};
+                                 {24, 6, 4},   {28, 7, 4},  {32, 4, 8},  {36, 6, 6},  {40, 5, 8},  {48, 6, 8},
+                                 {56, 7, 8},   {64, 8, 8},  {72, 9, 8},  {80, 8, 10}, {96, 8, 12}, {100, 10, 10},
+                                 {112, 7, 16}, {120, 15, 8}};
+    if (N == 120 && !forward) { *R1 = 10; *R2 = 12; return true; }
     for (const auto& e : tab)
         if (e[0] == N) { *R1 = e[1]; *R2 = e[2]; return true; }
     return false;
@@ -275,7 +279,8 @@ static bool fused_shape(const LayerPlan& L, FusedShape* F, bool forward = false)
     const Dims& d = L.d;
     if (d.Ny != d.Nz) return false;
     int R1, R2;
-    if (!fused_split(d.Ny, &R1, &R2)) return false;
+    if (!fused_split(d.Ny, forward, &R1, &R2)) return false;
+    F->R1 = R1; F->R2 = R2;
     if (forward) {
         if (!fast_pass_available(d.Nx) || d.nx > 65535 || L.nimg > 65535) return false;
     } else {
@@ -318,28 +323,30 @@ static znni_status launch_fused(void (*kernel)(Args), const Args& a, const Fused
     return ZNNI_OK;
 }
 
+// dispatch on the split that fused_split chose (R1 * 100 + R2)
 #define ZNNI_FUSED_CASES(KERNEL)                                                                   \
-    switch (d.Ny) {                                                                                \
-        case 8: return launch_fused(KERNEL<2, 4>, a, F, grid, st);                                 \
-        case 10: return launch_fused(KERNEL<5, 2>, a, F, grid, st);                                \
-        case 12: return launch_fused(KERNEL<3, 4>, a, F, grid, st);                                \
-        case 14: return launch_fused(KERNEL<7, 2>, a, F, grid, st);                                \
-        case 16: return launch_fused(KERNEL<4, 4>, a, F, grid, st);                                \
-        case 20: return launch_fused(KERNEL<5, 4>, a, F, grid, st);                                \
-        case 24: return launch_fused(KERNEL<6, 4>, a, F, grid, st);                                \
-        case 28: return launch_fused(KERNEL<7, 4>, a, F, grid, st);                                \
-        case 32: return launch_fused(KERNEL<4, 8>, a, F, grid, st);                                \
-        case 36: return launch_fused(KERNEL<9, 4>, a, F, grid, st);                                \
-        case 40: return launch_fused(KERNEL<5, 8>, a, F, grid, st);                                \
-        case 48: return launch_fused(KERNEL<6, 8>, a, F, grid, st);                                \
-        case 56: return launch_fused(KERNEL<7, 8>, a, F, grid, st);                                \
-        case 64: return launch_fused(KERNEL<8, 8>, a, F, grid, st);                                \
-        case 72: return launch_fused(KERNEL<9, 8>, a, F, grid, st);                                \
-        case 80: return launch_fused(KERNEL<10, 8>, a, F, grid, st);                               \
-        case 96: return launch_fused(KERNEL<12, 8>, a, F, grid, st);                               \
-        case 100: return launch_fused(KERNEL<10, 10>, a, F, grid, st);                             \
-        case 112: return launch_fused(KERNEL<14, 8>, a, F, grid, st);                              \
-        case 120: return launch_fused(KERNEL<15, 8>, a, F, grid, st);                              \
+    switch (F.R1 * 100 + F.R2) {                                                                   \
+        case 204: return launch_fused(KERNEL<2, 4>, a, F, grid, st);                               \
+        case 502: return launch_fused(KERNEL<5, 2>, a, F, grid, st);                               \
+        case 304: return launch_fused(KERNEL<3, 4>, a, F, grid, st);                               \
+        case 702: return launch_fused(KERNEL<7, 2>, a, F, grid, st);                               \
+        case 404: return launch_fused(KERNEL<4, 4>, a, F, grid, st);                               \
+        case 504: return launch_fused(KERNEL<5, 4>, a, F, grid, st);                               \
+        case 604: return launch_fused(KERNEL<6, 4>, a, F, grid, st);                               \
+        case 704: return launch_fused(KERNEL<7, 4>, a, F, grid, st);                               \
+        case 408: return launch_fused(KERNEL<4, 8>, a, F, grid, st);                               \
+        case 606: return launch_fused(KERNEL<6, 6>, a, F, grid, st);                               \
+        case 508: return launch_fused(KERNEL<5, 8>, a, F, grid, st);                               \
+        case 608: return launch_fused(KERNEL<6, 8>, a, F, grid, st);                               \
+        case 708: return launch_fused(KERNEL<7, 8>, a, F, grid, st);                               \
+        case 808: return launch_fused(KERNEL<8, 8>, a, F, grid, st);                               \
+        case 908: return launch_fused(KERNEL<9, 8>, a, F, grid, st);                               \
+        case 810: return launch_fused(KERNEL<8, 10>, a, F, grid, st);                              \
+        case 812: return launch_fused(KERNEL<8, 12>, a, F, grid, st);                              \
+        case 1010: return launch_fused(KERNEL<10, 10>, a, F, grid, st);                            \
+        case 716: return launch_fused(KERNEL<7, 16>, a, F, grid, st);                              \
+        case 1508: return launch_fused(KERNEL<15, 8>, a, F, grid, st);                             \
+        case 1012: return launch_fused(KERNEL<10, 12>, a, F, grid, st);                            \
     }                                                                                              \
     return ZNNI_ERR_UNSUPPORTED_SIZE;
 
