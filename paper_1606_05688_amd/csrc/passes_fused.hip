@@ -37,8 +37,28 @@ struct FusedArgs {
     int QP;                // pitch of the plane kept in LDS (noy + 1 or + 2, even)
 };
 
+// Threads of a workgroup, and the number of waves per SIMD the register allocation is held to.  By default four
+// (128 registers); the listed kernels sit a few registers above the step that lets one more workgroup share the
+// CU and are held below it.
 template <int R1, int R2>
-__global__ __launch_bounds__(1024) void k_inv_yz(FusedArgs a)
+constexpr int fused_nth() { return ((R1 * R2 / 2 + 1) * (R1 > R2 ? R1 : R2) + 63) / 64 * 64; }
+template <int R1, int R2, bool FWD>
+constexpr int fused_waves()
+{
+    constexpr int N = R1 * R2;
+    // measured (32 -> 32 images, batches of 1.5 GB): forward at 100 held to 80 registers (two over; three
+    // workgroups per CU instead of two) 18 % faster, inverse at 96 held to 64 (two over) 14 % faster, forward at 56
+    // and inverse at 112 3-4 %; where the step is further away (forward at 64, 72, 96, 112, 120) the spills cost
+    // 5 to 25 %
+    if (FWD && N == 100) return 6;
+    if (FWD && N == 56) return 8;
+    if (!FWD && (N == 96 || N == 112)) return 8;
+    return 4;
+}
+
+template <int R1, int R2>
+__global__ __launch_bounds__((fused_nth<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, false>()))))
+void k_inv_yz(FusedArgs a)
 {
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1;
@@ -136,7 +156,8 @@ struct FusedFwdArgs {
 };
 
 template <int R1, int R2>
-__global__ __launch_bounds__(1024) void k_fwd_zy(FusedFwdArgs a)
+__global__ __launch_bounds__((fused_nth<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, true>()))))
+void k_fwd_zy(FusedFwdArgs a)
 {
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1, TMAX = R1 > R2 ? R1 : R2;
