@@ -21,9 +21,9 @@ struct FftPlan {
 
 // Streaming (non-temporal) global accesses for tensors that are written once by one kernel and read once by the
 // next and are far larger than the caches.  Measured on the 320^3 workload: the middle four transform passes
-// gain 2 to 7 % with both, the first pass only with streaming stores (its input lines are touched by several
-// instructions and must stay cached), the last only with streaming loads (its unaligned output rows are merged
-// in L2 when stored normally).
+// gain 2 to 7 % with both, the last only with streaming loads (its unaligned output rows are merged in L2 when
+// stored normally); the first pass uses neither (its input lines are touched by several instructions and must
+// stay cached, and its stores were faster without at every smaller size).
 typedef float znni_v2f __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void st_stream(float2* p, float2 v)
 {
