@@ -50,7 +50,7 @@ constexpr int fused_waves()
     // workgroups per CU instead of two) 18 % faster, inverse at 96 held to 64 (two over) 14 % faster, forward at 56
     // and inverse at 112 3-4 %; where the step is further away (forward at 64, 72, 96, 112, 120) the spills cost
     // 5 to 25 %
-    if (FWD && N == 100) return 6;
+    if (FWD && (N == 100 || N == 120)) return 6;
     if (FWD && N == 56) return 8;
     if (!FWD && (N == 96 || N == 112)) return 8;
     return 4;
@@ -288,7 +288,7 @@ static bool fused_split(int N, bool forward, int* R1, int* R2)
                                  {24, 6, 4},   {28, 7, 4},  {32, 4, 8},  {36, 6, 6},  {40, 5, 8},  {48, 6, 8},
                                  {56, 7, 8},   {64, 8, 8},  {72, 9, 8},  {80, 8, 10}, {96, 8, 12}, {100, 10, 10},
                                  {112, 7, 16}, {120, 15, 8}};
-    if (N == 120 && !forward) { *R1 = 10; *R2 = 12; return true; }
+    if (N == 120) { *R1 = 10; *R2 = 12; return true; }
     for (const auto& e : tab)
         if (e[0] == N) { *R1 = e[1]; *R2 = e[2]; return true; }
     return false;
