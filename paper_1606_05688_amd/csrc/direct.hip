@@ -81,7 +81,16 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
     const int tilevol = TXI * TYI * TZI;
     const int taps = d.kx * d.ky * d.kz;
 
-    const int tz = blockIdx.x % a.ntz, ty = (blockIdx.x / a.ntz) % a.nty, tx = blockIdx.x / (a.ntz * a.nty);
+    // Tiles that are neighbours in memory go to one XCD, one after the other: hardware deals consecutive workgroup
+    // ids round-robin to the 8 XCDs, each with an L2 of its own, and the cache lines that two neighbouring tiles
+    // both write part of (rows of an output image are not multiples of 128 bytes) then meet in one L2.
+    int tile_id;
+    {
+        const int nb = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int per = nb >> 3, rem = nb & 7;
+        tile_id = xcd * per + min(xcd, rem) + slot;
+    }
+    const int tz = tile_id % a.ntz, ty = (tile_id / a.ntz) % a.nty, tx = tile_id / (a.ntz * a.nty);
     const int x0 = tx * TX, y0 = ty * TY, z0 = tz * TZ;
     const int s = blockIdx.y;
     const int rt0 = blockIdx.z * RTW;
@@ -94,18 +103,22 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
         }
         delta[q] = dl;
     }
-    // staged voxels of this thread: offset inside an image (clamped into it)
+    // staged voxels of this thread (compact tiles): offset inside an image (clamped into it).  Long tiles are
+    // staged by rows instead, see below.
     int goff[DIRECT_NQ];
+    if constexpr (!LONGZ) {
 #pragma unroll
-    for (int q = 0; q < DIRECT_NQ; ++q) {
-        goff[q] = 0;
-        if (256 * q < tilevol) {                     // uniform: small kernels need only the first few
-            const int e = min(t + 256 * q, tilevol - 1);
-            const int lz = e % TZI, ly = (e / TZI) % TYI, lx = e / (TZI * TYI);
-            const int gx = min(x0 + lx, d.nx - 1), gy = min(y0 + ly, d.ny - 1), gz = min(z0 + lz, d.nz - 1);
-            goff[q] = (gx * d.ny + gy) * d.nz + gz;
+        for (int q = 0; q < DIRECT_NQ; ++q) {
+            goff[q] = 0;
+            if (256 * q < tilevol) {                 // uniform: small kernels need only the first few
+                const int e = min(t + 256 * q, tilevol - 1);
+                const int lz = e % TZI, ly = (e / TZI) % TYI, lx = e / (TZI * TYI);
+                const int gx = min(x0 + lx, d.nx - 1), gy = min(y0 + ly, d.ny - 1), gz = min(z0 + lz, d.nz - 1);
+                goff[q] = (gx * d.ny + gy) * d.nz + gz;
+            }
         }
     }
+    const int wv = __builtin_amdgcn_readfirstlane(wave);      // wave-uniform, and known to be
     // column tiles of this wave: (tx, ty) pair and 16-voxel piece of the z run
     int voxbase[CTW];
 #pragma unroll
@@ -138,13 +151,45 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
         __syncthreads();                             // the previous chunk has been consumed
         for (int il = 0; il < icn; ++il) {
             const float* img = a.in + ((size_t)s * a.f + ic0 + il) * nvox;
-            float v[DIRECT_NQ];
+            if constexpr (LONGZ) {
+                // a wave per (x, y) row of the tile, lanes along z: the row's address is scalar arithmetic.  (With
+                // one or a few input images a voxel offset per thread, computed with divisions, is used too
+                // rarely to pay for itself.)
+                // Two rows per wave and three runs of 64 per row are requested before the first is written.
+                const int nrows = TXI * TYI;
+                for (int rg = 0; rg < nrows; rg += 8) {
+                    for (int zg = 0; zg < TZI; zg += 192) {
+                        float v[2][3];
 #pragma unroll
-            for (int q = 0; q < DIRECT_NQ; ++q)
-                if (256 * q < tilevol) v[q] = img[goff[q]];
+                        for (int ri = 0; ri < 2; ++ri) {
+                            const int row = min(rg + 4 * ri + wv, nrows - 1);
+                            const int lx = row / TYI, ly = row - lx * TYI;
+                            const float* src =
+                                img + ((size_t)min(x0 + lx, d.nx - 1) * d.ny + min(y0 + ly, d.ny - 1)) * d.nz;
 #pragma unroll
-            for (int q = 0; q < DIRECT_NQ; ++q)
-                if (t + 256 * q < tilevol) tile[il * tilevol + t + 256 * q] = v[q];
+                            for (int zi = 0; zi < 3; ++zi)
+                                v[ri][zi] = src[min(z0 + min(zg + 64 * zi + lane, TZI - 1), d.nz - 1)];
+                        }
+#pragma unroll
+                        for (int ri = 0; ri < 2; ++ri) {
+                            const int row = rg + 4 * ri + wv;
+#pragma unroll
+                            for (int zi = 0; zi < 3; ++zi) {
+                                const int z = zg + 64 * zi + lane;
+                                if (row < nrows && z < TZI) tile[il * tilevol + row * TZI + z] = v[ri][zi];
+                            }
+                        }
+                    }
+                }
+            } else {
+                float v[DIRECT_NQ];
+#pragma unroll
+                for (int q = 0; q < DIRECT_NQ; ++q)
+                    if (256 * q < tilevol) v[q] = img[goff[q]];
+#pragma unroll
+                for (int q = 0; q < DIRECT_NQ; ++q)
+                    if (t + 256 * q < tilevol) tile[il * tilevol + t + 256 * q] = v[q];
+            }
         }
         __syncthreads();
         // all steps of the chunk in one flat loop; the kernel values of the next step are requested before the
@@ -197,13 +242,40 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
             }
         }
         __syncthreads();
-        for (int e = t; e < 16 * NPAIR * TZ; e += 256) {            // lanes along z, then (x, y), then output image
-            const int zl = e % TZ, row = e / TZ;
-            const int jl = row / NPAIR, pair = row - jl * NPAIR;
-            const int j = (rt0 + r) * 16 + jl;
-            const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zl;
-            if (j >= a.fo || X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
-            a.out[((size_t)s * a.fo + j) * ovox + ((size_t)X * d.noy + Y) * d.noz + Z] = Ol[jl * OP + pair * TZ + zl];
+        if constexpr (LONGZ) {
+            // A wave per row (output image, x, y) of the tile, lanes along z.  Rows wv, wv + 4, ... are the same
+            // (x, y) of every (4 / NPAIR)-th output image: one address per wave, then a constant stride, and all
+            // of a wave's values leave LDS before the first store.
+            constexpr int RPW = 4 * NPAIR, JS = 4 / NPAIR;       // rows per wave, output images between them
+            static_assert(NPAIR == 1 || NPAIR == 2, "long tiles have one or two (x, y) rows");
+            const int pair = wv % NPAIR, jl0 = wv / NPAIR;
+            const int X = x0 + pair / TY, Y = y0 + pair % TY;
+            const int j0 = (rt0 + r) * 16 + jl0;
+            const int nrow = (X < d.nox && Y < d.noy) ? (a.fo - j0 + JS - 1) / JS : 0;      // rows to store: i < nrow
+            float val[RPW][TZ / 64];
+            const float* src = Ol + jl0 * OP + pair * TZ + lane;
+#pragma unroll
+            for (int i = 0; i < RPW; ++i)
+#pragma unroll
+                for (int zi = 0; zi < TZ / 64; ++zi) val[i][zi] = src[i * JS * OP + 64 * zi];
+            float* dst = a.out + ((size_t)s * a.fo + j0) * ovox + ((size_t)X * d.noy + Y) * d.noz + z0 + lane;
+#pragma unroll
+            for (int i = 0; i < RPW; ++i) {
+#pragma unroll
+                for (int zi = 0; zi < TZ / 64; ++zi)
+                    if (i < nrow && z0 + lane + 64 * zi < d.noz) dst[64 * zi] = val[i][zi];
+                dst += (size_t)JS * ovox;
+            }
+        } else {
+            for (int e = t; e < 16 * NPAIR * TZ; e += 256) {        // lanes along z, then (x, y), then output image
+                const int zl = e % TZ, row = e / TZ;
+                const int jl = row / NPAIR, pair = row - jl * NPAIR;
+                const int j = (rt0 + r) * 16 + jl;
+                const int X = x0 + pair / TY, Y = y0 + pair % TY, Z = z0 + zl;
+                if (j >= a.fo || X >= d.nox || Y >= d.noy || Z >= d.noz) continue;
+                a.out[((size_t)s * a.fo + j) * ovox + ((size_t)X * d.noy + Y) * d.noz + Z] =
+                    Ol[jl * OP + pair * TZ + zl];
+            }
         }
     }
 }
