@@ -49,6 +49,7 @@ struct DirectArgs {
     int IC;          // images per staged chunk
     int ntx, nty, ntz;
     int relu;
+    int ty_magic;    // long tiles: 65536 / (rows of the staged tile along y) + 1, for divisions of small numbers
 };
 
 // Wp[i][st][rt][kk][r] = w[rt*16 + r][i][tap st*4 + kk], zero beyond fo or beyond the last tap.
@@ -139,10 +140,16 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
 #pragma unroll
     for (int r = 0; r < RTW; ++r)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = (rt0 + r) * 16 + 4 * kk + e;
-            bj[r][e] = (a.bias && j < a.fo) ? a.bias[j] : 0.f;
+        for (int e = 0; e < 4; ++e) bj[r][e] = 0.f;
+    if (a.bias) {                                    // one uniform branch; output images past the last are not stored
+#pragma unroll
+        for (int r = 0; r < RTW; ++r) {
+            const float* bp = a.bias + min((rt0 + r) * 16 + 4 * kk, a.fo - 1);
+            const int left = a.fo - 1 - ((rt0 + r) * 16 + 4 * kk);       // last valid element of this group of four
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bj[r][e] = bp[max(min(e, left), 0)];
         }
+    }
 
     const size_t nvox = (size_t)d.nx * d.ny * d.nz;
     const int steps = a.T4 >> 2;
@@ -163,7 +170,7 @@ __global__ __launch_bounds__(256) void k_direct(DirectArgs a)
 #pragma unroll
                         for (int ri = 0; ri < 2; ++ri) {
                             const int row = min(rg + 4 * ri + wv, nrows - 1);
-                            const int lx = row / TYI, ly = row - lx * TYI;
+                            const int lx = (row * a.ty_magic) >> 16, ly = row - lx * TYI;     // row / TYI
                             const float* src =
                                 img + ((size_t)min(x0 + lx, d.nx - 1) * d.ny + min(y0 + ly, d.ny - 1)) * d.nz;
 #pragma unroll
@@ -339,6 +346,7 @@ static znni_status launch_direct_s(const DirectArgs& a, const DirectPlan& P, hip
     b.ntx = (P.d.nox + TL::TX - 1) / TL::TX;
     b.nty = (P.d.noy + TL::TY - 1) / TL::TY;
     b.ntz = (P.d.noz + TL::TZ - 1) / TL::TZ;
+    b.ty_magic = 65536 / (TL::TY + P.d.ky - 1) + 1;                       // exact for numerators below 65536 / TYI
     const long long tiles = (long long)b.ntx * b.nty * b.ntz;
     if (tiles > 0x7fffffffll) return ZNNI_ERR_SHAPE;
     if (P.lds > 48 * 1024 &&
@@ -394,7 +402,7 @@ znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int
     a.in = in; a.Wp = Wp; a.bias = bias; a.out = out;
     a.d = P.d; a.S = S; a.f = f; a.fo = fo;
     a.T4 = P.T4; a.RT = P.RT; a.IC = P.IC;
-    a.ntx = a.nty = a.ntz = 0;
+    a.ntx = a.nty = a.ntz = 0; a.ty_magic = 0;
     a.relu = (flags & ZNNI_RELU) ? 1 : 0;
     switch (P.RTW * 10 + P.CTW) {
         case 14: return launch_direct_t<1, 4>(a, P, st);
