@@ -185,19 +185,19 @@ void k_fwd_zy(FusedFwdArgs a)
     // slower with a whole plane per workgroup.)
     float* raw = reinterpret_cast<float*>(R);
     {
+        // element i = t + k * NTH of the plane is (row, col): one division, then steps of NTH with a carry
         const int tot = ny * nz;
-        const float inv_nz = 1.f / (float)nz;
+        const int srow = NTH / nz, scol = NTH - srow * nz;
+        int row = t / nz, col = t - row * nz;
         for (int i0 = 0; i0 < tot; i0 += 8 * NTH) {
             float r[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) r[k] = plane[min(i0 + k * NTH + t, tot - 1)];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const int i = i0 + k * NTH + t;
-                int row = (int)((float)i * inv_nz);
-                row -= row * nz > i ? 1 : 0;
-                row += (row + 1) * nz <= i ? 1 : 0;
-                if (i < tot) raw[row * RP + (i - row * nz)] = r[k];
+                if (i0 + k * NTH + t < tot) raw[row * RP + col] = r[k];
+                col += scol; row += srow;
+                if (col >= nz) { col -= nz; ++row; }
             }
         }
     }
@@ -210,11 +210,18 @@ void k_fwd_zy(FusedFwdArgs a)
         const float ma = la < np ? 1.f : 0.f, mb = (la < np && ya + 1 < ny) ? 1.f : 0.f;
         const float* ra = raw + ya * RP;
         const float* rb = raw + min(ya + 1, ny - 1) * RP;
+        // rows that fill the transform length: constant offsets, no padding in z.  (Not at 120, whose kernel is
+        // held to 80 registers: with this second path it spills more and is 8 % slower, measured.)
+        if (N != 120 && nz == N) {
 #pragma unroll
-        for (int m = 0; m < R1; ++m) {
-            const int e = ja + R2 * m, ec = min(e, nz - 1);
-            const float me = e < nz ? 1.f : 0.f;
-            v[m] = make_float2(ra[ec] * (me * ma), rb[ec] * (me * mb));
+            for (int m = 0; m < R1; ++m) v[m] = make_float2(ra[ja + R2 * m] * ma, rb[ja + R2 * m] * mb);
+        } else {
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const int e = ja + R2 * m, ec = min(e, nz - 1);
+                const float me = e < nz ? 1.f : 0.f;
+                v[m] = make_float2(ra[ec] * (me * ma), rb[ec] * (me * mb));
+            }
         }
     }
     __syncthreads();                          // the raw plane has been read: the region becomes the exchange buffer
@@ -229,22 +236,33 @@ void k_fwd_zy(FusedFwdArgs a)
     __syncthreads();
     // untangle the two rows of every line; they become two neighbouring y of each oz row of the plane Pl
     constexpr int UIT = (N / 2 + TMAX - 1) / TMAX;            // np * ZC <= (N / 2) * ZC elements, blockDim.x >= ZC * TMAX
+    // element e = t + k * NTH is (oz, l) = (e / np, e % np), lines fastest so that neighbouring lanes write
+    // neighbours: one division, then steps of NTH with a carry; past the end oz >= ZC
     float4 g[UIT];
+    const int soz = NTH / np, sl = NTH - soz * np;
+    const int oz0 = t / np, l0 = t - oz0 * np;
+    {
+        int oz = oz0, l = l0;
 #pragma unroll
-    for (int k = 0; k < UIT; ++k) {
-        const int e = min(t + k * NTH, np * ZC - 1);          // lines fastest: neighbouring lanes write neighbours
-        const int oz = e / np, l = e - oz * np;
-        const float2* row = R + l * P;
-        const float2 z1 = row[oz], z2 = cconj(row[oz ? N - oz : 0]);
-        const float2 ev = cscale(cadd(z1, z2), 0.5f), od = cscale(mul_mi(csub(z1, z2)), 0.5f);
-        g[k] = make_float4(ev.x, ev.y, od.x, od.y);
+        for (int k = 0; k < UIT; ++k) {
+            const int ozc = oz < ZC ? oz : 0;
+            const float2* row = R + l * P;
+            const float2 z1 = row[ozc], z2 = cconj(row[ozc ? N - ozc : 0]);
+            const float2 ev = cscale(cadd(z1, z2), 0.5f), od = cscale(mul_mi(csub(z1, z2)), 0.5f);
+            g[k] = make_float4(ev.x, ev.y, od.x, od.y);
+            l += sl; oz += soz;
+            if (l >= np) { l -= np; ++oz; }
+        }
     }
     __syncthreads();                          // the lines have been read: the region becomes Pl
+    {
+        int oz = oz0, l = l0;
 #pragma unroll
-    for (int k = 0; k < UIT; ++k) {
-        const int e = t + k * NTH;
-        const int oz = e / np, l = e - oz * np;
-        if (e < np * ZC) *reinterpret_cast<float4*>(R + oz * PP + 2 * l) = g[k];
+        for (int k = 0; k < UIT; ++k) {
+            if (oz < ZC) *reinterpret_cast<float4*>(R + oz * PP + 2 * l) = g[k];
+            l += sl; oz += soz;
+            if (l >= np) { l -= np; ++oz; }
+        }
     }
     __syncthreads();
 
