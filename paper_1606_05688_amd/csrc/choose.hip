@@ -24,7 +24,7 @@ constexpr double kMacFlopsPerSec = 110e12;          // issued matrix-core flops 
 constexpr double kMacBatchSecPerValue = 2.1e-12;    // batch form: per kernel-spectrum value and 16 inputs
 constexpr double kDirectFlopsPerSec = 80e12;        // direct convolution, windows of 27 taps and more
 constexpr double kDirectFlopsPerSecSmall = 60e12;   // ... of fewer taps
-constexpr double kDirectWriteBytesPerSec = 2.0e12;  // direct convolution, output write
+constexpr double kDirectWriteBytesPerSec = 3.6e12;  // direct convolution, output write
 constexpr double kLaunchSec = 3.5e-6;
 
 static double fft_seconds(int S, int f, int fo, const int n[3], const int k[3])
