@@ -135,9 +135,11 @@ void k_inv_yz(FusedArgs a)
     // rows yo of out[imgo][xo]: real part of line l -> row 2l, minus imaginary part -> row 2l+1
     const float bj = a.bias ? a.bias[img % a.fo] : 0.f;
     float* dst = a.out + (((size_t)img * nox + xo) * noy) * noz;
-    for (int ll = t / 64; ll < noy; ll += NTH / 64) {
+    // a wave per row, or per two or four rows where rows are at most 32 or 16 long
+    constexpr int LW = N <= 16 ? 16 : N <= 32 ? 32 : 64, RPI = 64 / LW;
+    for (int ll = (t / 64) * RPI + (t % 64) / LW; ll < noy; ll += (NTH / 64) * RPI) {
         const float2* row = R + (ll >> 1) * P + (d.kz - 1);
-        for (int zo = t % 64; zo < noz; zo += 64) {
+        for (int zo = t % LW; zo < noz; zo += LW) {
             const float2 c = row[zo];
             float val = ((ll & 1) ? -c.y : c.x) + bj;
             if (a.relu) val = fmaxf(val, 0.f);
@@ -288,8 +290,10 @@ void k_fwd_zy(FusedFwdArgs a)
     }
     __syncthreads();
     float2* dst = a.dst + (((size_t)img * d.nx + x) * ZC) * N;
-    for (int l = t / 64; l < ZC; l += NTH / 64)
-        for (int e = t % 64; e < N; e += 64) dst[(size_t)l * N + e] = R[l * P + e];
+    // a wave per row, or per two or four rows where rows are at most 32 or 16 long
+    constexpr int LW = N <= 16 ? 16 : N <= 32 ? 32 : 64, RPI = 64 / LW;
+    for (int l = (t / 64) * RPI + (t % 64) / LW; l < ZC; l += (NTH / 64) * RPI)
+        for (int e = t % LW; e < N; e += LW) dst[(size_t)l * N + e] = R[l * P + e];
 }
 
 // ------------------------------------------------------------------------------------------- host side
