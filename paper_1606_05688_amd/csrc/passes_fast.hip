@@ -59,10 +59,12 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         const int x0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * d.nx + x0) * zc + oz) * d.ldy;
         lpitch = (size_t)zc * d.ldy; nvalid = min(16, d.nx - x0); lin = d.ny;
-    } else if constexpr (KIND == P_FWD_XT) {  // tile: 16 oy of one (img, oz); element x of line l at x*epitch + l
-        const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + ((size_t)img * d.nx * zc + oz) * d.Ny + oy0;
-        lpitch = 1; epitch = (size_t)zc * d.Ny; nvalid = min(16, d.Ny - oy0); lin = d.nx;
+    } else if constexpr (KIND == P_FWD_XT) {
+        // tile: 16 neighbouring (oz, oy) of one img, counted oz * Ny + oy as they lie in X2' and in Xt, so that
+        // tiles are full whatever Ny is (mid = 0); element x of line l at x*epitch + l
+        const int q0 = tile * 16;
+        src = (const float2*)a.src + (size_t)img * d.nx * zc * d.Ny + q0;
+        lpitch = 1; epitch = (size_t)zc * d.Ny; nvalid = min(16, zc * d.Ny - q0); lin = d.nx;
     } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
         const int oy0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.ldx;
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         }
         __syncthreads();
         if constexpr (KIND == P_FWD_X || KIND == P_FWD_XT) {
-            // Xt[oz][oy0 + l][img][ox]: whole lines, contiguous
+            // Xt[oz][oy0 + l][img][ox]: whole lines, contiguous (P_FWD_XT: mid = 0, oy0 counts oz * Ny + oy)
             const int oy0 = tile * 16;
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
                 float2* o = (float2*)a.dst + (((size_t)mid * d.Ny + oy0 + l) * a.nimg + img) * N;
@@ -378,7 +380,7 @@ znni_status launch_fast_fwd_xt(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
     return launch_kind<P_FWD_XT>(d.Nx, base_args(L, L.buf1, L.buf0, L.twx, L.nimg),
-                                 dim3((d.Ny + 15) / 16, d.zc, L.nimg), st);
+                                 dim3((d.zc * d.Ny + 15) / 16, 1, L.nimg), st);
 }
 znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
 {
