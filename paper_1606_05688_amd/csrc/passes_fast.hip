@@ -30,6 +30,11 @@ struct PassArgs {
     int nimg, fo, relu;
 };
 
+// Inverse x pass: tiles counted over (oz, oy) together?  Measured 9-11 % faster at lengths 56 and 120 (fewer, full
+// tiles), but 30 % slower at 100, where the rows of Y2 are padded to whole cache lines and tiles that start
+// anywhere in a row make every 128-byte store straddle two lines.
+__host__ __device__ inline bool inv_x_flat(const Dims& d) { return d.ldn == d.Ny && d.Ny > 16 && (d.Ny & 15) != 0; }
+
 template <int R1, int R2, int KIND>
 __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
 {
@@ -69,10 +74,14 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         const int oy0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.ldx;
         lpitch = d.ldx; nvalid = min(16, d.Ny - oy0); lin = d.nx;
-    } else if constexpr (KIND == P_INV_X) {   // tile: 16 oy of one (oz, imgo); lines along ox in Yt
-        const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)oz * d.Ny + oy0) * a.nimg + img) * N;
-        lpitch = (size_t)a.nimg * N; nvalid = min(16, d.Ny - oy0);
+    } else if constexpr (KIND == P_INV_X) {
+        // tile: 16 oy of one (oz, imgo); or, where rows of Y2 are not padded to whole cache lines anyway and do not
+        // divide into tiles, 16 neighbouring (oz, oy) counted oz * Ny + oy as the pencils lie in Yt, so that
+        // tiles are full (mid = 0); lines along ox
+        const bool flat = inv_x_flat(d);
+        const int q0 = flat ? tile * 16 : mid * d.Ny + tile * 16;
+        src = (const float2*)a.src + ((size_t)q0 * a.nimg + img) * N;
+        lpitch = (size_t)a.nimg * N; nvalid = flat ? min(16, zc * d.Ny - q0) : min(16, d.Ny - tile * 16);
     } else if constexpr (KIND == P_INV_Y) {   // tile: 16 xo of one (imgo, oz); lines along oy, adjacent in Y2
         const int xo0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * zc + oz) * d.nox + xo0) * d.ldn;
@@ -172,9 +181,16 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int r = 0; r < R2; ++r) stg<STREAM>(o + (size_t)(q + R1 * r) * d.ldx, u[r]);
         }
     } else if constexpr (KIND == P_INV_X) {
-        // Y2[imgo][oz][xo][oy0 + lb], xo = element - (kx-1) in [0, nox)
+        // Y2[imgo][oz][xo][oy], xo = element - (kx-1) in [0, nox); with (oz, oy) counted together the tile's
+        // first line by a scalar division, then at most one row further (rows hold more than 16 values)
         if (q < R1 && lb < nvalid) {
-            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * d.nox * d.ldn + tile * 16 + lb;
+            int oz = mid, oy = tile * 16 + lb;
+            if (inv_x_flat(d)) {
+                const int q0 = tile * 16;
+                oz = q0 / d.Ny; oy = q0 - oz * d.Ny + lb;
+                if (oy >= d.Ny) { oy -= d.Ny; ++oz; }
+            }
+            float2* o = (float2*)a.dst + ((size_t)img * zc + oz) * d.nox * d.ldn + oy;
 #pragma unroll
             for (int r = 0; r < R2; ++r) {
                 const int xo = q + R1 * r - (d.kx - 1);
@@ -385,8 +401,8 @@ znni_status launch_fast_fwd_xt(const LayerPlan& L, hipStream_t st)
 znni_status launch_fast_inv_x(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    return launch_kind<P_INV_X>(d.Nx, base_args(L, L.Yt, L.buf0, L.twx, L.nimgo),
-                                dim3((d.Ny + 15) / 16, d.zc, L.nimgo), st);
+    const dim3 grid = inv_x_flat(d) ? dim3((d.zc * d.Ny + 15) / 16, 1, L.nimgo) : dim3((d.Ny + 15) / 16, d.zc, L.nimgo);
+    return launch_kind<P_INV_X>(d.Nx, base_args(L, L.Yt, L.buf0, L.twx, L.nimgo), grid, st);
 }
 znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)
 {
