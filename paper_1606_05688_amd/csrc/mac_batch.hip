@@ -62,13 +62,22 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
     float tr[3], ti[3], ts[3];
     {
+        // index (a * ox) mod N without a division: kk * ox and 4 * ox are below 4 N, later taps add 4 * ox
         const int ox = min(ox0 + l16, N - 1);
+        int q = kk * ox, q4 = 4 * ox;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            q = q >= N ? q - N : q;
+            q4 = q4 >= N ? q4 - N : q4;
+        }
 #pragma unroll
         for (int st = 0; st < 3; ++st) {
             const int a = 4 * st + kk;
             float2 v = make_float2(0.f, 0.f);
-            if (a < k) v = twg[(int)(((long long)a * ox) % N)];
+            if (a < k) v = twg[q];
             tr[st] = v.x; ti[st] = v.y; ts[st] = v.x + v.y;
+            q += q4;
+            q = q >= N ? q - N : q;
         }
     }
 
@@ -220,13 +229,22 @@ __global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ X
     const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
     float tr[3], ti[3], ts[3];
     {
+        // index (a * ox) mod N without a division: kk * ox and 4 * ox are below 4 N, later taps add 4 * ox
         const int ox = min(ox0 + l16, N - 1);
+        int q = kk * ox, q4 = 4 * ox;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            q = q >= N ? q - N : q;
+            q4 = q4 >= N ? q4 - N : q4;
+        }
 #pragma unroll
         for (int st = 0; st < 3; ++st) {
             const int a = 4 * st + kk;
             float2 v = make_float2(0.f, 0.f);
-            if (a < k) v = twg[(int)(((long long)a * ox) % N)];
+            if (a < k) v = twg[q];
             tr[st] = v.x; ti[st] = v.y; ts[st] = v.x + v.y;
+            q += q4;
+            q = q >= N ? q - N : q;
         }
     }
 
