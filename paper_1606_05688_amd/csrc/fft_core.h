@@ -67,6 +67,11 @@ __device__ __forceinline__ float2 caxpy(float2 a, float s, float2 b)
 {
     return make_float2(fmaf(s, b.x, a.x), fmaf(s, b.y, a.y));
 }
+// a + b*c, four fused multiply-adds
+__device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c)
+{
+    return make_float2(fmaf(-b.y, c.y, fmaf(b.x, c.x, a.x)), fmaf(b.y, c.x, fmaf(b.x, c.y, a.y)));
+}
 
 // Forward DFTs of length R in registers: v[m] <- sum_t v[t] exp(-2 pi i t m / R).
 template <int R> __device__ __forceinline__ void dft(float2* v);

@@ -24,49 +24,64 @@
 // the matrix cores (v_mfma_f32_16x16x4_f32), each complex product done as three real ones:
 //     P1 = Ar Br, P2 = Ai Bi, P3 = (Ar+Ai)(Br+Bi);  Re = P1 - P2, Im = P3 - P1 - P2.
 // A is stored in the order the contraction walks it: [oz][oy][i/4][a][i%4][j<Mp].
+#include <algorithm>
 #include "mac_common.h"
 
 namespace znni {
 
+// Both stages below need few twiddles per workgroup -- exp(-2 pi i o c / N) for the workgroup's KPREP_OZ (KPREP_OY)
+// consecutive outputs o and the taps c -- and every thread needs the same one at the same time.  They are gathered
+// once into LDS as tw2[c][o], KPREP_TAPS taps at a time, and the inner loops read them at constant offsets: no
+// index arithmetic per product (it was half of the vector instructions of kernels that are bound by issuing them).
+constexpr int KPREP_TAPS = 64;
+template <int NO>
+__device__ __forceinline__ void kprep_gather(float2* tw2, const float2* __restrict__ tw, int N, int o0, int c0, int nc)
+{
+    for (int e = threadIdx.x; e < nc * NO; e += 256) {
+        const int c = e / NO, o = e - c * NO;
+        tw2[e] = tw[(unsigned)((o0 + o) * (c0 + c)) % (unsigned)N];      // both factors below 1024
+    }
+}
+
 // A1[oz][b<ky][a<kx][i<fp][j<Mp] = sum_{c<kz} w[j][i][a][b][c] exp(-2 pi i oz c / Nz); zero where i >= f or
 // j >= fo.  (j fastest, so the y stage below reads and writes contiguous runs.)
 // One thread produces KPREP_OZ consecutive oz for one (b,a,i,j): its kz kernel values -- a short run of w, far
-// from the runs of the neighbouring lanes -- are read once per KPREP_OZ outputs, and the twiddle index advances
-// by c per oz.  (One thread per output re-read w for every oz: 3.2 ms for 80 x 80 kernels of 9^3 at length 100.)
+// from the runs of the neighbouring lanes -- are read once per KPREP_OZ outputs.  (One thread per output re-read w
+// for every oz: 3.2 ms for 80 x 80 kernels of 9^3 at length 100.)
 constexpr int KPREP_OZ = 16;
 __global__ __launch_bounds__(256) void k_kprep_z(const float* __restrict__ w, float2* __restrict__ A1,
                                                  const float2* __restrict__ twz, Dims d, int f, int fo, int fp,
                                                  int Mp, size_t wj_stride)
 {
-    extern __shared__ float2 tws[];                            // [Nz] copy of the twiddle table
+    extern __shared__ float2 tw2[];                            // [taps of the chunk][KPREP_OZ]
     const int N = d.Nz;
-    for (int q = threadIdx.x; q < N; q += 256) tws[q] = twz[q];
-    __syncthreads();
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int oz0 = blockIdx.y * KPREP_OZ;
     const int per = d.ky * d.kx * fp * Mp;
-    if (idx >= per) return;
     const int j = idx % Mp;
     const int i = (idx / Mp) % fp;
     const int ba = idx / (Mp * fp);
     const int a = ba % d.kx, b = ba / d.kx;
+    const bool live = idx < per && i < f && j < fo;
     float2 acc[KPREP_OZ];
 #pragma unroll
     for (int o = 0; o < KPREP_OZ; ++o) acc[o] = make_float2(0.f, 0.f);
-    if (i < f && j < fo) {
-        const float* wr = w + (size_t)j * wj_stride + ((((size_t)i) * d.kx + a) * d.ky + b) * d.kz;
-        for (int c = 0; c < d.kz; ++c) {
-            const float v = wr[c];
-            int q = (int)(((long long)oz0 * c) % N);
-            const int step = c % N;
+    const float* wr = w + (live ? (size_t)j * wj_stride + ((((size_t)i) * d.kx + a) * d.ky + b) * d.kz : 0);
+    for (int c0 = 0; c0 < d.kz; c0 += KPREP_TAPS) {
+        const int nc = min(KPREP_TAPS, d.kz - c0);
+        if (c0) __syncthreads();                               // the previous chunk's twiddles have been used
+        kprep_gather<KPREP_OZ>(tw2, twz, N, oz0, c0, nc);
+        __syncthreads();
+        if (live) {
+            for (int c = 0; c < nc; ++c) {
+                const float v = wr[c0 + c];
+                const float2* tc = tw2 + c * KPREP_OZ;
 #pragma unroll
-            for (int o = 0; o < KPREP_OZ; ++o) {
-                acc[o] = caxpy(acc[o], v, tws[q]);
-                q += step;
-                if (q >= N) q -= N;
+                for (int o = 0; o < KPREP_OZ; ++o) acc[o] = caxpy(acc[o], v, tc[o]);
             }
         }
     }
+    if (idx >= per) return;
 #pragma unroll
     for (int o = 0; o < KPREP_OZ; ++o)
         if (oz0 + o < d.zc) A1[(size_t)(oz0 + o) * per + idx] = acc[o];
@@ -74,35 +89,37 @@ __global__ __launch_bounds__(256) void k_kprep_z(const float* __restrict__ w, fl
 
 // A[oz][oy<Ny][i/4][a<kx][i%4][j<Mp] = scale * sum_{b<ky} A1[oz][b][a][i][j] exp(-2 pi i oy b / Ny)
 // (i < fp, j < Mp: f and fo rounded up to the matrix-core tiles; the padding holds zeros).
-// One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once and the twiddle
-// index advances by b per oy, so the kernel is bound by its 8-byte stores.
+// One thread produces KPREP_OY consecutive oy for one (a,i,j): each A1 value is loaded once, and per product the
+// thread issues the four multiply-adds and nothing else.
 constexpr int KPREP_OY = 32;
 __global__ __launch_bounds__(256) void k_kprep_y(const float2* __restrict__ A1, float2* __restrict__ A,
                                                  const float2* __restrict__ tw, int N, int k, int ky, int fp, int Mp,
                                                  int per, float scale)
 {
     // N = Ny, k = kx (taps left for the multiply-accumulate), ky = taps summed here, per = kx*fp*Mp
-    extern __shared__ float2 tws[];                            // [N] copy of the twiddle table
-    for (int q = threadIdx.x; q < N; q += 256) tws[q] = tw[q];
-    __syncthreads();
+    extern __shared__ float2 tw2[];                            // [taps of the chunk][KPREP_OY]
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (a, i, j) as laid out in A1
     const int oy0 = blockIdx.y * KPREP_OY, oz = blockIdx.z;
-    if (idx >= per) return;
-    const float2* a1 = A1 + (size_t)oz * ky * per + idx;
+    const bool live = idx < per;
+    const float2* a1 = A1 + (size_t)oz * ky * per + (live ? idx : 0);
     float2 acc[KPREP_OY];
 #pragma unroll
     for (int o = 0; o < KPREP_OY; ++o) acc[o] = make_float2(0.f, 0.f);
-    for (int b = 0; b < ky; ++b) {
-        const float2 v = a1[(size_t)b * per];
-        int q = (int)(((long long)oy0 * b) % N);
-        const int step = b % N;
+    for (int b0 = 0; b0 < ky; b0 += KPREP_TAPS) {
+        const int nb = min(KPREP_TAPS, ky - b0);
+        if (b0) __syncthreads();                               // the previous chunk's twiddles have been used
+        kprep_gather<KPREP_OY>(tw2, tw, N, oy0, b0, nb);
+        __syncthreads();
+        if (live) {
+            for (int b = 0; b < nb; ++b) {
+                const float2 v = a1[(size_t)(b0 + b) * per];
+                const float2* tb = tw2 + b * KPREP_OY;
 #pragma unroll
-        for (int o = 0; o < KPREP_OY; ++o) {
-            acc[o] = cadd(acc[o], cmul(v, tws[q]));
-            q += step;
-            if (q >= N) q -= N;
+                for (int o = 0; o < KPREP_OY; ++o) acc[o] = cfma(acc[o], v, tb[o]);
+            }
         }
     }
+    if (!live) return;
     const int j = idx % Mp, i = (idx / Mp) % fp, a = idx / (Mp * fp);
     float2* d = A + ((size_t)oz * N + oy0) * per + (size_t)(((i >> 2) * k + a) * 4 + (i & 3)) * Mp + j;
 #pragma unroll
@@ -311,12 +328,13 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_str
     const Dims& d = L.d;
     const int per = d.kx * L.fp * L.Mp;
     const int per1 = per * d.ky;
-    k_kprep_z<<<dim3((per1 + 255) / 256, (d.zc + KPREP_OZ - 1) / KPREP_OZ), dim3(256), sizeof(float2) * (size_t)d.Nz,
-                st>>>(w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp, wj_stride);
+    k_kprep_z<<<dim3((per1 + 255) / 256, (d.zc + KPREP_OZ - 1) / KPREP_OZ), dim3(256),
+                sizeof(float2) * KPREP_OZ * (size_t)std::min(d.kz, KPREP_TAPS), st>>>(
+        w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp, wj_stride);
     ZNNI_LAUNCH_CHECK();
     const float scale = (float)(1.0 / ((double)d.Nx * d.Ny * d.Nz));
     k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256),
-                sizeof(float2) * (size_t)d.Ny, st>>>(
+                sizeof(float2) * KPREP_OY * (size_t)std::min(d.ky, KPREP_TAPS), st>>>(
         L.A1, L.A, L.twy, d.Ny, d.kx, d.ky, L.fp, L.Mp, per, scale);
     ZNNI_LAUNCH_CHECK();
     return ZNNI_OK;
