@@ -50,6 +50,9 @@ CASES = [
     (1, 2, 2, (4, 5, 6), (4, 5, 6)),            # k = n: one output voxel
     (3, 2, 2, (1, 20, 33), (1, 3, 3)),          # flat images
     (1, 9, 4, (13, 21, 8), (4, 1, 6)),
+    (1, 1, 20, (4, 5, 140), (2, 2, 3)),         # first layer, long tiles: two tiles along z, the second ragged
+    (2, 2, 33, (3, 6, 260), (1, 2, 2)),         # long tiles: three tiles along z, a ragged third row tile
+    (1, 1, 81, (5, 4, 131), (2, 2, 4)),         # long tiles in two row blocks, 128 outputs along z exactly
 ]
 
 
