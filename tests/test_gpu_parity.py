@@ -71,6 +71,21 @@ SMALL = [
 ]
 
 
+# Cubic images at every length that has a fused z+y kernel and is not in SMALL or the benchmark list, at the length
+# itself (rows fill the transform length) or just below it (padded rows); 56, 72 and 120 also take the x passes
+# whose tiles of lines are counted across rows.
+FUSED_CUBIC = [(1, 2, 1, 10, 2), (1, 1, 2, 12, 3), (2, 1, 1, 14, 2), (1, 1, 1, 27, 3), (1, 2, 1, 32, 4),
+               (1, 1, 1, 36, 2), (1, 1, 2, 55, 3), (1, 2, 1, 56, 4), (1, 1, 1, 72, 3), (1, 1, 1, 79, 5),
+               (1, 1, 1, 100, 3), (1, 1, 1, 111, 2), (1, 1, 2, 118, 3), (1, 1, 1, 120, 2)]
+
+
+@pytest.mark.parametrize("shape", FUSED_CUBIC, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
+def test_fused_plane_kernel_lengths_full_compare(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand(500 + n + k, S, f, fo, n, k)
+    _check_full(oracle, inp, w, b, True, f"fused {shape}")
+
+
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
 def test_small_layers_full_compare(oracle, shape):
     S, f, fo, n, k = shape
