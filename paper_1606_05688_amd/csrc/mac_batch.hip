@@ -37,7 +37,9 @@ constexpr int MB_XP = 129;            // float2 between consecutive ox in the im
 constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
 constexpr int MB_WB = 2 * 16 * MB_WP; // floats per Wt buffer (real array, then imaginary array)
 
-__global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
+// (with one step the kernel needs 129 registers, one more than four waves per SIMD allow: held to 128)
+template <int KS>      // KS = steps of four taps: (k + 3) / 4, 1 to 3
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS == 1 ? 4 : 3)))) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
                                                    int nsc, int npencils, int accumulate)
@@ -59,8 +61,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     float2* Yp = Yt + (size_t)pencil * S * fo * N;
 
     // step-1 right operand of this lane: T[a = 4*st + kk][ox = ox0 + l16], zero beyond the last tap
-    const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
-    float tr[3], ti[3], ts[3];
+    float tr[KS], ti[KS], ts[KS];
     {
         // index (a * ox) mod N without a division: kk * ox and 4 * ox are below 4 N, later taps add 4 * ox
         const int ox = min(ox0 + l16, N - 1);
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
             q4 = q4 >= N ? q4 - N : q4;
         }
 #pragma unroll
-        for (int st = 0; st < 3; ++st) {
+        for (int st = 0; st < KS; ++st) {
             const int a = 4 * st + kk;
             float2 v = make_float2(0.f, 0.f);
             if (a < k) v = twg[q];
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
         xoff[r] = (size_t)min(gs, S - 1) * f * N + min(gox, N - 1);
     }
     const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
-    float2 xreg[XR], areg[2][3];
+    float2 xreg[XR], areg[2][KS];
     auto request = [&](int ic0) {
 #pragma unroll
         for (int r = 0; r < XR; ++r) xreg[r] = Xp[xoff[r] + (size_t)min(ic0 + xi[r], f - 1) * N];
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
             const int ic = min(ic0 + 2 * wave + h, fp - 1);
             const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
 #pragma unroll
-            for (int st = 0; st < 3; ++st)           // surplus taps meet a zero twiddle
+            for (int st = 0; st < KS; ++st)           // surplus taps meet a zero twiddle
                 areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
         }
     };
@@ -132,8 +133,8 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
             const float mi = ic0 + il < fp ? 1.f : 0.f;
             floatx4 q1 = floatx4{0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
 #pragma unroll
-            for (int st = 0; st < 3; ++st) {
-                if (st < ksteps) {                   // uniform
+            for (int st = 0; st < KS; ++st) {
+                {
                     const float ar = areg[h][st].x * mi, ai = areg[h][st].y * mi;
                     q1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar, tr[st], q1, 0, 0, 0);
                     q2 = __builtin_amdgcn_mfma_f32_16x16x4f32(ai, ti[st], q2, 0, 0, 0);
@@ -207,7 +208,10 @@ __global__ __launch_bounds__(256) void k_mac_batch(const float2* __restrict__ Xt
     }
 }
 
-__global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ Xt, const float2* __restrict__ A,
+// (one and two steps are held to 128 registers, four waves per SIMD: with two steps that costs 32 bytes of scratch
+// and is still 3-7 % faster, measured; the larger kernel above loses 10 % when its two-step form is held there)
+template <int KS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch8(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                     float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                     int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
                                                     int nsc, int npencils, int accumulate)
@@ -226,8 +230,7 @@ __global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ X
     float2* Yp = Yt + (size_t)pencil * S * fo * N;
 
     // step-1 right operand of this lane: T[a = 4*st + kk][ox = ox0 + l16], zero beyond the last tap
-    const int ksteps = (k + 3) >> 2;                 // at most 3 (k <= 12 is checked by the host)
-    float tr[3], ti[3], ts[3];
+    float tr[KS], ti[KS], ts[KS];
     {
         // index (a * ox) mod N without a division: kk * ox and 4 * ox are below 4 N, later taps add 4 * ox
         const int ox = min(ox0 + l16, N - 1);
@@ -238,7 +241,7 @@ __global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ X
             q4 = q4 >= N ? q4 - N : q4;
         }
 #pragma unroll
-        for (int st = 0; st < 3; ++st) {
+        for (int st = 0; st < KS; ++st) {
             const int a = 4 * st + kk;
             float2 v = make_float2(0.f, 0.f);
             if (a < k) v = twg[q];
@@ -265,14 +268,14 @@ __global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ X
     };
     // step-1 left operands of this wave's two images
     const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
-    float2 areg[2][3];
+    float2 areg[2][KS];
     auto request_a = [&](int ic0) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ic = min(ic0 + 2 * wave + h, fp - 1);
             const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
 #pragma unroll
-            for (int st = 0; st < 3; ++st)           // surplus taps meet a zero twiddle
+            for (int st = 0; st < KS; ++st)           // surplus taps meet a zero twiddle
                 areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
         }
     };
@@ -298,8 +301,8 @@ __global__ __launch_bounds__(256) void k_mac_batch8(const float2* __restrict__ X
             const int il = 2 * wave + h;                                                                  \
             const float mi = ic0 + il < fp ? 1.f : 0.f;                                                   \
             floatx4 q1 = floatx4{0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;                                   \
-            _Pragma("unroll") for (int st = 0; st < 3; ++st) {                                            \
-                if (st < ksteps) { /* uniform */                                                          \
+            _Pragma("unroll") for (int st = 0; st < KS; ++st) {                                            \
+                {                                                                                         \
                     const float ar = areg[h][st].x * mi, ai = areg[h][st].y * mi;                         \
                     q1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ar, tr[st], q1, 0, 0, 0);                   \
                     q2 = __builtin_amdgcn_mfma_f32_16x16x4f32(ai, ti[st], q2, 0, 0, 0);                   \
@@ -395,7 +398,10 @@ znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
     const int npencils = L.d.zc * L.d.Ny;
     const long long blocks = (long long)((npencils + 7) / 8) * noxt * njt * nsc * 8;
     if (blocks > 0x7fffffffll) return ZNNI_ERR_SHAPE;
-    auto* kernel = L.S <= 8 ? k_mac_batch8 : k_mac_batch;
+    // one instantiation per number of tap steps: the loops over them are straight-line code
+    const int ks = (L.d.kx + 3) / 4;
+    auto* kernel = L.S <= 8 ? (ks == 1 ? k_mac_batch8<1> : ks == 2 ? k_mac_batch8<2> : k_mac_batch8<3>)
+                            : (ks == 1 ? k_mac_batch<1> : ks == 2 ? k_mac_batch<2> : k_mac_batch<3>);
     kernel<<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo, L.d.kx, L.fp,
                                                            L.Mp, noxt, njt, nsc, npencils, accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
