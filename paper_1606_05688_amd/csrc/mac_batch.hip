@@ -37,9 +37,9 @@ constexpr int MB_XP = 129;            // float2 between consecutive ox in the im
 constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
 constexpr int MB_WB = 2 * 16 * MB_WP; // floats per Wt buffer (real array, then imaginary array)
 
-// (with one step the kernel needs 129 registers, one more than four waves per SIMD allow: held to 128)
+// (one and two steps are held to 128 registers, four waves per SIMD: 3-7 % faster for 5^3 to 8^3 kernels)
 template <int KS>      // KS = steps of four taps: (k + 3) / 4, 1 to 3
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS == 1 ? 4 : 3)))) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
                                                    int nsc, int npencils, int accumulate)
@@ -153,32 +153,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS == 1 ? 
         __syncthreads();
         if (ic0 + MB_IC < f) request(ic0 + MB_IC);   // in flight during step 2
         // ---- step 2 for ox = ox0 + 4*wave + q: left operand Wt[j = l16][i = 4*st + kk], right Xt[i][s = l16]
-        // all operands of the chunk first, then the products: the matrix instructions of one bin wait for nothing
-        float wr_[4][MB_IC / 4], wi_[4][MB_IC / 4];
-        float2 x_[4][MB_IC / 4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int oxl = 4 * wave + q;
-#pragma unroll
-            for (int st = 0; st < MB_IC / 4; ++st) {
-                const int o = st * 64 + lane;
-                wr_[q][st] = Wr[oxl * MB_WP + o];
-                wi_[q][st] = Wi[oxl * MB_WP + o];
-                x_[q][st] = Xl[oxl * MB_XP + o];
-            }
-        }
+        // the operands of four images for all four bins first, then their products; the scheduling barriers keep the
+        // two groups of a chunk apart, which is what lets the two-step form fit 128 registers without scratch
 #pragma unroll
         for (int st = 0; st < MB_IC / 4; ++st) {
+            float wr_[4], wi_[4];
+            float2 x_[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float wr = wr_[q][st], wi = wi_[q][st];
-                const float2 x = x_[q][st];
-                {
-                    p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
-                    p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
-                    p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
-                }
+                const int oxl = 4 * wave + q;
+                const int o = st * 64 + lane;
+                wr_[q] = Wr[oxl * MB_WP + o];
+                wi_[q] = Wi[oxl * MB_WP + o];
+                x_[q] = Xl[oxl * MB_XP + o];
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float wr = wr_[q], wi = wi_[q];
+                const float2 x = x_[q];
+                p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, x.x, p1[q], 0, 0, 0);
+                p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, x.y, p2[q], 0, 0, 0);
+                p3[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr + wi, x.x + x.y, p3[q], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     // ---- result through LDS: Ol[j][s][ox]; accumulator element e of lane: j = 4*kk + e, s = l16
@@ -209,7 +207,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS == 1 ? 
 }
 
 // (one and two steps are held to 128 registers, four waves per SIMD: with two steps that costs 32 bytes of scratch
-// and is still 3-7 % faster, measured; the larger kernel above loses 10 % when its two-step form is held there)
+// and is still 3-7 % faster, measured)
 template <int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch8(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                     float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
