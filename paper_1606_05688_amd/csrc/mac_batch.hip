@@ -206,8 +206,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
     }
 }
 
-// (one and two steps are held to 128 registers, four waves per SIMD: with two steps that costs 32 bytes of scratch
-// and is still 3-7 % faster, measured)
+// (one and two steps are held to 128 registers, four waves per SIMD; the operands of the second product are
+// staged four images at a time behind scheduling barriers, as above, and no scratch is needed: 3-7 % faster)
 template <int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch8(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                     float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
@@ -322,22 +322,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
         __syncthreads();                                                                                  \
         /* ---- step 2 for ox = ox0 + 4*wave + q: left operand Wt[j = l16][i = 4*st + kk]; all operands */ \
         /* first, then the products                                                                      */\
-        float wr_[4][MB_IC / 4], wi_[4][MB_IC / 4];                                                       \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
-            const int oxl = 4 * wave + q;                                                                 \
-            _Pragma("unroll") for (int st = 0; st < MB_IC / 4; ++st) {                                    \
-                wr_[q][st] = Wr[oxl * MB_WP + st * 64 + lane];                                            \
-                wi_[q][st] = Wi[oxl * MB_WP + st * 64 + lane];                                            \
-            }                                                                                             \
-        }                                                                                                 \
         _Pragma("unroll") for (int st = 0; st < MB_IC / 4; ++st) {                                        \
+            float wr_[4], wi_[4];                                                                         \
             _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                               \
-                const float wr = wr_[q][st], wi = wi_[q][st];                                             \
+                const int oxl = 4 * wave + q;                                                             \
+                wr_[q] = Wr[oxl * MB_WP + st * 64 + lane];                                                \
+                wi_[q] = Wi[oxl * MB_WP + st * 64 + lane];                                                \
+            }                                                                                             \
+            __builtin_amdgcn_sched_barrier(0);                                                            \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                               \
+                const float wr = wr_[q], wi = wi_[q];                                                     \
                 const float4 xp = XC[st][q >> 1];                                                         \
                 const float2 x = (q & 1) ? make_float2(xp.z, xp.w) : make_float2(xp.x, xp.y);             \
                 p1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr, lowcol ? x.x : x.y, p1[q], 0, 0, 0);     \
                 p2[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(wi, lowcol ? -x.y : x.x, p2[q], 0, 0, 0);    \
             }                                                                                             \
+            __builtin_amdgcn_sched_barrier(0);                                                            \
         }                                                                                                 \
     }
     int c = 0;
