@@ -100,9 +100,9 @@ void k_inv_yz(FusedArgs a)
             if (yo >= 0 && yo < noy) R[lb * QP + yo] = cconj(u[r]);
         }
     }
-    for (int e = t; e < ZC * (QP - noy); e += NTH) {         // the spare columns read by the last yo pair
-        const int row = e / (QP - noy), c = e - row * (QP - noy);
-        R[row * QP + noy + c] = make_float2(0.f, 0.f);
+    {
+        const int sh = QP - noy - 1;                         // one or two spare columns, read by the last yo pair
+        for (int e = t; e < (ZC << sh); e += NTH) R[(e >> sh) * QP + noy + (e & sh)] = make_float2(0.f, 0.f);
     }
     __syncthreads();
 
@@ -135,15 +135,19 @@ void k_inv_yz(FusedArgs a)
     // rows yo of out[imgo][xo]: real part of line l -> row 2l, minus imaginary part -> row 2l+1
     const float bj = a.bias ? a.bias[img % a.fo] : 0.f;
     float* dst = a.out + (((size_t)img * nox + xo) * noy) * noz;
-    // a wave per row, or per two or four rows where rows are at most 32 or 16 long
+    // a wave per line = pair of rows (one LDS read serves both), or per two or four lines where rows are at most 32
+    // or 16 long
     constexpr int LW = N <= 16 ? 16 : N <= 32 ? 32 : 64, RPI = 64 / LW;
-    for (int ll = (t / 64) * RPI + (t % 64) / LW; ll < noy; ll += (NTH / 64) * RPI) {
-        const float2* row = R + (ll >> 1) * P + (d.kz - 1);
+    for (int l = (t / 64) * RPI + (t % 64) / LW; l < np; l += (NTH / 64) * RPI) {
+        const float2* row = R + l * P + (d.kz - 1);
+        float* d0 = dst + (size_t)(2 * l) * noz;
+        const bool two = 2 * l + 1 < noy;
         for (int zo = t % LW; zo < noz; zo += LW) {
             const float2 c = row[zo];
-            float val = ((ll & 1) ? -c.y : c.x) + bj;
-            if (a.relu) val = fmaxf(val, 0.f);
-            dst[(size_t)ll * noz + zo] = val;
+            float v0 = c.x + bj, v1 = bj - c.y;
+            if (a.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+            d0[zo] = v0;
+            if (two) d0[noz + zo] = v1;
         }
     }
 }
