@@ -158,7 +158,6 @@ struct FusedFwdArgs {
     const float2* tw;      // [N]
     Dims d;
     int PP;                // pitch of the plane kept in LDS (ny + 1 or + 2, even)
-    int RP;                // pitch, in floats, of the raw input plane in LDS
 };
 
 template <int R1, int R2>
@@ -168,7 +167,7 @@ void k_fwd_zy(FusedFwdArgs a)
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1, TMAX = R1 > R2 ? R1 : R2;
     extern __shared__ float2 lds[];
-    const int PP = a.PP, RP = a.RP;
+    const int PP = a.PP, RP = a.d.nz;         // the raw plane keeps its pitch
     float2* tws = lds;                 // [N]
     float2* R = lds + N;               // in turn: raw plane [ny][RP] floats, exchange buffer [ZC][P], plane Pl[ZC][PP]
     const int t = threadIdx.x, NTH = blockDim.x;
@@ -191,20 +190,17 @@ void k_fwd_zy(FusedFwdArgs a)
     // slower with a whole plane per workgroup.)
     float* raw = reinterpret_cast<float*>(R);
     {
-        // element i = t + k * NTH of the plane is (row, col): one division, then steps of NTH with a carry
+        // a flat copy, rows at their pitch in memory.  (Padding the rows in LDS so that the lines a wave reads
+        // together spread over all banks costs index arithmetic per element -- these kernels are bound by issuing
+        // instructions, not by LDS -- and was measured 3-8 % slower at almost every length.)
         const int tot = ny * nz;
-        const int srow = NTH / nz, scol = NTH - srow * nz;
-        int row = t / nz, col = t - row * nz;
         for (int i0 = 0; i0 < tot; i0 += 8 * NTH) {
             float r[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) r[k] = plane[min(i0 + k * NTH + t, tot - 1)];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (i0 + k * NTH + t < tot) raw[row * RP + col] = r[k];
-                col += scol; row += srow;
-                if (col >= nz) { col -= nz; ++row; }
-            }
+            for (int k = 0; k < 8; ++k)
+                if (i0 + k * NTH + t < tot) raw[i0 + k * NTH + t] = r[k];
         }
     }
     __syncthreads();
@@ -336,10 +332,7 @@ static bool fused_shape(const LayerPlan& L, FusedShape* F, bool forward = false)
     const int N = d.Ny, zc = d.zc;
     const int cols = forward ? d.ny : d.noy;
     F->QP = cols + 2 - (cols & 1);
-    // rows of the raw plane 2*RP floats apart must spread the R2 neighbouring samples of the lines that a wave
-    // reads together over all LDS banks: RP = 2 mod 4 for R2 = 4, 4 mod 8 otherwise
-    const int mod = R2 == 4 ? 4 : 8;
-    F->RP = d.nz + ((mod / 2 - d.nz) % mod + mod) % mod;
+    F->RP = d.nz;
     F->nth = (zc * std::max(R1, R2) + 63) / 64 * 64;
     size_t region = sizeof(float2) * (size_t)zc * (N + 2);
     if (forward) region = std::max(region, sizeof(float) * (size_t)d.ny * F->RP);
@@ -404,7 +397,7 @@ znni_status launch_fwd_zy(const LayerPlan& L, const float* in, hipStream_t st)
     if (!fused_shape(L, &F, true)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const Dims& d = L.d;
     FusedFwdArgs a;
-    a.in = in; a.dst = L.buf1; a.tw = L.twy; a.d = d; a.PP = F.QP; a.RP = F.RP;
+    a.in = in; a.dst = L.buf1; a.tw = L.twy; a.d = d; a.PP = F.QP;
     const dim3 grid(d.nx, L.nimg);
     ZNNI_FUSED_CASES(k_fwd_zy)
 }
