@@ -123,3 +123,45 @@ def test_auto_call_runs_the_picked_primitive_and_matches_oracle(oracle, case):
     exp = oracle.conv3d(inp, w, b, relu=True)
     tol = oracle.tolerance(inp, w)[None, :, None, None, None]
     assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - exp) <= tol)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_match_oracle_on_both_routes(oracle, seed):
+    """Seeded random shapes (per-axis sizes and kernels, small batches, ragged everything): the direct primitive and
+    the transform route against the oracle, and therefore against each other."""
+    r = np.random.default_rng(9000 + seed)
+    S, f, fo = int(r.integers(1, 4)), int(r.integers(1, 6)), int(r.integers(1, 40))
+    k = tuple(int(v) for v in r.integers(1, 6, 3))
+    n = tuple(int(k[a] + r.integers(0, 60 if a == 2 else 14)) for a in range(3))
+    _say(f"[random] seed {seed}: S={S} f={f} fo={fo} n={n} k={k}")
+    inp, w, b = _rand(9100 + seed, S, f, fo, n, k)
+    exp = oracle.conv3d(inp, w, b, relu=True)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    got_d = _gpu(inp, w, b, True)
+    d = torch.device("cuda:0")
+    got_f = B.znni_conv3d_fft(torch.from_numpy(inp).to(d), torch.from_numpy(w).to(d), torch.from_numpy(b).to(d),
+                              relu=True).cpu().numpy().astype(np.float64)
+    assert got_d.shape == exp.shape and got_f.shape == exp.shape
+    assert np.all(np.abs(got_d - exp) <= tol), "direct"
+    assert np.all(np.abs(got_f - exp) <= tol), "transform"
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_cubic_shapes_match_oracle_on_both_routes(oracle, seed):
+    """Seeded random cubic images (8^3 to 72^3: the transform route's fused plane kernels, at and below their
+    lengths) on both routes against the oracle."""
+    r = np.random.default_rng(9500 + seed)
+    S, f, fo = int(r.integers(1, 3)), int(r.integers(1, 4)), int(r.integers(1, 4))
+    kk = int(r.integers(1, 6))
+    nn = int(r.integers(max(8, kk), 73))
+    n, k = (nn, nn, nn), (kk, kk, kk)
+    _say(f"[random cubic] seed {seed}: S={S} f={f} fo={fo} n={nn} k={kk}")
+    inp, w, b = _rand(9600 + seed, S, f, fo, n, k)
+    exp = oracle.conv3d(inp, w, b, relu=True)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    got_d = _gpu(inp, w, b, True)
+    d = torch.device("cuda:0")
+    got_f = B.znni_conv3d_fft(torch.from_numpy(inp).to(d), torch.from_numpy(w).to(d), torch.from_numpy(b).to(d),
+                              relu=True).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_d - exp) <= tol), "direct"
+    assert np.all(np.abs(got_f - exp) <= tol), "transform"
