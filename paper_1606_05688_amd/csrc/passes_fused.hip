@@ -157,7 +157,6 @@ struct FusedFwdArgs {
     float2* dst;           // X2'[img][x][oz][oy]
     const float2* tw;      // [N]
     Dims d;
-    int PP;                // pitch of the plane kept in LDS (ny + 1 or + 2, even)
 };
 
 template <int R1, int R2>
@@ -165,11 +164,11 @@ __global__ __launch_bounds__((fused_nth<R1, R2>())) __attribute__((amdgpu_waves_
 void k_fwd_zy(FusedFwdArgs a)
 {
     using TS = TwoStep<R1, R2>;
-    constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1, TMAX = R1 > R2 ? R1 : R2;
+    constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1;
     extern __shared__ float2 lds[];
-    const int PP = a.PP, RP = a.d.nz;         // the raw plane keeps its pitch
+    const int RP = a.d.nz;             // the raw plane keeps its pitch
     float2* tws = lds;                 // [N]
-    float2* R = lds + N;               // in turn: raw plane [ny][RP] floats, exchange buffer [ZC][P], plane Pl[ZC][PP]
+    float2* R = lds + N;               // in turn: raw plane [ny][RP] floats, exchange buffer and lines [ZC][P]
     const int t = threadIdx.x, NTH = blockDim.x;
     const int x = blockIdx.x, img = blockIdx.y;
     const Dims& d = a.d;
@@ -236,50 +235,27 @@ void k_fwd_zy(FusedFwdArgs a)
         for (int r = 0; r < R2; ++r) R[lb * P + q + R1 * r] = u[r];           // natural order per line
     }
     __syncthreads();
-    // untangle the two rows of every line; they become two neighbouring y of each oz row of the plane Pl
-    constexpr int UIT = (N / 2 + TMAX - 1) / TMAX;            // np * ZC <= (N / 2) * ZC elements, blockDim.x >= ZC * TMAX
-    // element e = t + k * NTH is (oz, l) = (e / np, e % np), lines fastest so that neighbouring lanes write
-    // neighbours: one division, then steps of NTH with a carry; past the end oz >= ZC
-    float4 g[UIT];
-    const int soz = NTH / np, sl = NTH - soz * np;
-    const int oz0 = t / np, l0 = t - oz0 * np;
-    {
-        int oz = oz0, l = l0;
-#pragma unroll
-        for (int k = 0; k < UIT; ++k) {
-            const int ozc = oz < ZC ? oz : 0;
-            const float2* row = R + l * P;
-            const float2 z1 = row[ozc], z2 = cconj(row[ozc ? N - ozc : 0]);
-            const float2 ev = cscale(cadd(z1, z2), 0.5f), od = cscale(mul_mi(csub(z1, z2)), 0.5f);
-            g[k] = make_float4(ev.x, ev.y, od.x, od.y);
-            l += sl; oz += soz;
-            if (l >= np) { l -= np; ++oz; }
-        }
-    }
-    __syncthreads();                          // the lines have been read: the region becomes Pl
-    {
-        int oz = oz0, l = l0;
-#pragma unroll
-        for (int k = 0; k < UIT; ++k) {
-            if (oz < ZC) *reinterpret_cast<float4*>(R + oz * PP + 2 * l) = g[k];
-            l += sl; oz += soz;
-            if (l >= np) { l -= np; ++oz; }
-        }
-    }
-    __syncthreads();
-
-    // ---- along y: one line per oz
+    // ---- along y: one line per oz.  Its sample y = 2l + h is row h of line l above, untangled on the way in:
+    // with Z = line l and W = conj(Z[N - oz]), row 0 is (Z[oz] + W) / 2 and row 1 is -i (Z[oz] - W) / 2.  R2 is even,
+    // so a thread sees rows of one parity only, and its lines l advance by R2 / 2 per sample: two addresses, then
+    // constant offsets.  (Untangling into a plane of its own first cost a pass through LDS each way, a barrier and
+    // index arithmetic per element.)
+    static_assert(R2 % 2 == 0, "a thread's samples must have one parity");
     if (in_a) {
-        const float2* line = R + la * PP;
+        const int oz = la, om = oz ? N - oz : 0;
+        const bool odd = ja & 1;
+        const float sg = odd ? -1.f : 1.f;
+        const float2* pz = R + (ja >> 1) * P + oz;
+        const float2* pw = R + (ja >> 1) * P + om;
 #pragma unroll
         for (int m = 0; m < R1; ++m) {
-            const int y = ja + R2 * m;
-            const float mk = y < ny ? 1.f : 0.f;
-            const float2 c = line[min(y, ny - 1)];
-            v[m] = make_float2(c.x * mk, c.y * mk);
+            const float mk = ja + R2 * m < ny ? 0.5f : 0.f;
+            const float2 z = pz[(R2 / 2) * P * m], w = pw[(R2 / 2) * P * m];
+            const float pr = fmaf(sg, w.x, z.x) * mk, qi = fmaf(-sg, w.y, z.y) * mk;
+            v[m] = odd ? make_float2(qi, -pr) : make_float2(pr, qi);
         }
     }
-    __syncthreads();                          // Pl has been read: the region is the exchange buffer again
+    __syncthreads();                          // the lines have been read: the region is the exchange buffer again
     if (in_a) TS::step_a(v, la, ja, tws, R);
     __syncthreads();
     if (q < R1) TS::step_b(u, lb, q, R);
@@ -397,7 +373,7 @@ znni_status launch_fwd_zy(const LayerPlan& L, const float* in, hipStream_t st)
     if (!fused_shape(L, &F, true)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const Dims& d = L.d;
     FusedFwdArgs a;
-    a.in = in; a.dst = L.buf1; a.tw = L.twy; a.d = d; a.PP = F.QP;
+    a.in = in; a.dst = L.buf1; a.tw = L.twy; a.d = d;
     const dim3 grid(d.nx, L.nimg);
     ZNNI_FUSED_CASES(k_fwd_zy)
 }
