@@ -46,12 +46,10 @@ template <int R1, int R2, bool FWD>
 constexpr int fused_waves()
 {
     constexpr int N = R1 * R2;
-    // measured (32 -> 32 images, batches of 1.5 GB): forward at 100 held to 80 registers (two over; three
-    // workgroups per CU instead of two) 18 % faster, inverse at 96 held to 64 (two over) 14 % faster, forward at 56
-    // and inverse at 112 3-4 %; where the step is further away (forward at 64, 72, 96, 112, 120) the spills cost
-    // 5 to 25 %
-    if (FWD && (N == 100 || N == 120)) return 6;
-    if (FWD && N == 56) return 8;
+    // measured (32 -> 32 images, batches of 1.5 GB): inverse at 96 held to 64 registers (two over; three workgroups
+    // per CU instead of two) 14 % faster, inverse at 112 3-4 %; where the step is further away the spills cost 5 to
+    // 25 %.  (The forward kernels need no budget: since they untangle on the way into the y transform they use 38
+    // to 68 registers.)
     if (!FWD && (N == 96 || N == 112)) return 8;
     return 4;
 }
@@ -211,9 +209,8 @@ void k_fwd_zy(FusedFwdArgs a)
         const float ma = la < np ? 1.f : 0.f, mb = (la < np && ya + 1 < ny) ? 1.f : 0.f;
         const float* ra = raw + ya * RP;
         const float* rb = raw + min(ya + 1, ny - 1) * RP;
-        // rows that fill the transform length: constant offsets, no padding in z.  (Not at 120, whose kernel is
-        // held to 80 registers: with this second path it spills more and is 8 % slower, measured.)
-        if (N != 120 && nz == N) {
+        // rows that fill the transform length: constant offsets, no padding in z
+        if (nz == N) {
 #pragma unroll
             for (int m = 0; m < R1; ++m) v[m] = make_float2(ra[ja + R2 * m] * ma, rb[ja + R2 * m] * mb);
         } else {
@@ -277,9 +274,9 @@ struct FusedShape { int R1, R2, QP, RP, nth; size_t lds; };
 
 // The in-register split of each supported length, measured best per length (32 -> 32 images, batches of 1.5 GB):
 // mostly R1 x 8 -- fewer, fatter threads than the separate passes use would not cover a plane's lines in one
-// round --, with the squarer splits 6 x 6, 8 x 10 and 8 x 12 10 to 15 % ahead at 36, 80 and 96.  At 120 the inverse
-// kernel runs two workgroups per CU with 10 x 12 (12 threads per line) and only one with 15 x 8: 40 % faster; the
-// forward kernel is 12 % slower with it and keeps 15 x 8.
+// round --, with the squarer splits 6 x 6, 8 x 10 and 8 x 12 10 to 15 % ahead at 36, 80 and 96.  At 120 both
+// kernels take 10 x 12 (12 threads per line instead of 15): the inverse kernel then runs two workgroups per CU instead
+// of one and is 40 % faster, the forward kernel is 10 % faster with it than with 15 x 8.
 static bool fused_split(int N, bool forward, int* R1, int* R2)
 {
     static const int tab[][3] = {{8, 2, 4},    {10, 5, 2},  {12, 3, 4},  {14, 7, 2},  {16, 4, 4},  {20, 5, 4},
