@@ -293,6 +293,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
             case 96: return launch_one<12, 8, KIND>(a, grid, st);
             case 100: return launch_one<5, 20, KIND>(a, grid, st);
             case 112: return launch_one<14, 8, KIND>(a, grid, st);
+            case 128: return launch_one<16, 8, KIND>(a, grid, st);
         }
     }
     if constexpr (KIND == P_INV_X) {

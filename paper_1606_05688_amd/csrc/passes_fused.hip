@@ -42,6 +42,16 @@ struct FusedArgs {
 // CU and are held below it.
 template <int R1, int R2>
 constexpr int fused_nth() { return ((R1 * R2 / 2 + 1) * (R1 > R2 ? R1 : R2) + 63) / 64 * 64; }
+// The forward kernel can do with N / 2 lines per direction instead of N / 2 + 1 (see there).  It does where that
+// saves a wave per workgroup and was measured faster (7 to 21 % at 32, 48, 64; 2 % at 96) and at 128, which then fits
+// one round of 1024 threads; where no wave is saved the special cases cost up to 10 % (24), and at 112 it was 5 %
+// slower in spite of the wave saved.
+constexpr bool fused_fwd_packs(int N) { return N == 32 || N == 48 || N == 64 || N == 96 || N == 128; }
+template <int R1, int R2>
+constexpr int fused_nth_fwd()
+{
+    return ((R1 * R2 / 2 + (fused_fwd_packs(R1 * R2) ? 0 : 1)) * (R1 > R2 ? R1 : R2) + 63) / 64 * 64;
+}
 template <int R1, int R2, bool FWD>
 constexpr int fused_waves()
 {
@@ -51,6 +61,9 @@ constexpr int fused_waves()
     // 25 %.  (The forward kernels need no budget: since they untangle on the way into the y transform they use 38
     // to 68 registers.)
     if (!FWD && (N == 96 || N == 112)) return 8;
+    // forward at 128: 1024 threads; at 76 registers one workgroup has a CU to itself, held to 64 (16 bytes of
+    // scratch) two share it: 0.24 -> 0.19 ms for 40 images of 128^3
+    if (FWD && N == 128) return 8;
     return 4;
 }
 
@@ -157,16 +170,22 @@ struct FusedFwdArgs {
     Dims d;
 };
 
+// Lines per transform: along z two real rows ride in one complex line, N / 2 lines at most.  Along y the plane has
+// N / 2 + 1 lines (oz = 0 ... N / 2), but the first and the last are real sequences (sums and alternating sums of
+// real rows): with PACK they ride together as real and imaginary part of line 0 and are separated, by the same
+// symmetry, when the rows are stored -- N / 2 lines in both directions.
 template <int R1, int R2>
-__global__ __launch_bounds__((fused_nth<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, true>()))))
+__global__ __launch_bounds__((fused_nth_fwd<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, true>()))))
 void k_fwd_zy(FusedFwdArgs a)
 {
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1;
+    constexpr bool PACK = fused_fwd_packs(N);
+    constexpr int NL = PACK ? N / 2 : ZC;
     extern __shared__ float2 lds[];
     const int RP = a.d.nz;             // the raw plane keeps its pitch
     float2* tws = lds;                 // [N]
-    float2* R = lds + N;               // in turn: raw plane [ny][RP] floats, exchange buffer and lines [ZC][P]
+    float2* R = lds + N;               // in turn: raw plane [ny][RP] floats, exchange buffer and lines [NL][P]
     const int t = threadIdx.x, NTH = blockDim.x;
     const int x = blockIdx.x, img = blockIdx.y;
     const Dims& d = a.d;
@@ -176,8 +195,8 @@ void k_fwd_zy(FusedFwdArgs a)
     for (int q = t; q < N; q += NTH) tws[q] = a.tw[q];
 
     const int ja = t % R2, la = t / R2;
-    const bool in_a = la < ZC;
-    const int lb = t % ZC, q = t / ZC;
+    const bool in_a = la < NL;
+    const int lb = t % NL, q = t / NL;
     float2 v[R1];
     float2 u[R2];
 
@@ -239,17 +258,29 @@ void k_fwd_zy(FusedFwdArgs a)
     // index arithmetic per element.)
     static_assert(R2 % 2 == 0, "a thread's samples must have one parity");
     if (in_a) {
-        const int oz = la, om = oz ? N - oz : 0;
+        const int oz = la;
         const bool odd = ja & 1;
-        const float sg = odd ? -1.f : 1.f;
-        const float2* pz = R + (ja >> 1) * P + oz;
-        const float2* pw = R + (ja >> 1) * P + om;
+        if (!PACK || oz) {
+            const float sg = odd ? -1.f : 1.f;
+            const float2* pz = R + (ja >> 1) * P + oz;
+            const float2* pw = R + (ja >> 1) * P + (oz ? N - oz : 0);
 #pragma unroll
-        for (int m = 0; m < R1; ++m) {
-            const float mk = ja + R2 * m < ny ? 0.5f : 0.f;
-            const float2 z = pz[(R2 / 2) * P * m], w = pw[(R2 / 2) * P * m];
-            const float pr = fmaf(sg, w.x, z.x) * mk, qi = fmaf(-sg, w.y, z.y) * mk;
-            v[m] = odd ? make_float2(qi, -pr) : make_float2(pr, qi);
+            for (int m = 0; m < R1; ++m) {
+                const float mk = ja + R2 * m < ny ? 0.5f : 0.f;
+                const float2 z = pz[(R2 / 2) * P * m], w = pw[(R2 / 2) * P * m];
+                const float pr = fmaf(sg, w.x, z.x) * mk, qi = fmaf(-sg, w.y, z.y) * mk;
+                v[m] = odd ? make_float2(qi, -pr) : make_float2(pr, qi);
+            }
+        } else {
+            // line 0 carries oz = 0 (real part) and oz = N / 2 (imaginary part): at these two bins the rows of a
+            // line are simply the real and the imaginary part of the line's value
+            const float2* pz = R + (ja >> 1) * P;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const float mk = ja + R2 * m < ny ? 1.f : 0.f;
+                const float2 z = pz[(R2 / 2) * P * m], w = pz[(R2 / 2) * P * m + N / 2];
+                v[m] = odd ? make_float2(z.y * mk, w.y * mk) : make_float2(z.x * mk, w.x * mk);
+            }
         }
     }
     __syncthreads();                          // the lines have been read: the region is the exchange buffer again
@@ -263,10 +294,19 @@ void k_fwd_zy(FusedFwdArgs a)
     }
     __syncthreads();
     float2* dst = a.dst + (((size_t)img * d.nx + x) * ZC) * N;
-    // a wave per row, or per two or four rows where rows are at most 32 or 16 long
+    // a wave per row, or per two or four rows where rows are at most 32 or 16 long; rows 0 and N / 2 come out of
+    // line 0 = C: (C[oy] + conj(C[N - oy])) / 2 and -i (C[oy] - conj(C[N - oy])) / 2
     constexpr int LW = N <= 16 ? 16 : N <= 32 ? 32 : 64, RPI = 64 / LW;
-    for (int l = (t / 64) * RPI + (t % 64) / LW; l < ZC; l += (NTH / 64) * RPI)
-        for (int e = t % LW; e < N; e += LW) dst[(size_t)l * N + e] = R[l * P + e];
+    for (int l = (t / 64) * RPI + (t % 64) / LW; l < ZC; l += (NTH / 64) * RPI) {
+        if (!PACK || (l != 0 && l != N / 2)) {
+            for (int e = t % LW; e < N; e += LW) dst[(size_t)l * N + e] = R[l * P + e];
+        } else {
+            for (int e = t % LW; e < N; e += LW) {
+                const float2 c = R[e], m = cconj(R[e ? N - e : 0]);
+                dst[(size_t)l * N + e] = l ? cscale(mul_mi(csub(c, m)), 0.5f) : cscale(cadd(c, m), 0.5f);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------- host side
@@ -284,6 +324,7 @@ static bool fused_split(int N, bool forward, int* R1, int* R2)
                                  {56, 7, 8},   {64, 8, 8},  {72, 9, 8},  {80, 8, 10}, {96, 8, 12}, {100, 10, 10},
                                  {112, 7, 16}, {120, 15, 8}};
     if (N == 120) { *R1 = 10; *R2 = 12; return true; }
+    if (N == 128 && forward) { *R1 = 8; *R2 = 16; return true; }    // one round of 1024 threads: 64 lines x 16
     for (const auto& e : tab)
         if (e[0] == N) { *R1 = e[1]; *R2 = e[2]; return true; }
     return false;
@@ -306,11 +347,12 @@ static bool fused_shape(const LayerPlan& L, FusedShape* F, bool forward = false)
     const int cols = forward ? d.ny : d.noy;
     F->QP = cols + 2 - (cols & 1);
     F->RP = d.nz;
-    F->nth = (zc * std::max(R1, R2) + 63) / 64 * 64;
-    size_t region = sizeof(float2) * (size_t)zc * (N + 2);
+    const int lines = forward && fused_fwd_packs(N) ? N / 2 : zc;      // the forward kernel may pack two lines into one
+    F->nth = (lines * std::max(R1, R2) + 63) / 64 * 64;
+    size_t region = sizeof(float2) * (size_t)lines * (N + 2);
     if (forward) region = std::max(region, sizeof(float) * (size_t)d.ny * F->RP);
     F->lds = sizeof(float2) * (size_t)N + region;
-    return F->nth <= 1024 && F->lds <= 64 * 1024;
+    return F->nth <= 1024 && F->lds <= 80 * 1024;             // two workgroups per CU at least
 }
 
 bool fused_inv_yz_available(const LayerPlan& L)
@@ -360,6 +402,7 @@ static znni_status launch_fused(void (*kernel)(Args), const Args& a, const Fused
         case 716: return launch_fused(KERNEL<7, 16>, a, F, grid, st);                              \
         case 1508: return launch_fused(KERNEL<15, 8>, a, F, grid, st);                             \
         case 1012: return launch_fused(KERNEL<10, 12>, a, F, grid, st);                            \
+        case 816: return launch_fused(KERNEL<8, 16>, a, F, grid, st);                              \
     }                                                                                              \
     return ZNNI_ERR_UNSUPPORTED_SIZE;
 
