@@ -67,12 +67,26 @@ constexpr int fused_waves()
     return 4;
 }
 
+// The inverse kernel can pack the same two lines: rows oz = 0 and N / 2 of the plane are spectra of real sequences,
+// so c = row 0 + i row N/2 comes back from the inverse y transform as (row 0's values, row N/2's values).  Measured:
+// 11-12 % faster at 32 and 64 (a wave less per workgroup), a tie at 48, 3 % slower at 96; at 128 the kernel it makes
+// possible (1024 threads, held to 64 registers with 36 bytes of scratch) is 13 % slower than the two separate
+// passes on 40 images of 128^3 and 16-19 % faster on 32 or 8 images: not used there.
+constexpr bool fused_inv_packs(int N) { return N == 32 || N == 64; }
 template <int R1, int R2>
-__global__ __launch_bounds__((fused_nth<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, false>()))))
+constexpr int fused_nth_inv()
+{
+    return ((R1 * R2 / 2 + (fused_inv_packs(R1 * R2) ? 0 : 1)) * (R1 > R2 ? R1 : R2) + 63) / 64 * 64;
+}
+
+template <int R1, int R2>
+__global__ __launch_bounds__((fused_nth_inv<R1, R2>())) __attribute__((amdgpu_waves_per_eu((fused_waves<R1, R2, false>()))))
 void k_inv_yz(FusedArgs a)
 {
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, ZC = N / 2 + 1;
+    constexpr bool PACK = fused_inv_packs(N);
+    constexpr int NL = PACK ? N / 2 : ZC;     // lines per transform
     extern __shared__ float2 lds[];
     const int QP = a.QP;
     float2* tws = lds;                 // [N]
@@ -85,18 +99,27 @@ void k_inv_yz(FusedArgs a)
     for (int q = t; q < N; q += NTH) tws[q] = a.tw[q];
 
     const int ja = t % R2, la = t / R2;       // step A: (line la, sample offset ja)
-    const bool in_a = la < ZC;
-    const int lb = t % ZC, q = t / ZC;        // step B: (line lb, output offset q); work only for q < R1
+    const bool in_a = la < NL;
+    const int lb = t % NL, q = t / NL;        // step B: (line lb, output offset q); work only for q < R1
     float2 v[R1];
     float2 u[R2];
 
     // ---- inverse along y: the rows oz of the plane, conj . forward . conj
     if (in_a) {
         const float2* row = a.src + (((size_t)img * ZC + la) * nox + xo) * d.ldn;
+        if (!PACK || la) {
 #pragma unroll
-        for (int m = 0; m < R1; ++m) {
-            const float2 x = row[ja + R2 * m];
-            v[m] = make_float2(x.x, -x.y);
+            for (int m = 0; m < R1; ++m) {
+                const float2 x = row[ja + R2 * m];
+                v[m] = make_float2(x.x, -x.y);
+            }
+        } else {                              // line 0 = row 0 + i row N/2, conjugated
+            const float2* rown = row + (size_t)(N / 2) * nox * d.ldn;
+#pragma unroll
+            for (int m = 0; m < R1; ++m) {
+                const float2 x = row[ja + R2 * m], y = rown[ja + R2 * m];
+                v[m] = make_float2(x.x - y.y, -(x.y + y.x));
+            }
         }
     }
     __syncthreads();                          // twiddles are in LDS
@@ -108,7 +131,14 @@ void k_inv_yz(FusedArgs a)
 #pragma unroll
         for (int r = 0; r < R2; ++r) {
             const int yo = q + R1 * r - (d.ky - 1);
-            if (yo >= 0 && yo < noy) R[lb * QP + yo] = cconj(u[r]);
+            if (yo >= 0 && yo < noy) {
+                if (!PACK || lb) {
+                    R[lb * QP + yo] = cconj(u[r]);
+                } else {                      // real part: row 0, imaginary part of the conjugate: row N/2
+                    R[yo] = make_float2(u[r].x, 0.f);
+                    R[(N / 2) * QP + yo] = make_float2(-u[r].y, 0.f);
+                }
+            }
         }
     }
     {
@@ -347,9 +377,9 @@ static bool fused_shape(const LayerPlan& L, FusedShape* F, bool forward = false)
     const int cols = forward ? d.ny : d.noy;
     F->QP = cols + 2 - (cols & 1);
     F->RP = d.nz;
-    const int lines = forward && fused_fwd_packs(N) ? N / 2 : zc;      // the forward kernel may pack two lines into one
+    const int lines = (forward ? fused_fwd_packs(N) : fused_inv_packs(N)) ? N / 2 : zc;   // two lines may ride as one
     F->nth = (lines * std::max(R1, R2) + 63) / 64 * 64;
-    size_t region = sizeof(float2) * (size_t)lines * (N + 2);
+    size_t region = sizeof(float2) * (size_t)(forward ? lines : zc) * (N + 2);      // the inverse plane Q has zc rows
     if (forward) region = std::max(region, sizeof(float) * (size_t)d.ny * F->RP);
     F->lds = sizeof(float2) * (size_t)N + region;
     return F->nth <= 1024 && F->lds <= 80 * 1024;             // two workgroups per CU at least
