@@ -15,12 +15,13 @@
 // writes X2'[img][x][oz][oy] as whole rows; the intermediate tensor X1 never exists.  The forward x pass that
 // follows reads X2' with a transposing load (P_FWD_XT in passes_fast.hip).
 //
-// Every line is transformed by the same two in-register steps as in passes_fast.hip (two_step.h), all zc lines
-// of the plane in one round (one thread per (line, sample offset)).  The exchange buffer of the two steps, the
-// plane between the two transforms and (forward) the raw input plane take turns in ONE region of zc x (N + 2)
-// complex values: whatever is read next sits in registers across the barrier that hands the region over.  That
-// is 42 KB at N = 100 -- three workgroups per CU, where separate regions (83 KB) left room for one, and a
-// workgroup's life is a chain of memory round trips and barriers that only other workgroups can fill.
+// Every line is transformed by the same two in-register steps as in passes_fast.hip (two_step.h), all lines of the
+// plane in one round (one thread per (line, sample offset); zc lines, or N / 2 where the two real ones ride as one,
+// see the kernels).  The exchange buffer of the two steps, the plane between the two transforms (inverse) and the
+// raw input plane (forward) take turns in ONE region of zc x (N + 2) complex values: whatever is read next sits in
+// registers across the barrier that hands the region over.  That is 42 KB at N = 100 -- three workgroups per CU,
+// where separate regions (83 KB) left room for one, and a workgroup's life is a chain of memory round trips and
+// barriers that only other workgroups can fill.  The forward kernel exists up to length 128, the inverse up to 120.
 #include "two_step.h"
 #include <algorithm>
 #include "znni_internal.h"
