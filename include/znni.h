@@ -39,7 +39,7 @@ typedef enum {
     ZNNI_ERR_SHAPE = -2,            /* S, f, f' < 1, k < 1 or k > n on an axis, or a count too large for the launch grid */
     ZNNI_ERR_UNSUPPORTED_SIZE = -3, /* no supported transform size n~ >= n                                 */
     ZNNI_ERR_WORKSPACE = -4,        /* workspace smaller than znni_conv3d_fft_workspace reports            */
-    ZNNI_ERR_FLAGS = -5,            /* unknown flag bit                                                    */
+    ZNNI_ERR_FLAGS = -5,            /* unknown flag bit, or more than one of the ZNNI_MAC_* bits           */
     ZNNI_ERR_HIP = -6,              /* a HIP call or kernel launch failed                                  */
     ZNNI_ERR_ALIGN = -7             /* a device pointer is not 16-byte aligned (workspace: 256-byte)       */
 } znni_status;
@@ -186,7 +186,9 @@ znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int
  * were measured on MI355X and writes the pick to *primitive; est_ms, if not NULL, receives the two estimates in
  * milliseconds (index = primitive; negative = that primitive does not take this shape).
  * znni_conv3d_workspace_v / znni_conv3d_v are the workspace query and the layer call of the picked primitive;
- * arguments as for znni_conv3d_fft_v (ZNNI_MAC_REFERENCE is rejected when the direct route is picked).
+ * arguments as for znni_conv3d_fft_v.  When the direct route is picked, ZNNI_MAC_SINGLE and ZNNI_MAC_BATCH are
+ * accepted and ignored (they choose between forms of the transform route only) and ZNNI_MAC_REFERENCE is rejected
+ * with ZNNI_ERR_FLAGS.
  */
 enum { ZNNI_PRIMITIVE_FFT = 0, ZNNI_PRIMITIVE_DIRECT = 1 };
 

@@ -234,12 +234,20 @@ static znni_status choose_division(int S, int f, int fo, const int n[3], const i
     return ZNNI_OK;
 }
 
+// Known bits only, and at most one of the three bits that pick a multiply-accumulate form.
+static bool flags_ok(unsigned flags)
+{
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
+    const unsigned forms = flags & (unsigned)(ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH);
+    return (forms & (forms - 1)) == 0;
+}
+
 static znni_status validate(int S, int f, int fo, const int n[3], const int k[3], const float* in,
                             const float* w, float* out, unsigned flags, void* workspace,
                             size_t workspace_bytes, LayerPlan* L)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return ZNNI_ERR_FLAGS;
+    if (!flags_ok(flags)) return ZNNI_ERR_FLAGS;
     znni_status rc = make_plan(S, f, fo, n, k, workspace, L);
     if (rc) return rc;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u) return ZNNI_ERR_ALIGN;
@@ -361,7 +369,7 @@ const char* znni_status_string(znni_status st)
         case ZNNI_ERR_SHAPE: return "bad layer shape (need S,f,f' >= 1 and 1 <= k <= n on every axis, counts within launch limits)";
         case ZNNI_ERR_UNSUPPORTED_SIZE: return "no supported transform size for this image edge";
         case ZNNI_ERR_WORKSPACE: return "workspace too small";
-        case ZNNI_ERR_FLAGS: return "unknown flag bit";
+        case ZNNI_ERR_FLAGS: return "unknown flag bit, or more than one multiply-accumulate form requested";
         case ZNNI_ERR_HIP: return "HIP call or kernel launch failed";
         case ZNNI_ERR_ALIGN: return "device pointer not sufficiently aligned";
     }
@@ -459,7 +467,7 @@ znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const
                                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return ZNNI_ERR_FLAGS;
+    if (!flags_ok(flags)) return ZNNI_ERR_FLAGS;
     Division D;
     znni_status rc = choose_division(S, f, fo, n, k, workspace_bytes, &D);
     if (rc) return rc;

@@ -108,7 +108,11 @@ znni_status znni_conv3d_v(int S, int f, int fo, const int n[3], const int k[3], 
         if (flags & ZNNI_MAC_REFERENCE) return ZNNI_ERR_FLAGS;
         // the transform route's stricter alignment is asked of both, so a call does not depend on the pick
         if (in && w && out && (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u)) return ZNNI_ERR_ALIGN;
-        return znni_conv3d_direct_v(S, f, fo, n, k, in, w, bias, out, flags, workspace, workspace_bytes, stream);
+        // the hints that pick a multiply-accumulate form mean nothing to the direct route: validated, then dropped
+        const unsigned forms = flags & (unsigned)(ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH);
+        if (forms == (unsigned)(ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return ZNNI_ERR_FLAGS;
+        return znni_conv3d_direct_v(S, f, fo, n, k, in, w, bias, out, flags & ~forms, workspace, workspace_bytes,
+                                    stream);
     }
     return znni_conv3d_fft_v(S, f, fo, n, k, in, w, bias, out, flags, workspace, workspace_bytes, stream);
 }

@@ -60,28 +60,40 @@ def make_inputs(layer: Layer, seed: int = 0):
     return inp, w, bias
 
 
-def sample_points(layer: Layer, n_random: int, seed: int = 1, block: int = 4):
-    """Output positions (s, j, x, y, z) for spot checks of layers too large for a full CPU evaluation.
+def sample_points(layer: Layer, n_random: int = 1 << 20, seed: int = 1, block: int = 8, midplanes: bool = True):
+    """Output positions (s, j, x, y, z) for checks of layers too large for a full CPU evaluation.
 
-    Every output image contributes its 8 corner blocks (block^3 voxels each) and the centres of its 6
-    faces; n_random further positions are drawn uniformly over the whole output tensor.
+    Every output image contributes its 8 corner blocks (block^3 voxels each) and, at the centre of each of its
+    6 faces, a patch of block x block voxels, two voxels deep.  One complete output image (the middle one of the
+    last input of the batch) contributes its three mid-planes x = m/2, y = m/2, z = m/2.  n_random further
+    positions are drawn uniformly over the whole output tensor.  Duplicates are removed; rows come back sorted.
     """
     m = layer.n_out
     b = min(block, m)
+    dp = min(2, m)
     rng = np.random.default_rng(seed)
-    pts = []
-    lo = np.arange(b)
-    hi = np.arange(m - b, m)
     c = m // 2
-    faces = [(0, c, c), (m - 1, c, c), (c, 0, c), (c, m - 1, c), (c, c, 0), (c, c, m - 1)]
+    lo, hi = np.arange(b), np.arange(m - b, m)
+    mid = np.arange(max(c - b // 2, 0), max(c - b // 2, 0) + b)
+    near, far = np.arange(dp), np.arange(m - dp, m)
+
+    def grid(xs, ys, zs):
+        return np.stack(np.meshgrid(xs, ys, zs, indexing="ij"), -1).reshape(-1, 3)
+
+    per_image = [grid(xs, ys, zs) for xs in (lo, hi) for ys in (lo, hi) for zs in (lo, hi)]
+    per_image += [grid(near, mid, mid), grid(far, mid, mid), grid(mid, near, mid), grid(mid, far, mid),
+                  grid(mid, mid, near), grid(mid, mid, far)]
+    per_image = np.unique(np.concatenate(per_image, 0), axis=0)
+    pts = []
     for s in range(layer.S):
         for j in range(layer.fo):
-            for xs in (lo, hi):
-                for ys in (lo, hi):
-                    for zs in (lo, hi):
-                        g = np.stack(np.meshgrid(xs, ys, zs, indexing="ij"), -1).reshape(-1, 3)
-                        pts.append(np.concatenate([np.full((len(g), 1), s), np.full((len(g), 1), j), g], 1))
-            pts.append(np.array([[s, j, *p] for p in faces]))
+            pts.append(np.concatenate([np.full((len(per_image), 1), s), np.full((len(per_image), 1), j),
+                                       per_image], 1))
+    if midplanes:
+        s, j = layer.S - 1, layer.fo // 2
+        full = np.arange(m)
+        for g in (grid([c], full, full), grid(full, [c], full), grid(full, full, [c])):
+            pts.append(np.concatenate([np.full((len(g), 1), s), np.full((len(g), 1), j), g], 1))
     if n_random > 0:
         r = np.stack([rng.integers(0, layer.S, n_random), rng.integers(0, layer.fo, n_random),
                       rng.integers(0, m, n_random), rng.integers(0, m, n_random),

@@ -92,6 +92,9 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
     assert call(flags=16) == -5 and call(flags=0x80000001) == -5
+    # at most one of the three bits that pick a multiply-accumulate form
+    assert call(flags=2 | 4) == -5 and call(flags=4 | 8) == -5 and call(flags=1 | 2 | 8) == -5
+    assert call(flags=1 | 4, wsb=1024) == -4 and call(flags=8, wsb=1024) == -4     # one of them: validation goes on
     assert call(inp=p + 4) == -7 and call(out=p + 8) == -7 and call(wsp=ws + 128) == -7
     assert call(wsb=1024) == -4
     need = B.znni_conv3d_fft_workspace(1, 1, 1, 8, 3)
@@ -186,6 +189,7 @@ def test_sublayer_division_follows_the_stated_preference():
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 16, 0x100000, full, None) == -5
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 4 | 8, 0x100000, full, None) == -5
 
 
 def test_primitive_choice_follows_kernel_size_and_image_count():
@@ -215,6 +219,11 @@ def test_primitive_choice_follows_kernel_size_and_image_count():
     p = 0x1000
     assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 40, None) == -5
     assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 0, 0x100000, 16, None) == -4
+    # the form hints of the transform route do not change what a call does when the direct route is picked: they
+    # pass validation (the call goes on to the workspace check) unless both are given
+    for hint in (4, 8, 1 | 4):
+        assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, hint, 0x100000, 16, None) == -4
+    assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 4 | 8, 0x100000, 16, None) == -5
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), None, p, None, p, 0, 0x100000, 1 << 20, None) == -1
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 20, None) == -5
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p + 1, 0, 0x100000, 1 << 20, None) == -7

@@ -70,6 +70,37 @@ def test_budgeted_layer_matches_oracle(oracle, case):
         assert torch.equal(got, whole)               # same arithmetic per input: bitwise equal
 
 
+def test_largest_benchmark_layer_under_half_its_workspace(largest_layer_case):
+    """The division the benchmark times: 48 -> 48 images of 320^3 with half of the whole-layer workspace, i.e.
+    blocks of input and output images whose products are added into output spectra that live in a buffer of
+    their own.  Compared with the whole-layer result on every voxel and with the oracle on the declared sample."""
+    C = largest_layer_case
+    L = C.layer
+    n, k = (L.n,) * 3, (L.k,) * 3
+    budget = B.znni_conv3d_fft_workspace(L.S, L.f, L.fo, n, k) // 2
+    sub, need = B.znni_conv3d_fft_sublayers(L.S, L.f, L.fo, n, k, budget)
+    _say(f"[sublayers] {L.name}: division S_i={sub[0]} f_i={sub[1]} f'_i={sub[2]}, {need} of {budget} bytes")
+    assert sub[0] == 1 and sub[1] < L.f and sub[2] < L.fo
+    d = torch.device("cuda:0")
+    ti, tw, tb = (torch.from_numpy(t).to(d) for t in (C.inp, C.w, C.bias))
+    ws = torch.empty(budget, dtype=torch.uint8, device=d)
+    ws.fill_(0xFF)
+    got = B.znni_conv3d_fft_budget(ti, tw, tb, relu=L.relu, workspace=ws)
+    torch.cuda.synchronize()
+    del ws
+    whole = B.znni_conv3d_fft(ti, tw, tb, relu=L.relu)
+    torch.cuda.synchronize()
+    tj = torch.from_numpy(C.tol_j).to(d).float()[None, :, None, None, None]
+    worst = float(((got - whole).abs() / tj).max())
+    _say(f"    all {got.numel()} voxels: max |budget - whole| / tol = {worst:.3e}")
+    assert worst <= 0.1
+    tp = torch.from_numpy(C.pts.astype(np.int64)).to(d)
+    g = got[tp[:, 0], tp[:, 1], tp[:, 2], tp[:, 3], tp[:, 4]].cpu().numpy().astype(np.float64)
+    ratio = np.abs(g - C.exp) / C.tol
+    _say(f"    {len(C.pts)} sampled voxels against the oracle: max err/tol {ratio.max():.3e}")
+    assert np.all(ratio <= 1.0)
+
+
 def test_blocks_accumulate_with_either_multiply_accumulate_form(oracle):
     S, f, fo, n, k = 1, 24, 40, (24, 20, 16), (3, 5, 2)
     budget = int(0.25 * B.znni_conv3d_fft_workspace(S, f, fo, n, k))
