@@ -111,6 +111,24 @@ znni_status znni_conv3d_fft(int S, int f, int fo, int n, int k,
                             unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * znni_conv3d_fft_v for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same tensors, flags, result (bit for bit)
+ * and status codes as znni_conv3d_fft_v, but the workspace is an array of ZNNI_STATIC_SCRATCH_BYTES bytes that
+ * is part of the library's device code: every GPU the library runs on holds one copy from the moment the code is
+ * loaded there until the process ends.  The call allocates and frees nothing.
+ *   - ZNNI_ERR_WORKSPACE if the layer needs more than ZNNI_STATIC_SCRATCH_BYTES (znni_conv3d_fft_workspace_v
+ *     tells what a shape needs; the second benchmark-sized layer, 8 -> 8 images of 64^3 with 5^3 kernels, fits).
+ *   - The array belongs to the GPU that is current when the call is made; `stream` must be a stream of that GPU.
+ *     Its address is looked up on the first call on each GPU (make that call outside a graph capture).
+ *   - All calls on one GPU share the array, which keeps whatever the last call left in it (no call depends on
+ *     that): two calls that overlap in time on one GPU, on any streams, race.  Calls on one stream do not overlap.
+ */
+#define ZNNI_STATIC_SCRATCH_BYTES (64u << 20)
+znni_status znni_conv3d_fft_static_v(int S, int f, int fo, const int n[3], const int k[3],
+                                     const float* in, const float* w, const float* bias, float* out,
+                                     unsigned flags, void* stream);
+
+/*
  * Same computation, with a HIP event recorded on `stream` between stages; synchronises `stream` before
  * returning and writes the elapsed milliseconds of each stage to stage_ms[ZNNI_NUM_STAGES] (HOST pointer).
  * Meant for measurement: creates and destroys its events on every call.  For small images the z and y

@@ -19,7 +19,7 @@ MAC_BATCH = 8
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_conv3d_choose_v", "znni_conv3d_workspace_v", "znni_conv3d_v", "znni_mpf", "znni_maxpool",
+           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_static_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_conv3d_choose_v", "znni_conv3d_workspace_v", "znni_conv3d_v", "znni_mpf", "znni_maxpool",
            "znni_copy_probe")
 
 _lib = None
@@ -56,6 +56,8 @@ def lib():
         L.znni_conv3d_fft_workspace_v.argtypes = [i, i, i, i3, i3, ctypes.POINTER(sz)]
         L.znni_conv3d_fft_v.restype = i
         L.znni_conv3d_fft_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
+        L.znni_conv3d_fft_static_v.restype = i
+        L.znni_conv3d_fft_static_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp]
         L.znni_conv3d_fft_profile_v.restype = i
         L.znni_conv3d_fft_profile_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp,
                                                 ctypes.POINTER(ctypes.c_float)]
@@ -164,6 +166,20 @@ def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, str
         _check(lib().znni_conv3d_fft(S, f, fo, n[0], k[0], *tail))
     else:
         _check(lib().znni_conv3d_fft_v(S, f, fo, _triple(n), _triple(k), *tail))
+    return out
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def znni_conv3d_fft_static(inp, w, bias=None, relu=False, out=None, stream=None, mac_reference=False):
+    """znni_conv3d_fft on the library's own fixed scratch array instead of a caller's workspace (`out` should be
+    passed by callers that must not allocate; without it torch allocates the result)."""
+    S, f, fo, n, k, out, _ = _marshal(inp, w, bias, out, inp.new_empty(0, dtype=torch.uint8))
+    st = stream if stream is not None else torch.cuda.current_stream(inp.device)
+    _check(lib().znni_conv3d_fft_static_v(S, f, fo, _triple(n), _triple(k), inp.data_ptr(), w.data_ptr(),
+                                          bias.data_ptr() if bias is not None else None, out.data_ptr(),
+                                          _flags(relu, mac_reference), st.cuda_stream))
     return out
 
 

@@ -3,7 +3,14 @@
 // kernel transforms, inverse-transform the output images.  All validation happens before the first HIP call.
 #include <stdint.h>
 
+#include <mutex>
+
 #include "znni_internal.h"
+
+// Scratch memory of znni_conv3d_fft_static_v, the entry point for callers that cannot allocate: one array per GPU,
+// placed by the loader when the library's code is loaded on that GPU and held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[ZNNI_STATIC_SCRATCH_BYTES];
 
 namespace znni {
 
@@ -347,6 +354,26 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
 }
 #undef ZNNI_DO
 
+// Device address of `scratch` on the current GPU, looked up once per GPU (each GPU holds its own copy of the
+// array at its own address).
+static znni_status static_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static void* ptr[kMaxDevices];          // zero-initialised
+    static std::mutex mu;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ZNNI_ERR_HIP;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ZNNI_ERR_HIP;
+        if ((uintptr_t)p & 255u) return ZNNI_ERR_ALIGN;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return ZNNI_OK;
+}
+
 __global__ void k_copy_probe(float4* __restrict__ dst, const float4* __restrict__ src, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -394,6 +421,21 @@ znni_status znni_conv3d_fft_v(int S, int f, int fo, const int n[3], const int k[
 {
     LayerPlan L;
     znni_status rc = validate(S, f, fo, n, k, in, w, out, flags, workspace, workspace_bytes, &L);
+    if (rc) return rc;
+    return run(L, in, w, bias, out, flags, (hipStream_t)stream, nullptr);
+}
+
+znni_status znni_conv3d_fft_static_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
+                                     const float* w, const float* bias, float* out, unsigned flags, void* stream)
+{
+    // host-only checks first, against a stand-in workspace address (only its alignment matters to them)
+    LayerPlan L;
+    znni_status rc = validate(S, f, fo, n, k, in, w, out, flags, (void*)(uintptr_t)256, ZNNI_STATIC_SCRATCH_BYTES, &L);
+    if (rc) return rc;                       // ZNNI_ERR_WORKSPACE: the layer needs more than the array holds
+    void* base = nullptr;
+    rc = static_scratch(&base);
+    if (rc) return rc;
+    rc = make_plan(S, f, fo, n, k, base, &L);
     if (rc) return rc;
     return run(L, in, w, bias, out, flags, (hipStream_t)stream, nullptr);
 }
