@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the pruned-FFT 3D convolutional layer on one MI355X.
 
-A step is one whole layer call (kernel prep, three forward passes, multiply-accumulate, three inverse passes)
-on inputs already resident in HBM with a pre-allocated workspace.  The timed steps go through the profiling
+A step is one whole layer call (kernel prep, forward passes, multiply-accumulate, inverse passes) on the seeded
+synthetic inputs of the parity tests, already resident in HBM, with a pre-allocated workspace.  The timed steps go through the profiling
 entry point, which records a HIP event on the launch stream between stages, so the per-stage durations behind
 the roofline figures come from the same timed region as the throughput.  One JSON line is printed.
 """
@@ -23,32 +23,36 @@ MFMA_FP32_PEAK_TFLOPS = 157.3    # dense fp32 matrix, published
 VALU_FP32_UNPACKED_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 
 
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by
-# what the same counters report for the library's plain copy kernel; see profiles/.  Keyed by (workload, stage).
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg5_320c_f48x48_k5", "mac"): 17.84e9,      # 11.51 GB fetched + 6.33 GB written
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_bytes.txt")
 
 
-def algorithmic_work(L, N):
-    """Bytes / flops the method itself has to move / do per stage of one layer call."""
-    S, f, fo, n, k = L.S, L.f, L.fo, L.n, L.k
-    no = n - k + 1
-    zc = N // 2 + 1
-    bins = zc * N * N
-    c = 8  # bytes per complex
-    nimg, nimgo = S * f, S * fo
-    return {
-        "fwd_z": ("bytes", nimg * (4 * n ** 3 + c * n * n * zc)),
-        "fwd_y": ("bytes", nimg * (c * n * n * zc + c * n * N * zc)),
-        "fwd_x": ("bytes", nimg * (c * n * N * zc + c * bins)),
-        "kernel_prep": ("bytes", 4 * fo * f * k ** 3 + c * zc * N * fo * f * k),
-        # complex multiply-add = 8 flops; the last kernel-transform stage is a k-term sum per bin
-        "mac": ("flops", (8 * S + 8 * (k - 1)) * f * fo * bins),
-        "inv_x": ("bytes", nimgo * (c * bins + c * zc * no * N)),
-        "inv_y": ("bytes", nimgo * (c * zc * no * N + c * no * no * zc)),
-        "inv_z": ("bytes", nimgo * (c * no * no * zc + 4 * no ** 3)),
-    }
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (read + written) of `kernel` on `workload`, from the table of calibrated rocprofv3
+    FETCH_SIZE / WRITE_SIZE counter runs kept under profiles/ (lines: workload kernel read_bytes written_bytes
+    source); None if the table has no such line."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            for line in fh:
+                t = line.split()
+                if len(t) >= 4 and not line.startswith("#") and t[0] == workload and t[1] == kernel:
+                    return float(t[2]) + float(t[3])
+    except OSError:
+        pass
+    return None
+
+
+def check_timed_output(layer, workloads, inp, w, bias, out_gpu):
+    """The output tensor the timed steps left, against the oracle on about 1e5 sampled positions (corner blocks
+    and face patches of every output image, mid-planes of one, random positions).  Part of the oracle leg."""
+    import numpy as np
+    import torch
+    from oracle import ref
+    pts = workloads.sample_points(layer, n_random=100_000, block=4, midplanes=layer.out_voxels < 5e8)
+    tp = torch.from_numpy(pts.astype(np.int64)).to(out_gpu.device)
+    got = out_gpu[tp[:, 0], tp[:, 1], tp[:, 2], tp[:, 3], tp[:, 4]].cpu().numpy().astype(np.float64)
+    exp = ref.conv3d_points(inp, w, bias, pts, relu=layer.relu)
+    tol = ref.tolerance(inp, w)[pts[:, 1]]
+    return {"sampled_voxels": int(len(pts)), "max_err_over_tol": float(np.max(np.abs(got - exp) / tol))}
 
 
 def cpu_baseline(layer, workloads):
@@ -154,11 +158,12 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--route", choices=("default", "single", "batch", "xdirect"), default="default",
+                    help="force a form of the multiply-accumulate stage (default: the library picks)")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle leg: its timing and the check of the timed output against it")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the short measurements of the pooling layer and of the budgeted (sub-layer) run")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run the library's plain 1 GiB copy kernel (calibrates rocprofv3 traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -168,26 +173,25 @@ def main():
     from paper_1606_05688_amd import workloads as W
 
     layer = W.CONFIGS[args.config - 1]
+    route = None if args.route == "default" else args.route
     dev = torch.device("cuda:0")
-    g = torch.Generator(device=dev)
-    g.manual_seed(0)
     S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
-    # synthetic inputs of the layer's distribution, drawn on the device (values do not affect timing)
-    inp = torch.rand((S, f, n, n, n), device=dev, generator=g) * 2 - 1
-    w = torch.randn((fo, f, k, k, k), device=dev, generator=g) * (f * k ** 3) ** -0.5
-    bias = torch.randn((fo,), device=dev, generator=g) * 0.1 ** 0.5 if layer.bias else None
+    # the seeded synthetic inputs the parity tests use (images U(-1,1), kernels N(0, 1/(f k^3)), bias N(0, 0.1))
+    inp_h, w_h, bias_h = W.make_inputs(layer)
+    inp, w = torch.from_numpy(inp_h).to(dev), torch.from_numpy(w_h).to(dev)
+    bias = torch.from_numpy(bias_h).to(dev) if bias_h is not None else None
     out = torch.empty((S, fo, n - k + 1, n - k + 1, n - k + 1), device=dev)
     ws = B.alloc_workspace(S, f, fo, n, k, dev)
     N = B.znni_fft_size(n)
 
     for _ in range(args.warmup):
-        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws, mac_reference=route)
     torch.cuda.synchronize()
 
     stage_sum = {s: 0.0 for s in B.STAGES}
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        _, ms = B.znni_conv3d_fft_profile(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+        _, ms = B.znni_conv3d_fft_profile(inp, w, bias, relu=layer.relu, out=out, workspace=ws, mac_reference=route)
         for s_, v in ms.items():
             stage_sum[s_] += v
     torch.cuda.synchronize()
@@ -198,52 +202,55 @@ def main():
     # the same steps through the plain asynchronous entry point, for reference
     t1 = time.perf_counter()
     for _ in range(args.steps):
-        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws)
+        B.znni_conv3d_fft(inp, w, bias, relu=layer.relu, out=out, workspace=ws, mac_reference=route)
     torch.cuda.synchronize()
     ms_plain = 1e3 * (time.perf_counter() - t1) / args.steps
 
-    if args.copy_probe:
-        src = torch.ones(1 << 28, device=dev)           # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            B.znni_copy_probe(dst, src)
-        torch.cuda.synchronize()
-        del src, dst
+    # what a plain copy kernel reaches on this machine: the achievable line next to the 8 TB/s peak (also the kernel
+    # the rocprofv3 traffic counters are calibrated against)
+    src = torch.ones(1 << 28, device=dev)               # 1 GiB
+    dst = torch.empty_like(src)
+    copy_ms = _time_ms(torch, lambda: B.znni_copy_probe(dst, src), 5)
+    copy_gbs = 2 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
+    del src, dst
 
-    work = algorithmic_work(layer, N)
+    # the work of the kernels that actually ran (fused kernels and skipped stages priced as such)
+    nbytes, nflops = B.znni_conv3d_fft_stage_work(S, f, fo, n, k, relu=layer.relu, mac_reference=route)
     stages = {}
-    for s_, (kind, amount) in work.items():
+    for s_ in B.STAGES:
+        if nbytes[s_] == 0 and nflops[s_] == 0:
+            continue                                    # the call has no such stage
         t = stage_ms[s_] * 1e-3
-        if kind == "bytes":
-            ach = amount / t / 1e9 if t > 0 else 0.0
-            stages[s_] = {"ms": stage_ms[s_], "GB": amount / 1e9, "GB/s": ach, "frac_hbm": ach / HBM_PEAK_GBS}
-        else:
-            ach = amount / t / 1e12 if t > 0 else 0.0
-            stages[s_] = {"ms": stage_ms[s_], "GFLOP": amount / 1e9, "TFLOP/s": ach,
-                          "frac_peak": ach / MFMA_FP32_PEAK_TFLOPS}
-    dom = max(B.STAGES, key=lambda s_: stage_ms[s_])
-    kind, amount = work[dom]
+        e = {"ms": stage_ms[s_], "GB": nbytes[s_] / 1e9, "GB/s": nbytes[s_] / t / 1e9,
+             "frac_hbm": nbytes[s_] / t / 1e9 / HBM_PEAK_GBS}
+        if nflops[s_]:
+            e.update({"GFLOP": nflops[s_] / 1e9, "TFLOP/s": nflops[s_] / t / 1e12,
+                      "frac_peak": nflops[s_] / t / 1e12 / MFMA_FP32_PEAK_TFLOPS})
+        stages[s_] = e
+    dom = max(stages, key=lambda s_: stage_ms[s_])
     t = stage_ms[dom] * 1e-3
-    if kind == "bytes":
-        roof = {"kernel": dom, "bound": "hbm", "achieved": amount / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roof = {"kernel": dom, "bound": "mfma", "achieved": amount / t / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
+    if nflops[dom]:
+        roof = {"kernel": dom, "bound": "mfma", "achieved": nflops[dom] / t / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
+    else:
+        roof = {"kernel": dom, "bound": "hbm", "achieved": nbytes[dom] / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((layer.name, dom))
+    roof["traffic"] = measured_traffic(layer.name + ("" if route is None else ":" + route), dom)
+    roof["traffic_source"] = os.path.relpath(TRAFFIC_FILE, ROOT)
     roof["avg_launch_ms"] = stage_ms[dom]
     if dom == "mac":
-        # each complex product is issued as three real matrix-core products (6 flops instead of the 8 counted
-        # above), so the matrix pipes are busy for 3/4 of the algorithmic rate
+        # `achieved` counts 8 flops per complex multiply-add; each is issued as three real matrix-core products
+        # (6 flops), so the matrix pipes are busy for 3/4 of that rate
+        roof["counting"] = "algorithmic: 8 flops per complex multiply-add; issued_*: the 6 the three-product form issues"
         roof["issued_TFLOP/s"] = 0.75 * roof["achieved"]
         roof["issued_frac"] = 0.75 * roof["frac"]
-        # the multiply-accumulate proper, without the kernel-spectrum generation that replaces a stored bank:
-        # 8 flops per (input of the batch, input image, output image, bin)
+        # the per-bin product alone, without the kernel-tap sum that replaces a stored kernel-spectrum bank
         mac_only = 8.0 * S * f * fo * (N // 2 + 1) * N * N
         roof["mac_only_TFLOP/s"] = mac_only / t / 1e12
         roof["mac_only_frac"] = mac_only / t / 1e12 / MFMA_FP32_PEAK_TFLOPS
-    fft_bytes = sum(work[s_][1] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
-    fft_ms = sum(stage_ms[s_] for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z"))
+    pass_names = [s_ for s_ in ("fwd_z", "fwd_y", "fwd_x", "inv_x", "inv_y", "inv_z") if s_ in stages]
+    fft_bytes = sum(nbytes[s_] for s_ in pass_names)
+    fft_ms = sum(stage_ms[s_] for s_ in pass_names)
 
     rec = {
         "metric": "output voxels/sec per conv layer at 1 GPU",
@@ -254,15 +261,27 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": layer.name, "S": S, "f": f, "f_out": fo, "n": n, "k": k,
-                   "fft_size": N, "out_voxels": layer.out_voxels, "relu": layer.relu, "bias": layer.bias},
+                   "fft_size": N, "out_voxels": layer.out_voxels, "relu": layer.relu, "bias": layer.bias,
+                   "route": args.route, "stages_run": list(stages)},
         "roofline": roof,
-        "fft_passes": {"GB": fft_bytes / 1e9, "ms": fft_ms, "GB/s": fft_bytes / (fft_ms * 1e-3) / 1e9,
+        "fft_passes": {"kernels": pass_names, "GB": fft_bytes / 1e9, "ms": fft_ms,
+                       "GB/s": fft_bytes / (fft_ms * 1e-3) / 1e9,
                        "frac_hbm": fft_bytes / (fft_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "copy_probe": {"GB/s": copy_gbs, "frac_hbm": copy_gbs / HBM_PEAK_GBS,
+                       "what": "plain 1 GiB device copy kernel, read + write: the achievable line for the passes"},
         "stages": stages,
     }
+    if not args.no_cpu_baseline:
+        # the oracle leg, part one: the tensor the timed steps wrote, checked before anything overwrites it
+        rec["parity_of_timed_output"] = check_timed_output(layer, W, inp_h, w_h, bias_h, out)
     if not args.no_extras:
         # not part of the timed steps above: the rows built next to the hot path, measured once each
+        whole = out.clone() if out.numel() * 4 < 8e9 else None
         rec["next_rows"] = {"sublayers": bench_sublayers(torch, B, layer, inp, w, bias, out, ms_plain)}
+        if whole is not None:
+            tolj = (1e-4 * float(inp.abs().max()) * w.abs().sum(dim=(1, 2, 3, 4)))[None, :, None, None, None]
+            rec["next_rows"]["sublayers"]["max_diff_vs_whole_layer_over_tol"] = float(((out - whole).abs() / tolj).max())
+            del whole
         del ws
         torch.cuda.empty_cache()
         rec["next_rows"]["mpf"] = bench_mpf(torch, B, dev)

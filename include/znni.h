@@ -51,11 +51,16 @@ enum {
                                     /* per-bin kernel instead of the matrix-core kernel (same result up to     */
                                     /* rounding, much slower)                                                   */
     ZNNI_MAC_SINGLE = 4u,           /* force the multiply-accumulate form built for S = 1 (work grows with k*S) */
-    ZNNI_MAC_BATCH = 8u             /* force the form built for batches (kernel spectrum generated once per    */
+    ZNNI_MAC_BATCH = 8u,            /* force the form built for batches (kernel spectrum generated once per    */
                                     /* bin, shared by the S inputs; ignored where that form does not exist:    */
                                     /* more than 12 kernel taps, or up to 8 inputs with an odd transform       */
-                                    /* length along x); without                                                 */
-                                    /* either flag the library picks                                            */
+                                    /* length along x)                                                          */
+    ZNNI_MAC_XDIRECT = 16u          /* force the route that does not transform the x axis at all: transforms    */
+                                    /* along z and y only, and the kernel's taps along x applied as a short     */
+                                    /* valid convolution inside the multiply-accumulate (same contraction       */
+                                    /* length as ZNNI_MAC_SINGLE, no x passes; ignored where it does not exist: */
+                                    /* more than 9 taps along x, or a y transform length without an in-register */
+                                    /* pass kernel); without any of these flags the library picks               */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */
@@ -101,7 +106,7 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
  *   w         [fo][f][k][k][k]         device, read-only
  *   bias      [fo] device, read-only, or NULL for zero bias
  *   out       [S][fo][n-k+1]^3         device, written (every element)
- *   flags     bitwise OR of ZNNI_RELU and at most one of ZNNI_MAC_REFERENCE / ZNNI_MAC_SINGLE / ZNNI_MAC_BATCH, or 0
+ *   flags     bitwise OR of ZNNI_RELU and at most one of the ZNNI_MAC_* flags, or 0
  *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
  *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
  *             not overlap in time.
@@ -139,6 +144,19 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
                                     const float* in, const float* w, const float* bias, float* out,
                                     unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
                                     float* stage_ms);
+
+/*
+ * Measurement aid (host only): the work the method itself has to do in each stage of a layer call with these
+ * flags, for the kernels that call would run.  hbm_bytes[s] = bytes stage s must read plus write once (its input
+ * and output tensors, unpadded); flops[s] = floating-point operations of the contraction in the
+ * multiply-accumulate stage, counting 8 per complex multiply-add: (8 S + 8 (kx - 1)) f f' per bin of the transformed
+ * image when the x axis is transformed (the per-bin product of Algorithm 3 plus the kx-term sum that stands in for a
+ * stored kernel spectrum), 8 kx S f f' per bin of the image transformed along y and z only when it is not.  Stages a
+ * call does not run (the y or z stage where one kernel does both, the x stages where the x axis is not transformed)
+ * get 0.  Both arrays have ZNNI_NUM_STAGES elements, indexed like stage_ms above.
+ */
+znni_status znni_conv3d_fft_stage_work_v(int S, int f, int fo, const int n[3], const int k[3], unsigned flags,
+                                         double hbm_bytes[ZNNI_NUM_STAGES], double flops[ZNNI_NUM_STAGES]);
 
 /*
  * General image and kernel sizes (Section IV: an image has size n = <nx,ny,nz>, a kernel k = <kx,ky,kz>, the

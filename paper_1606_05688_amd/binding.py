@@ -16,10 +16,11 @@ RELU = 1
 MAC_REFERENCE = 2
 MAC_SINGLE = 4
 MAC_BATCH = 8
+MAC_XDIRECT = 16
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
-           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_static_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_conv3d_choose_v", "znni_conv3d_workspace_v", "znni_conv3d_v", "znni_mpf", "znni_maxpool",
+           "znni_conv3d_fft_profile_v", "znni_conv3d_fft_static_v", "znni_conv3d_fft_stage_work_v", "znni_conv3d_fft_sublayers_v", "znni_conv3d_fft_budget_v", "znni_conv3d_direct_workspace_v", "znni_conv3d_direct_v", "znni_conv3d_choose_v", "znni_conv3d_workspace_v", "znni_conv3d_v", "znni_mpf", "znni_maxpool",
            "znni_copy_probe")
 
 _lib = None
@@ -58,6 +59,9 @@ def lib():
         L.znni_conv3d_fft_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp]
         L.znni_conv3d_fft_static_v.restype = i
         L.znni_conv3d_fft_static_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp]
+        L.znni_conv3d_fft_stage_work_v.restype = i
+        L.znni_conv3d_fft_stage_work_v.argtypes = [i, i, i, i3, i3, u, ctypes.POINTER(ctypes.c_double),
+                                                   ctypes.POINTER(ctypes.c_double)]
         L.znni_conv3d_fft_profile_v.restype = i
         L.znni_conv3d_fft_profile_v.argtypes = [i, i, i, i3, i3, vp, vp, vp, vp, u, vp, sz, vp,
                                                 ctypes.POINTER(ctypes.c_float)]
@@ -120,9 +124,10 @@ def alloc_workspace(S, f, fo, n, k, device="cuda"):
 
 
 def _flags(relu, mac_reference):
-    """mac_reference: False/True, or one of the strings 'single' / 'batch' to force a multiply-accumulate form."""
+    """mac_reference: False/True, or one of the strings 'single' / 'batch' / 'xdirect' to force a
+    multiply-accumulate form."""
     m = {False: 0, None: 0, True: MAC_REFERENCE, "reference": MAC_REFERENCE, "single": MAC_SINGLE,
-         "batch": MAC_BATCH}[mac_reference]
+         "batch": MAC_BATCH, "xdirect": MAC_XDIRECT}[mac_reference]
     return (RELU if relu else 0) | m
 
 
@@ -196,6 +201,16 @@ def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=N
     else:
         _check(lib().znni_conv3d_fft_profile_v(S, f, fo, _triple(n), _triple(k), *tail))
     return out, {name: float(ms[i]) for i, name in enumerate(STAGES)}
+
+
+def znni_conv3d_fft_stage_work(S, f, fo, n, k, relu=False, mac_reference=False):
+    """({stage: bytes the stage must move}, {stage: flops of its contraction}) for the kernels a call would run."""
+    nb = (ctypes.c_double * len(STAGES))()
+    fl = (ctypes.c_double * len(STAGES))()
+    _check(lib().znni_conv3d_fft_stage_work_v(int(S), int(f), int(fo), _triple(n), _triple(k),
+                                              _flags(relu, mac_reference), nb, fl))
+    return ({name: float(nb[q]) for q, name in enumerate(STAGES)},
+            {name: float(fl[q]) for q, name in enumerate(STAGES)})
 
 
 def znni_conv3d_fft_sublayers(S, f, fo, n, k, budget_bytes):

@@ -5,6 +5,7 @@
 
 #include <mutex>
 
+#include "mac_common.h"
 #include "znni_internal.h"
 
 // Scratch memory of znni_conv3d_fft_static_v, the entry point for callers that cannot allocate: one array per GPU,
@@ -61,8 +62,24 @@ static void make_fft_plan(int N, FftPlan* P)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Whether a layer runs without transforming its x axis (mac_xd.hip).  A flag that names a multiply-accumulate form
+// decides; otherwise that route is taken where each kernel-spectrum value would serve too few inputs to be worth
+// generating (the same rule that picks between the two forms of the fully transformed route), provided the y
+// transform has an in-register kernel (only those read the transposed layout).  Measured on 48 -> 48 images of
+// 320^3 with 5^3 kernels: 20.9 ms against 25.0 ms; 40 -> 40 images of 128^3, 3^3 kernels: 0.98 against 1.10 ms.
+static bool pick_xdirect(const LayerPlan& L, unsigned flags)
+{
+    if (!mac_xd_available(L) || !fast_pass_available(L.d.Ny)) return false;
+    if (flags & ZNNI_MAC_XDIRECT) return true;
+    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
+    // small images, where one kernel per side does the z and y transforms: the two routes were measured within
+    // a few per cent of each other (lengths 64 and 100), the fully transformed one ahead
+    if (fused_fwd_zy_available(L) && fused_inv_yz_available(L)) return false;
+    return !mac_batch_preferred(L);
+}
+
 // Shape part of a plan: validates, fills every size and the array sizes sz[]; assigns no pointers.
-static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[3], LayerPlan* L)
+static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[3], unsigned flags, LayerPlan* L)
 {
     if (!n || !k) return ZNNI_ERR_NULL;
     if (S < 1 || f < 1 || fo < 1) return ZNNI_ERR_SHAPE;
@@ -89,10 +106,16 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     // like 100: the inverse x pass, which stores 128-byte runs into them, is then 20 % faster); where rows are
     // 64-byte aligned anyway the extra bytes cost more than the alignment gains (measured at 40 and 72)
     d.ldn = (d.Ny % 8 == 0) ? d.Ny : ((d.Ny + 15) & ~15);
+    d.ldxo = (d.nox + 15) & ~15;
     L->nimg = S * f;
     L->nimgo = S * fo;
     L->fp = (f + 3) & ~3;
     plan_mac(L);        // also sets Mp
+    L->xdirect = pick_xdirect(*L, flags);
+    // X2 and Yd are ordered [image][oz][oy]; the order [oz][image][oy] was measured too: 2 % faster for the
+    // multiply-accumulate that reads X2 and writes Yd, 6 % slower for the y passes on the other side of them
+    d.x2i = d.zc * d.Ny; d.x2o = d.Ny;
+    d.ydi = d.zc * d.Ny; d.ydo = d.Ny;
     make_fft_plan(d.Nx, &L->fftx);
     make_fft_plan(d.Ny, &L->ffty);
     make_fft_plan(d.Nz, &L->fftz);
@@ -102,19 +125,25 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->sz[0] = zc * d.ky * d.kx * L->fp * L->Mp * c;                                    // A1
     // A + room for the operand requests the multiply-accumulate issues one group of steps past the end
     L->sz[1] = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
+    // Sized for either route (x axis transformed or not), so that the workspace a shape needs does not depend on
+    // the flags of the call.
     size_t b0 = nimg * d.nx * zc * d.ldy;                            // X1
     size_t t = zc * d.Ny * nimg * d.Nx; if (t > b0) b0 = t;          // Xt
     t = nimgo * zc * d.nox * d.ldn; if (t > b0) b0 = t;              // Y2
+    const size_t yd = nimgo * zc * d.Ny * d.ldxo;                    // Yd
+    if (yd > b0) b0 = yd;
     size_t b1 = nimg * zc * d.Ny * d.ldx;                            // X2
     t = nimgo * d.nox * zc * d.ldo; if (t > b1) b1 = t;              // Y1
     L->sz[2] = b0 * c;
     L->sz[3] = b1 * c;
-    L->sz[4] = zc * d.Ny * nimgo * d.Nx * c;                         // Yt
+    t = zc * d.Ny * nimgo * d.Nx;                                    // Yt
+    L->sz[4] = (t > yd ? t : yd) * c;
     return ZNNI_OK;
 }
 
 // Pointer part: carve the workspace at `base` into arrays of the given byte sizes.  own_yt = false: the output
-// spectra share buf1 (a whole-layer call never needs X2 or Y1 while Yt is alive).
+// spectra share buf1 (a whole-layer call never needs X2 or Y1 while Yt is alive), or buf0 where the x axis is not
+// transformed (X1 is dead by then and X2, in buf1, is being read).
 static void place_plan(LayerPlan* L, void* base, const size_t sz[5], bool own_yt)
 {
     const Dims& d = L->d;
@@ -127,16 +156,18 @@ static void place_plan(LayerPlan* L, void* base, const size_t sz[5], bool own_yt
     L->A1 = (float2*)(p + off); off += align_up(sz[0], 256);
     L->A = (float2*)(p + off); off += align_up(sz[1], 256);
     L->buf0 = (float2*)(p + off); off += align_up(sz[2], 256);
+    // (sz[2] already covers Yd, so nothing is added for the layers whose x axis is not transformed)
     const size_t b1 = own_yt ? sz[3] : (sz[3] > sz[4] ? sz[3] : sz[4]);
     L->buf1 = (float2*)(p + off); off += align_up(b1, 256);
     if (own_yt) { L->Yt = (float2*)(p + off); off += align_up(sz[4], 256); }
-    else L->Yt = L->buf1;
+    else L->Yt = L->xdirect ? L->buf0 : L->buf1;
     L->bytes = off;
 }
 
-znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* L)
+znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], unsigned flags, void* base,
+                      LayerPlan* L)
 {
-    znni_status rc = shape_plan(S, f, fo, n, k, L);
+    znni_status rc = shape_plan(S, f, fo, n, k, flags, L);
     if (rc) return rc;
     place_plan(L, base, L->sz, false);
     return ZNNI_OK;
@@ -169,7 +200,7 @@ static znni_status division_bytes(int S, int f, int fo, const int n[3], const in
         for (int b = 0; b < 2; ++b)
             for (int c = 0; c < 2; ++c) {
                 if (Ss[a] == 0 || fs[b] == 0 || fos[c] == 0) continue;
-                znni_status rc = shape_plan(Ss[a], fs[b], fos[c], n, k, &L);
+                znni_status rc = shape_plan(Ss[a], fs[b], fos[c], n, k, 0, &L);
                 if (rc) return rc;
                 for (int q = 0; q < 5; ++q)
                     if (L.sz[q] > D->sz[q]) D->sz[q] = L.sz[q];
@@ -244,8 +275,9 @@ static znni_status choose_division(int S, int f, int fo, const int n[3], const i
 // Known bits only, and at most one of the three bits that pick a multiply-accumulate form.
 static bool flags_ok(unsigned flags)
 {
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
-    const unsigned forms = flags & (unsigned)(ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH);
+    const unsigned all_forms = ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT;
+    if (flags & ~(unsigned)(ZNNI_RELU | all_forms)) return false;
+    const unsigned forms = flags & all_forms;
     return (forms & (forms - 1)) == 0;
 }
 
@@ -255,7 +287,7 @@ static znni_status validate(int S, int f, int fo, const int n[3], const int k[3]
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
     if (!flags_ok(flags)) return ZNNI_ERR_FLAGS;
-    znni_status rc = make_plan(S, f, fo, n, k, workspace, L);
+    znni_status rc = make_plan(S, f, fo, n, k, flags, workspace, L);
     if (rc) return rc;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u) return ZNNI_ERR_ALIGN;
     if ((uintptr_t)workspace & 255u) return ZNNI_ERR_ALIGN;
@@ -281,6 +313,23 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     ZNNI_DO(launch_twiddles(L, st));
     ZNNI_MARK(ZNNI_STAGE_KERNEL_PREP);
     ZNNI_DO(launch_kernel_prep(L, w, (size_t)L.f * L.d.kx * L.d.ky * L.d.kz, st));
+    if (L.xdirect) {
+        // x axis not transformed: the x stages do nothing and read about zero
+        ZNNI_MARK(ZNNI_STAGE_FWD_Z);
+        ZNNI_DO(launch_fwd_z(L, in, st));
+        ZNNI_MARK(ZNNI_STAGE_FWD_Y);
+        ZNNI_DO(launch_fwd_y(L, st));
+        ZNNI_MARK(ZNNI_STAGE_FWD_X);
+        ZNNI_MARK(ZNNI_STAGE_MAC);
+        ZNNI_DO(launch_mac_xd(L, 0, st));
+        ZNNI_MARK(ZNNI_STAGE_INV_X);
+        ZNNI_MARK(ZNNI_STAGE_INV_Y);
+        ZNNI_DO(launch_fast_inv_yt(L, st));
+        ZNNI_MARK(ZNNI_STAGE_INV_Z);
+        ZNNI_DO(launch_inv_z(L, bias, out, flags, st));
+        ZNNI_MARK(ZNNI_NUM_STAGES);
+        return ZNNI_OK;
+    }
     const bool fused_zy = fused_fwd_zy_available(L);       // then the z stage's time covers z and y
     ZNNI_MARK(ZNNI_STAGE_FWD_Z);
     if (fused_zy) ZNNI_DO(launch_fwd_zy(L, in, st));
@@ -322,13 +371,19 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 const int fc = f - i0 < D.fi ? f - i0 : D.fi;
                 // a block of images is one contiguous tensor only if it spans all images of a tuple or one tuple
                 if (Sc > 1 && (fc != f || foc != fo)) return ZNNI_ERR_SHAPE;
-                ZNNI_DO(shape_plan(Sc, fc, foc, n, k, &L));
+                ZNNI_DO(shape_plan(Sc, fc, foc, n, k, flags, &L));
                 for (int q = 0; q < 5; ++q)
                     if (L.sz[q] > D.sz[q]) return ZNNI_ERR_WORKSPACE;
                 place_plan(&L, workspace, D.sz, D.own_yt);
                 ZNNI_DO(launch_twiddles(L, st));      // also zeroes the padding behind this chunk's A
                 ZNNI_DO(launch_kernel_prep(L, w + ((size_t)j0 * f + i0) * kvol, (size_t)f * kvol, st));
                 const float* isub = in + ((size_t)s0 * f + i0) * nvox;
+                if (L.xdirect) {
+                    ZNNI_DO(launch_fwd_z(L, isub, st));
+                    ZNNI_DO(launch_fwd_y(L, st));
+                    ZNNI_DO(launch_mac_xd(L, i0 > 0, st));
+                    continue;
+                }
                 if (fused_fwd_zy_available(L)) {
                     ZNNI_DO(launch_fwd_zy(L, isub, st));
                     ZNNI_DO(launch_fast_fwd_xt(L, st));
@@ -339,9 +394,14 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 }
                 ZNNI_DO(launch_mac(L, flags, i0 > 0, st));
             }
-            ZNNI_DO(launch_inv_x(L, st));
             const float* bsub = bias ? bias + j0 : nullptr;
             float* osub = out + ((size_t)s0 * fo + j0) * ovox;
+            if (L.xdirect) {
+                ZNNI_DO(launch_fast_inv_yt(L, st));
+                ZNNI_DO(launch_inv_z(L, bsub, osub, flags, st));
+                continue;
+            }
+            ZNNI_DO(launch_inv_x(L, st));
             if (fused_inv_yz_available(L)) {
                 ZNNI_DO(launch_inv_yz(L, bsub, osub, flags, st));
             } else {
@@ -409,7 +469,7 @@ znni_status znni_conv3d_fft_workspace_v(int S, int f, int fo, const int n[3], co
 {
     if (!bytes) return ZNNI_ERR_NULL;
     LayerPlan L;
-    znni_status rc = make_plan(S, f, fo, n, k, nullptr, &L);
+    znni_status rc = make_plan(S, f, fo, n, k, 0, nullptr, &L);
     if (rc) return rc;
     *bytes = L.bytes;
     return ZNNI_OK;
@@ -425,6 +485,48 @@ znni_status znni_conv3d_fft_v(int S, int f, int fo, const int n[3], const int k[
     return run(L, in, w, bias, out, flags, (hipStream_t)stream, nullptr);
 }
 
+znni_status znni_conv3d_fft_stage_work_v(int S, int f, int fo, const int n[3], const int k[3], unsigned flags,
+                                         double hbm_bytes[ZNNI_NUM_STAGES], double flops[ZNNI_NUM_STAGES])
+{
+    if (!hbm_bytes || !flops) return ZNNI_ERR_NULL;
+    if (!flags_ok(flags)) return ZNNI_ERR_FLAGS;
+    LayerPlan L;
+    znni_status rc = make_plan(S, f, fo, n, k, flags, nullptr, &L);
+    if (rc) return rc;
+    const Dims& d = L.d;
+    const double c = sizeof(float2), ni = L.nimg, no = L.nimgo, zc = d.zc;
+    const double vox = (double)d.nx * d.ny * d.nz, ovox = (double)d.nox * d.noy * d.noz;
+    const double x1 = c * d.nx * d.ny * zc, x2 = c * d.nx * d.Ny * zc, xt = c * (double)d.Nx * d.Ny * zc;
+    const double y2 = c * zc * d.nox * d.Ny, y1 = c * (double)d.nox * d.noy * zc;
+    const double a = c * zc * d.Ny * (double)f * fo * d.kx;              // stored kernel transforms, unpadded
+    for (int q = 0; q < ZNNI_NUM_STAGES; ++q) hbm_bytes[q] = flops[q] = 0.0;
+    hbm_bytes[ZNNI_STAGE_KERNEL_PREP] = 4.0 * f * fo * d.kx * d.ky * d.kz + a;
+    const bool fused_zy = !L.xdirect && fused_fwd_zy_available(L), fused_yz = !L.xdirect && fused_inv_yz_available(L);
+    if (fused_zy) hbm_bytes[ZNNI_STAGE_FWD_Z] = ni * (4.0 * vox + x2);
+    else {
+        hbm_bytes[ZNNI_STAGE_FWD_Z] = ni * (4.0 * vox + x1);
+        hbm_bytes[ZNNI_STAGE_FWD_Y] = ni * (x1 + x2);
+    }
+    if (fused_yz) hbm_bytes[ZNNI_STAGE_INV_Y] = no * (y2 + 4.0 * ovox);
+    else {
+        hbm_bytes[ZNNI_STAGE_INV_Y] = no * (y2 + y1);
+        hbm_bytes[ZNNI_STAGE_INV_Z] = no * (y1 + 4.0 * ovox);
+    }
+    if (L.xdirect) {
+        // the spectra between the y passes and the multiply-accumulate keep the x axis as it is
+        const double bins = zc * d.Ny * d.nox;
+        hbm_bytes[ZNNI_STAGE_MAC] = ni * x2 + a + no * y2;
+        flops[ZNNI_STAGE_MAC] = 8.0 * d.kx * S * (double)f * fo * bins;
+    } else {
+        const double bins = zc * d.Ny * d.Nx;
+        hbm_bytes[ZNNI_STAGE_FWD_X] = ni * (x2 + xt);
+        hbm_bytes[ZNNI_STAGE_INV_X] = no * (xt + y2);
+        hbm_bytes[ZNNI_STAGE_MAC] = ni * xt + a + no * xt;
+        flops[ZNNI_STAGE_MAC] = (8.0 * S + 8.0 * (d.kx - 1)) * (double)f * fo * bins;
+    }
+    return ZNNI_OK;
+}
+
 znni_status znni_conv3d_fft_static_v(int S, int f, int fo, const int n[3], const int k[3], const float* in,
                                      const float* w, const float* bias, float* out, unsigned flags, void* stream)
 {
@@ -435,7 +537,7 @@ znni_status znni_conv3d_fft_static_v(int S, int f, int fo, const int n[3], const
     void* base = nullptr;
     rc = static_scratch(&base);
     if (rc) return rc;
-    rc = make_plan(S, f, fo, n, k, base, &L);
+    rc = make_plan(S, f, fo, n, k, flags, base, &L);
     if (rc) return rc;
     return run(L, in, w, bias, out, flags, (hipStream_t)stream, nullptr);
 }

@@ -332,7 +332,8 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_str
                 sizeof(float2) * KPREP_OZ * (size_t)std::min(d.kz, KPREP_TAPS), st>>>(
         w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp, wj_stride);
     ZNNI_LAUNCH_CHECK();
-    const float scale = (float)(1.0 / ((double)d.Nx * d.Ny * d.Nz));
+    // the unnormalised transforms' factor: one per transformed axis
+    const float scale = (float)(1.0 / ((L.xdirect ? 1.0 : (double)d.Nx) * d.Ny * d.Nz));
     k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256),
                 sizeof(float2) * KPREP_OY * (size_t)std::min(d.ky, KPREP_TAPS), st>>>(
         L.A1, L.A, L.twy, d.Ny, d.kx, d.ky, L.fp, L.Mp, per, scale);

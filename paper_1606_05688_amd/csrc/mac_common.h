@@ -127,6 +127,10 @@ bool mac_batch_available(const LayerPlan& L);      // up to 12 taps along x
 bool mac_batch_preferred(const LayerPlan& L);
 znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st);
 
+// mac_xd.hip: the form for layers whose x axis is not transformed (1 to 9 taps along x).
+bool mac_xd_available(const LayerPlan& L);
+znni_status launch_mac_xd(const LayerPlan& L, int accumulate, hipStream_t st);
+
 // mac_k.hip: kernels with the number of kernel taps known at compile time (2 to 9).
 bool mac_k_available(const LayerPlan& L);
 znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st);

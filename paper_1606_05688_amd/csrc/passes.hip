@@ -112,7 +112,7 @@ __global__ void k_fwd_y(const float2* __restrict__ X1, float2* __restrict__ X2, 
     }
     __syncthreads();
     const float2* r = fft_lines(L.a, L.b, L.tw, TL, L.ld, P);
-    float2* dst = X2 + ((size_t)img * zc + oz) * N * d.ldx + x0;
+    float2* dst = X2 + ((size_t)img * d.x2i + (size_t)oz * d.x2o) * d.ldx + x0;
     for (int e = threadIdx.x; e < N * TL; e += blockDim.x) {
         const int l = e & (TL - 1), oy = e / TL;
         if (l < nvalid) dst[(size_t)oy * d.ldx + l] = r[l * L.ld + oy];
@@ -129,7 +129,7 @@ __global__ void k_fwd_x(const float2* __restrict__ X2, float2* __restrict__ Xt, 
     const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
     const int nx = d.nx, Ny = d.Ny, zc = d.zc;
     const int nvalid = min(TL, Ny - oy0);
-    const float2* src = X2 + (((size_t)img * zc + oz) * Ny + oy0) * d.ldx;
+    const float2* src = X2 + ((size_t)img * d.x2i + (size_t)oz * d.x2o + oy0) * d.ldx;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {
         const int l = e / N, x = e - l * N;
         float2 v = make_float2(0.f, 0.f);

@@ -19,7 +19,10 @@ namespace znni {
 // P_FWD_XT: the forward x pass reading the layout the fused z+y kernel leaves, X2'[img][x][oz][oy]: the 16 lines
 // of a tile (neighbouring oy) are adjacent elements of every x row, so the pass loads 128-byte runs with the line
 // index fastest across lanes (a transposing load instead of the transposing store of the pass before it).
-enum PassKind { P_FWD_Z, P_FWD_Y, P_FWD_X, P_INV_X, P_INV_Y, P_INV_Z, P_FWD_XT };
+// P_INV_YT: the inverse y pass of layers whose x axis is not transformed, reading Yd[imgo][oz][oy][xo]: the 16 lines
+// of a tile (neighbouring xo) are adjacent elements of every oy row -- the same transposing load.
+enum PassKind { P_FWD_Z, P_FWD_Y, P_FWD_X, P_INV_X, P_INV_Y, P_INV_Z, P_FWD_XT, P_INV_YT };
+constexpr bool pass_loads_transposed(int kind) { return kind == P_FWD_XT || kind == P_INV_YT; }
 
 struct PassArgs {
     const void* src;
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         lpitch = 1; epitch = (size_t)zc * d.Ny; nvalid = min(16, zc * d.Ny - q0); lin = d.nx;
     } else if constexpr (KIND == P_FWD_X) {   // tile: 16 oy of one (img, oz); lines along x in X2
         const int oy0 = tile * 16, oz = mid;
-        src = (const float2*)a.src + (((size_t)img * zc + oz) * d.Ny + oy0) * d.ldx;
+        src = (const float2*)a.src + ((size_t)img * d.x2i + (size_t)oz * d.x2o + oy0) * d.ldx;
         lpitch = d.ldx; nvalid = min(16, d.Ny - oy0); lin = d.nx;
     } else if constexpr (KIND == P_INV_X) {
         // tile: 16 oy of one (oz, imgo); or, where rows of Y2 are not padded to whole cache lines anyway and do not
@@ -86,11 +89,16 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
         const int xo0 = tile * 16, oz = mid;
         src = (const float2*)a.src + (((size_t)img * zc + oz) * d.nox + xo0) * d.ldn;
         lpitch = d.ldn; nvalid = min(16, d.nox - xo0);
+    } else if constexpr (KIND == P_INV_YT) {  // the same tile in Yd: element oy of line l at oy*ldxo + l
+        const int xo0 = tile * 16, oz = mid;
+        src = (const float2*)a.src + ((size_t)img * d.ydi + (size_t)oz * d.ydo) * d.ldxo + xo0;
+        lpitch = 1; epitch = d.ldxo; nvalid = min(16, d.nox - xo0);
     }
 
     // ---- step A: loads first (they do not need the twiddle table), then the barrier, then the arithmetic
     // step A thread = (line la, sample offset ja); samples fastest across lanes, except for the transposing load
-    const int ja = KIND == P_FWD_XT ? t >> 4 : t % R2, la = KIND == P_FWD_XT ? t & 15 : t / R2;
+    constexpr bool LT = pass_loads_transposed(KIND);
+    const int ja = LT ? t >> 4 : t % R2, la = LT ? t & 15 : t / R2;
     const bool in_a = t < 16 * R2;
     float2 v[R1];
     // Every load is issued unconditionally from a clamped (always valid, so finite) address and multiplied by
@@ -120,8 +128,9 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
                 const float mk = e < lin ? ml : 0.f;
-                const float2 x = ldg<STREAM && KIND != P_FWD_XT>(ls + (size_t)min(e, lin - 1) * epitch);
-                v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y) ? -(x.y * mk) : x.y * mk);
+                const float2 x = ldg<STREAM && !LT>(ls + (size_t)min(e, lin - 1) * epitch);
+                v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y || KIND == P_INV_YT) ? -(x.y * mk)
+                                                                                                      : x.y * mk);
             }
         }
     }
@@ -176,7 +185,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     if constexpr (KIND == P_FWD_Y) {
         // X2[img][oz][oy][x0 + lb]
         if (q < R1 && lb < nvalid) {
-            float2* o = (float2*)a.dst + ((size_t)img * zc + mid) * N * d.ldx + tile * 16 + lb;
+            float2* o = (float2*)a.dst + ((size_t)img * d.x2i + (size_t)mid * d.x2o) * d.ldx + tile * 16 + lb;
 #pragma unroll
             for (int r = 0; r < R2; ++r) stg<STREAM>(o + (size_t)(q + R1 * r) * d.ldx, u[r]);
         }
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
                 float2* o = (float2*)a.dst + (((size_t)mid * d.Ny + oy0 + l) * a.nimg + img) * N;
                 for (int e = t % 64; e < N; e += 64) stg<STREAM>(o + e, buf[l * P + e]);
             }
-        } else if constexpr (KIND == P_INV_Y) {
+        } else if constexpr (KIND == P_INV_Y || KIND == P_INV_YT) {
             // Y1[imgo][xo0 + l][oz][yo]: the valid part of each line, contiguous
             const int xo0 = tile * 16;
             for (int l = t / 64; l < nvalid; l += NTH / 64) {
@@ -309,7 +318,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
             case 160: return launch_one<8, 20, KIND>(a, grid, st);
         }
     }
-    if constexpr (KIND == P_INV_Y) {
+    if constexpr (KIND == P_INV_Y || KIND == P_INV_YT) {
         if (N == 128) return launch_one<16, 8, KIND>(a, grid, st);
     }
     if constexpr (KIND == P_FWD_Z || KIND == P_INV_Z) {
@@ -410,6 +419,12 @@ znni_status launch_fast_inv_y(const LayerPlan& L, hipStream_t st)
     const Dims& d = L.d;
     return launch_kind<P_INV_Y>(d.Ny, base_args(L, L.buf0, L.buf1, L.twy, L.nimgo),
                                 dim3((d.nox + 15) / 16, d.zc, L.nimgo), st);
+}
+znni_status launch_fast_inv_yt(const LayerPlan& L, hipStream_t st)
+{
+    const Dims& d = L.d;
+    return launch_kind<P_INV_YT>(d.Ny, base_args(L, L.Yt, L.buf1, L.twy, L.nimgo),
+                                 dim3((d.nox + 15) / 16, d.zc, L.nimgo), st);
 }
 znni_status launch_fast_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {

@@ -19,6 +19,9 @@ struct Dims {
     int ldy, ldx, ldo;    // row strides of X1, X2 and Y1: ny, nx and noy rounded up to a multiple of 16 complex
     int ldn;              // row stride of Y2: Ny, rounded up likewise where Ny is not a multiple of 8
                           // (128 bytes)
+    int ldxo;             // row stride of Yd (layers whose x axis is not transformed): nox rounded up likewise
+    int x2i, x2o;         // row (img, oz, oy) of X2 is row number img*x2i + oz*x2o + oy
+    int ydi, ydo;         // row (imgo, oz, oy) of Yd is row number imgo*ydi + oz*ydo + oy
 };
 
 // Everything one call needs: sizes, the radix schedules, and where each buffer lives in the workspace.
@@ -27,6 +30,9 @@ struct Dims {
 struct LayerPlan {
     int S, f, fo;
     Dims d;
+    // The x axis is not transformed (mac_xd.hip): in -> X1 -> X2, multiply-accumulate with the kx taps as shifted
+    // reads of X2 -> Yd[imgo][oz][oy][xo] (in Yt), inverse y pass reading Yd transposed -> Y1 -> out.
+    bool xdirect;
     int nimg;     // S * f
     int nimgo;    // S * fo
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)
@@ -43,7 +49,8 @@ struct LayerPlan {
     float2* A;    // [zc][Ny][fp/4][kx][4][Mp]       after the z and y stages, scaled by 1/(Nx Ny Nz)
     float2* buf0;
     float2* buf1;
-    float2* Yt;   // accumulated output spectra: buf1 itself for a whole-layer call; a buffer of its own when the
+    float2* Yt;   // accumulated output spectra: buf1 itself for a whole-layer call (buf0 where the x axis is not
+                  // transformed: the multiply-accumulate then reads X2 from buf1); a buffer of its own when the
                   // layer runs as sub-layers, because it must then survive the forward passes of later input chunks
     size_t sz[5]; // bytes of A1, A, buf0, buf1 and of a separate Yt
     size_t bytes; // total workspace bytes
@@ -51,7 +58,9 @@ struct LayerPlan {
 
 // Host-only: validate the shape and fill every field; pointers are offsets from `base` (may be NULL when
 // only the size is wanted).
-znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], void* base, LayerPlan* out);
+// flags: the call's flags (only the bits that pick a multiply-accumulate form matter: they decide `xdirect`).
+znni_status make_plan(int S, int f, int fo, const int n[3], const int k[3], unsigned flags, void* base,
+                      LayerPlan* out);
 
 int lines_per_tile(int N);
 
@@ -67,6 +76,9 @@ void plan_mac(LayerPlan* L);
 znni_status launch_mac(const LayerPlan& L, unsigned flags, int accumulate, hipStream_t st);
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st);
+// Inverse y pass for layers whose x axis is not transformed: reads Yd[imgo][oz][oy][xo] from L.Yt with a
+// transposing load, writes Y1 to buf1.  Exists for the in-register transform lengths only.
+znni_status launch_fast_inv_yt(const LayerPlan& L, hipStream_t st);
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st);
 
 // Forward z and y transforms in one kernel when a (oz, oy) plane fits LDS (passes_fused.hip): in -> X2' in buf1,

@@ -91,9 +91,9 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
-    assert call(flags=16) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=32) == -5 and call(flags=0x80000001) == -5
     # at most one of the three bits that pick a multiply-accumulate form
-    assert call(flags=2 | 4) == -5 and call(flags=4 | 8) == -5 and call(flags=1 | 2 | 8) == -5
+    assert call(flags=2 | 4) == -5 and call(flags=4 | 8) == -5 and call(flags=1 | 2 | 8) == -5 and call(flags=8 | 16) == -5
     assert call(flags=1 | 4, wsb=1024) == -4 and call(flags=8, wsb=1024) == -4     # one of them: validation goes on
     assert call(inp=p + 4) == -7 and call(out=p + 8) == -7 and call(wsp=ws + 128) == -7
     assert call(wsb=1024) == -4
@@ -188,7 +188,7 @@ def test_sublayer_division_follows_the_stated_preference():
     p = 0x1000
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
-    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 16, 0x100000, full, None) == -5
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 32, 0x100000, full, None) == -5
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 4 | 8, 0x100000, full, None) == -5
 
 
@@ -228,3 +228,29 @@ def test_primitive_choice_follows_kernel_size_and_image_count():
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 20, None) == -5
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p + 1, 0, 0x100000, 1 << 20, None) == -7
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 0, 0x100000, 8, None) == -4
+
+
+def test_stage_work_follows_the_kernels_a_call_would_run():
+    S, f, fo, n, k = 1, 48, 48, 320, 5
+    zc, no = n // 2 + 1, n - k + 1
+    img = 8 * zc * n * n                                     # one transformed image, bytes
+    nb, fl = B.znni_conv3d_fft_stage_work(S, f, fo, n, k, mac_reference="single")
+    assert nb["fwd_z"] == f * (4 * n ** 3 + img) and nb["fwd_y"] == f * 2 * img and nb["fwd_x"] == f * 2 * img
+    assert nb["inv_x"] == fo * (img + 8 * zc * no * n) and nb["inv_z"] == fo * (8 * no * no * zc + 4 * no ** 3)
+    assert nb["kernel_prep"] == 4 * f * fo * k ** 3 + 8 * zc * n * f * fo * k
+    assert fl["mac"] == (8 * S + 8 * (k - 1)) * f * fo * zc * n * n and sum(fl.values()) == fl["mac"]
+    # the same layer without transforming the x axis: no x stages, multiply-accumulate on n' of n columns
+    nb, fl = B.znni_conv3d_fft_stage_work(S, f, fo, n, k, mac_reference="xdirect")
+    assert nb["fwd_x"] == 0 and nb["inv_x"] == 0 and nb["fwd_y"] == f * 2 * img
+    assert nb["inv_y"] == fo * (8 * zc * no * n + 8 * no * no * zc)
+    assert fl["mac"] == 8 * k * S * f * fo * zc * n * no
+    # small images: one kernel per side does the z and y transforms, and its stage carries the bytes of both
+    nb, _ = B.znni_conv3d_fft_stage_work(8, 32, 32, 64, 7)
+    assert nb["fwd_y"] == 0 and nb["inv_z"] == 0
+    assert nb["fwd_z"] == 8 * 32 * (4 * 64 ** 3 + 8 * 33 * 64 * 64)
+    assert nb["inv_y"] == 8 * 32 * (8 * 33 * 58 * 64 + 4 * 58 ** 3)
+    L = B.lib()
+    arr = (ctypes.c_double * 8)()
+    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 0, None, arr) == -1
+    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(9, 3, 3), 0, arr, arr) == -2
+    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 64, arr, arr) == -5

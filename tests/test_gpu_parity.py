@@ -33,16 +33,24 @@ def _run_gpu(inp, w, bias, relu, **kw):
     return out
 
 
-def _check_full(oracle, inp, w, bias, relu, label):
+# The library's own pick of the multiply-accumulate form, then each route forced: x axis transformed (kernel
+# spectrum folded into the contraction) and x axis not transformed.  For one input per batch the pick is one of the
+# two, so every layer shape below runs through both sets of kernels.
+ROUTES = (False, "single", "xdirect")
+
+
+def _check_full(oracle, inp, w, bias, relu, label, routes=ROUTES):
     _say(f"[parity/full] {label} inp={inp.shape} w={w.shape} relu={relu} bias={'yes' if bias is not None else 'no'}")
-    got = _run_gpu(inp, w, bias, relu).cpu().numpy().astype(np.float64)
     exp = oracle.conv3d(inp, w, bias, relu=relu)
-    assert got.shape == exp.shape
     tol = oracle.tolerance(inp, w)
-    err = np.abs(got - exp).max(axis=(0, 2, 3, 4))
-    _say(f"    max err/tol per output image: {np.max(err / tol):.3e} (worst abs {err.max():.3e})")
-    assert np.all(np.isfinite(got))
-    assert np.all(err <= tol), f"{label}: err {err} > tol {tol}"
+    for route in routes:
+        got = _run_gpu(inp, w, bias, relu, mac_reference=route).cpu().numpy().astype(np.float64)
+        assert got.shape == exp.shape
+        err = np.abs(got - exp).max(axis=(0, 2, 3, 4))
+        _say(f"    route {route or 'default'}: max err/tol per output image: {np.max(err / tol):.3e} "
+             f"(worst abs {err.max():.3e})")
+        assert np.all(np.isfinite(got))
+        assert np.all(err <= tol), f"{label} route {route}: err {err} > tol {tol}"
 
 
 def _rand(seed, S, f, fo, n, k):
@@ -92,7 +100,7 @@ def test_small_layers_full_compare(oracle, shape):
     S, f, fo, n, k = shape
     inp, w, b = _rand(100 + n + k, S, f, fo, n, k)
     _check_full(oracle, inp, w, b, True, f"small {shape}")
-    _check_full(oracle, inp, w, None, False, f"small {shape} linear")
+    _check_full(oracle, inp, w, None, False, f"small {shape} linear", routes=(False,))
 
 
 def _rand_v(seed, S, f, fo, n, k):
@@ -214,20 +222,21 @@ def test_benchmark_layers_every_voxel(oracle, idx):
     L = W.CONFIGS[idx]
     _say(f"[parity/full] {L.name}: drawing inputs")
     inp, w, b = W.make_inputs(L)
-    out = _run_gpu(inp, w, b, L.relu)
-    assert bool(torch.isfinite(out).all())
+    routes = (False, "single" if L.S == 1 else "batch", "xdirect")
+    outs = [_run_gpu(inp, w, b, L.relu, mac_reference=r) for r in routes]
+    assert all(bool(torch.isfinite(o).all()) for o in outs)
     tol = oracle.tolerance(inp, w)[None, :, None, None, None]
-    worst, checked = 0.0, 0
+    worst, checked = [0.0] * len(routes), 0
     for s in range(L.S):
         _say(f"    oracle: input {s + 1} of {L.S}")
         exp = oracle.conv3d(inp[s:s + 1], w, b, relu=L.relu)
-        got = out[s:s + 1].cpu().numpy()
-        ratio = np.abs(got - exp) / tol
-        worst = max(worst, float(ratio.max()))
-        checked += exp.size
-        assert np.all(ratio <= 1.0), f"{L.name}: input {s}: err/tol {ratio.max():.3e}"
         assert np.count_nonzero(exp) > 0.2 * exp.size
-    _say(f"    {checked} output voxels checked (all {L.out_voxels}); max err/tol {worst:.3e}")
+        checked += exp.size
+        for q, (route, out) in enumerate(zip(routes, outs)):
+            ratio = np.abs(out[s:s + 1].cpu().numpy() - exp) / tol
+            worst[q] = max(worst[q], float(ratio.max()))
+            assert np.all(ratio <= 1.0), f"{L.name}: route {route}: input {s}: err/tol {ratio.max():.3e}"
+    _say(f"    {checked} output voxels checked (all {L.out_voxels}) on the routes {routes}: max err/tol {worst}")
     assert checked == L.out_voxels
 
 
@@ -242,16 +251,18 @@ def test_largest_benchmark_layer_declared_sample(largest_layer_case):
     the three mid-planes of one complete output image, and 2^20 uniformly random positions."""
     C = largest_layer_case
     L = C.layer
-    _say(f"[parity/sampled] {L.name}: {len(C.pts)} sampled output voxels; running the layer")
-    out = _run_gpu(C.inp, C.w, C.bias, L.relu)
-    assert bool(torch.isfinite(out).all())
-    got = _gather(out, C.pts)
-    del out
-    torch.cuda.empty_cache()
-    ratio = np.abs(got - C.exp) / C.tol
-    _say(f"    {len(C.pts)} output voxels checked; max err/tol {ratio.max():.3e}; mean |out| {np.abs(C.exp).mean():.3e}")
     assert len(C.pts) >= (1 << 20)
-    assert np.all(ratio <= 1.0)
+    for route in ROUTES[1:]:
+        _say(f"[parity/sampled] {L.name}: {len(C.pts)} sampled output voxels; running the layer, route {route}")
+        out = _run_gpu(C.inp, C.w, C.bias, L.relu, mac_reference=route)
+        assert bool(torch.isfinite(out).all())
+        got = _gather(out, C.pts)
+        del out
+        torch.cuda.empty_cache()
+        ratio = np.abs(got - C.exp) / C.tol
+        _say(f"    {len(C.pts)} output voxels checked; max err/tol {ratio.max():.3e}; "
+             f"mean |out| {np.abs(C.exp).mean():.3e}")
+        assert np.all(ratio <= 1.0)
 
 
 def test_results_are_bitwise_reproducible_and_workspace_reusable():
@@ -356,6 +367,31 @@ def test_batch_mac_form_matches_oracle_and_single_form(oracle, shape):
     assert np.all(np.abs(batch - exp) <= tol)
     assert np.all(np.abs(single - exp) <= tol)
     assert np.all(np.abs(batch - single) <= 0.1 * tol)
+
+
+# (S, f, fo, <nx,ny,nz>, <kx,ky,kz>) for the route that leaves the x axis untransformed: every tap count it has a
+# kernel for (1 to 9 along x), row blocks of one to five tiles, 128-wide and 64-wide column blocks with ragged ends,
+# several inputs per batch (columns run over (input, xo)), x extents that are no transform length at all (the axis is
+# never padded), output rows shorter than a tile.
+XDIRECT = [(1, 3, 2, (9, 16, 16), (1, 3, 3)), (1, 5, 17, (37, 12, 20), (2, 3, 2)), (2, 6, 33, (150, 8, 10), (3, 2, 3)),
+           (1, 9, 49, (70, 10, 8), (4, 3, 2)), (3, 4, 65, (45, 8, 12), (5, 2, 2)), (1, 7, 80, (131, 8, 8), (6, 1, 3)),
+           (1, 13, 48, (203, 10, 8), (7, 3, 1)), (2, 2, 20, (67, 12, 14), (8, 2, 2)), (1, 4, 40, (300, 8, 8), (9, 2, 2)),
+           (1, 48, 48, (40, 16, 20), (5, 5, 5)), (4, 3, 3, (11, 20, 24), (11, 3, 3)), (1, 2, 2, (5, 14, 10), (3, 3, 3))]
+
+
+@pytest.mark.parametrize("shape", XDIRECT, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
+def test_untransformed_x_axis_route_matches_oracle_and_transformed_route(oracle, shape):
+    S, f, fo, n, k = shape
+    inp, w, b = _rand_v(900 + sum(n) + fo, S, f, fo, n, k)
+    _say(f"[mac/xdirect] {shape}")
+    xd = _run_gpu(inp, w, b, False, mac_reference="xdirect").cpu().numpy().astype(np.float64)
+    single = _run_gpu(inp, w, b, False, mac_reference="single").cpu().numpy().astype(np.float64)
+    exp = oracle.conv3d(inp, w, b, relu=False)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    _say(f"    max err/tol: xdirect {np.max(np.abs(xd - exp) / tol):.3e}, single {np.max(np.abs(single - exp) / tol):.3e}")
+    assert np.all(np.abs(xd - exp) <= tol)
+    assert np.all(np.abs(single - exp) <= tol)
+    assert np.all(np.abs(xd - single) <= 0.1 * tol)
 
 
 def test_relu_flag_and_null_bias(oracle):
