@@ -55,12 +55,18 @@ enum {
                                     /* bin, shared by the S inputs; ignored where that form does not exist:    */
                                     /* more than 12 kernel taps, or up to 8 inputs with an odd transform       */
                                     /* length along x)                                                          */
-    ZNNI_MAC_XDIRECT = 16u          /* force the route that does not transform the x axis at all: transforms    */
+    ZNNI_MAC_XDIRECT = 16u,         /* force the route that does not transform the x axis at all: transforms    */
                                     /* along z and y only, and the kernel's taps along x applied as a short     */
                                     /* valid convolution inside the multiply-accumulate (same contraction       */
                                     /* length as ZNNI_MAC_SINGLE, no x passes; ignored where it does not exist: */
                                     /* more than 9 taps along x, or a y transform length without an in-register */
-                                    /* pass kernel); without any of these flags the library picks               */
+                                    /* pass kernel)                                                             */
+    ZNNI_MAC_XBLOCK = 32u           /* force the route that transforms the x axis in overlapping blocks of      */
+                                    /* eight inside the multiply-accumulate (transforms along z and y as for    */
+                                    /* ZNNI_MAC_XDIRECT; 8 / (9 - kx) multiply-adds per output instead of kx;   */
+                                    /* ignored where it does not exist: other than 4 or 5 taps along x, fewer   */
+                                    /* than 16 input images, more than 48 output images per row block, or no    */
+                                    /* in-register y pass kernel); without any of these flags the library picks */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */

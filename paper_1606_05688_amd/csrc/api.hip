@@ -67,11 +67,18 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // generating (the same rule that picks between the two forms of the fully transformed route), provided the y
 // transform has an in-register kernel (only those read the transposed layout).  Measured on 48 -> 48 images of
 // 320^3 with 5^3 kernels: 20.9 ms against 25.0 ms; 40 -> 40 images of 128^3, 3^3 kernels: 0.98 against 1.10 ms.
+static bool pick_xblock(const LayerPlan& L, unsigned flags)
+{
+    if (!mac_xb_available(L) || !fast_pass_available(L.d.Ny)) return false;
+    return (flags & ZNNI_MAC_XBLOCK) != 0;
+}
+
 static bool pick_xdirect(const LayerPlan& L, unsigned flags)
 {
+    if (L.xblock) return true;
     if (!mac_xd_available(L) || !fast_pass_available(L.d.Ny)) return false;
     if (flags & ZNNI_MAC_XDIRECT) return true;
-    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
+    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XBLOCK)) return false;
     // small images, where one kernel per side does the z and y transforms: the two routes were measured within
     // a few per cent of each other (lengths 64 and 100), the fully transformed one ahead
     if (fused_fwd_zy_available(L) && fused_inv_yz_available(L)) return false;
@@ -111,6 +118,7 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->nimgo = S * fo;
     L->fp = (f + 3) & ~3;
     plan_mac(L);        // also sets Mp
+    L->xblock = pick_xblock(*L, flags);
     L->xdirect = pick_xdirect(*L, flags);
     // X2 and Yd are ordered [image][oz][oy]; the order [oz][image][oy] was measured too: 2 % faster for the
     // multiply-accumulate that reads X2 and writes Yd, 6 % slower for the y passes on the other side of them
@@ -125,6 +133,7 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->sz[0] = zc * d.ky * d.kx * L->fp * L->Mp * c;                                    // A1
     // A + room for the operand requests the multiply-accumulate issues one group of steps past the end
     L->sz[1] = zc * d.Ny * d.kx * L->fp * L->Mp * c + (size_t)(L->fp + 64) * L->Mp * c;
+    if (mac_xb_available(*L) && mac_xb_kernel_bytes(*L) > L->sz[1]) L->sz[1] = mac_xb_kernel_bytes(*L);
     // Sized for either route (x axis transformed or not), so that the workspace a shape needs does not depend on
     // the flags of the call.
     size_t b0 = nimg * d.nx * zc * d.ldy;                            // X1
@@ -275,7 +284,7 @@ static znni_status choose_division(int S, int f, int fo, const int n[3], const i
 // Known bits only, and at most one of the three bits that pick a multiply-accumulate form.
 static bool flags_ok(unsigned flags)
 {
-    const unsigned all_forms = ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT;
+    const unsigned all_forms = ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT | ZNNI_MAC_XBLOCK;
     if (flags & ~(unsigned)(ZNNI_RELU | all_forms)) return false;
     const unsigned forms = flags & all_forms;
     return (forms & (forms - 1)) == 0;
@@ -321,7 +330,7 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
         ZNNI_DO(launch_fwd_y(L, st));
         ZNNI_MARK(ZNNI_STAGE_FWD_X);
         ZNNI_MARK(ZNNI_STAGE_MAC);
-        ZNNI_DO(launch_mac_xd(L, 0, st));
+        ZNNI_DO(L.xblock ? launch_mac_xb(L, 0, st) : launch_mac_xd(L, 0, st));
         ZNNI_MARK(ZNNI_STAGE_INV_X);
         ZNNI_MARK(ZNNI_STAGE_INV_Y);
         ZNNI_DO(launch_fast_inv_yt(L, st));
@@ -381,7 +390,7 @@ static znni_status run_divided(const Division& D, int S, int f, int fo, const in
                 if (L.xdirect) {
                     ZNNI_DO(launch_fwd_z(L, isub, st));
                     ZNNI_DO(launch_fwd_y(L, st));
-                    ZNNI_DO(launch_mac_xd(L, i0 > 0, st));
+                    ZNNI_DO(L.xblock ? launch_mac_xb(L, i0 > 0, st) : launch_mac_xd(L, i0 > 0, st));
                     continue;
                 }
                 if (fused_fwd_zy_available(L)) {

@@ -332,6 +332,7 @@ znni_status launch_kernel_prep(const LayerPlan& L, const float* w, size_t wj_str
                 sizeof(float2) * KPREP_OZ * (size_t)std::min(d.kz, KPREP_TAPS), st>>>(
         w, L.A1, L.twz, d, L.f, L.fo, L.fp, L.Mp, wj_stride);
     ZNNI_LAUNCH_CHECK();
+    if (L.xblock) return launch_kprep_yb(L, st);
     // the unnormalised transforms' factor: one per transformed axis
     const float scale = (float)(1.0 / ((L.xdirect ? 1.0 : (double)d.Nx) * d.Ny * d.Nz));
     k_kprep_y<<<dim3((per + 255) / 256, (d.Ny + KPREP_OY - 1) / KPREP_OY, d.zc), dim3(256),

@@ -131,6 +131,14 @@ znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
 bool mac_xd_available(const LayerPlan& L);
 znni_status launch_mac_xd(const LayerPlan& L, int accumulate, hipStream_t st);
 
+// mac_xb.hip: the same route with the x axis transformed in overlapping blocks of eight (up to 5 taps along x):
+// its own second stage of the kernel transform (launch_kprep_yb, after the z stage of mac.hip) and the bytes the
+// result takes.
+bool mac_xb_available(const LayerPlan& L);
+size_t mac_xb_kernel_bytes(const LayerPlan& L);
+znni_status launch_kprep_yb(const LayerPlan& L, hipStream_t st);
+znni_status launch_mac_xb(const LayerPlan& L, int accumulate, hipStream_t st);
+
 // mac_k.hip: kernels with the number of kernel taps known at compile time (2 to 9).
 bool mac_k_available(const LayerPlan& L);
 znni_status launch_mac_k(const LayerPlan& L, int accumulate, hipStream_t st);

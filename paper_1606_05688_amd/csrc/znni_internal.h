@@ -33,6 +33,9 @@ struct LayerPlan {
     // The x axis is not transformed (mac_xd.hip): in -> X1 -> X2, multiply-accumulate with the kx taps as shifted
     // reads of X2 -> Yd[imgo][oz][oy][xo] (in Yt), inverse y pass reading Yd transposed -> Y1 -> out.
     bool xdirect;
+    // ... and the kx taps are applied through length-8 transforms of overlapping blocks of X2 rows (mac_xb.hip)
+    // instead of shifted reads; A then holds the length-8 transforms of the taps.  Implies xdirect.
+    bool xblock;
     int nimg;     // S * f
     int nimgo;    // S * fo
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)

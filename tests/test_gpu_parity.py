@@ -34,9 +34,9 @@ def _run_gpu(inp, w, bias, relu, **kw):
 
 
 # The library's own pick of the multiply-accumulate form, then each route forced: x axis transformed (kernel
-# spectrum folded into the contraction) and x axis not transformed.  For one input per batch the pick is one of the
-# two, so every layer shape below runs through both sets of kernels.
-ROUTES = (False, "single", "xdirect")
+# spectrum folded into the contraction), x axis not transformed, x axis transformed in overlapping blocks of eight
+# (up to 5 taps along x; the flag is ignored elsewhere).  Every layer shape below runs through all sets of kernels.
+ROUTES = (False, "single", "xdirect", "xblock")
 
 
 def _check_full(oracle, inp, w, bias, relu, label, routes=ROUTES):
@@ -222,7 +222,7 @@ def test_benchmark_layers_every_voxel(oracle, idx):
     L = W.CONFIGS[idx]
     _say(f"[parity/full] {L.name}: drawing inputs")
     inp, w, b = W.make_inputs(L)
-    routes = (False, "single" if L.S == 1 else "batch", "xdirect")
+    routes = (False, "single" if L.S == 1 else "batch", "xdirect", "xblock")
     outs = [_run_gpu(inp, w, b, L.relu, mac_reference=r) for r in routes]
     assert all(bool(torch.isfinite(o).all()) for o in outs)
     tol = oracle.tolerance(inp, w)[None, :, None, None, None]
@@ -376,7 +376,11 @@ def test_batch_mac_form_matches_oracle_and_single_form(oracle, shape):
 XDIRECT = [(1, 3, 2, (9, 16, 16), (1, 3, 3)), (1, 5, 17, (37, 12, 20), (2, 3, 2)), (2, 6, 33, (150, 8, 10), (3, 2, 3)),
            (1, 9, 49, (70, 10, 8), (4, 3, 2)), (3, 4, 65, (45, 8, 12), (5, 2, 2)), (1, 7, 80, (131, 8, 8), (6, 1, 3)),
            (1, 13, 48, (203, 10, 8), (7, 3, 1)), (2, 2, 20, (67, 12, 14), (8, 2, 2)), (1, 4, 40, (300, 8, 8), (9, 2, 2)),
-           (1, 48, 48, (40, 16, 20), (5, 5, 5)), (4, 3, 3, (11, 20, 24), (11, 3, 3)), (1, 2, 2, (5, 14, 10), (3, 3, 3))]
+           (1, 48, 48, (40, 16, 20), (5, 5, 5)), (4, 3, 3, (11, 20, 24), (11, 3, 3)), (1, 2, 2, (5, 14, 10), (3, 3, 3)),
+           # blocks of eight along x: ragged last block, more than 32 blocks (wide and narrow column blocks), a number
+           # of input images that is no multiple of 8 or 4, several inputs per batch, two row blocks, one block only
+           (1, 19, 40, (141, 8, 10), (5, 2, 2)), (2, 20, 48, (70, 10, 8), (4, 3, 2)), (1, 16, 7, (203, 8, 8), (4, 2, 2)),
+           (1, 33, 96, (77, 8, 12), (5, 2, 3)), (3, 24, 4, (8, 12, 10), (5, 3, 2)), (1, 17, 3, (300, 8, 8), (4, 2, 2))]
 
 
 @pytest.mark.parametrize("shape", XDIRECT, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
@@ -385,13 +389,17 @@ def test_untransformed_x_axis_route_matches_oracle_and_transformed_route(oracle,
     inp, w, b = _rand_v(900 + sum(n) + fo, S, f, fo, n, k)
     _say(f"[mac/xdirect] {shape}")
     xd = _run_gpu(inp, w, b, False, mac_reference="xdirect").cpu().numpy().astype(np.float64)
+    xb = _run_gpu(inp, w, b, False, mac_reference="xblock").cpu().numpy().astype(np.float64)
     single = _run_gpu(inp, w, b, False, mac_reference="single").cpu().numpy().astype(np.float64)
     exp = oracle.conv3d(inp, w, b, relu=False)
     tol = oracle.tolerance(inp, w)[None, :, None, None, None]
-    _say(f"    max err/tol: xdirect {np.max(np.abs(xd - exp) / tol):.3e}, single {np.max(np.abs(single - exp) / tol):.3e}")
+    _say(f"    max err/tol: xdirect {np.max(np.abs(xd - exp) / tol):.3e}, xblock {np.max(np.abs(xb - exp) / tol):.3e}, "
+         f"single {np.max(np.abs(single - exp) / tol):.3e}")
     assert np.all(np.abs(xd - exp) <= tol)
+    assert np.all(np.abs(xb - exp) <= tol)
     assert np.all(np.abs(single - exp) <= tol)
     assert np.all(np.abs(xd - single) <= 0.1 * tol)
+    assert np.all(np.abs(xb - single) <= 0.1 * tol)
 
 
 def test_relu_flag_and_null_bias(oracle):

@@ -110,7 +110,7 @@ def test_blocks_accumulate_with_either_multiply_accumulate_form(oracle):
     ws = torch.empty(budget, dtype=torch.uint8, device=d)
     exp = oracle.conv3d(inp, w, b, relu=True)
     tol = oracle.tolerance(inp, w)[None, :, None, None, None]
-    for form in ("single", "batch", "reference", "xdirect"):
+    for form in ("single", "batch", "reference", "xdirect", "xblock"):
         got = B.znni_conv3d_fft_budget(ti, tw, tb, relu=True, workspace=ws, mac_reference=form)
         torch.cuda.synchronize()
         assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - exp) <= tol), form
