@@ -158,7 +158,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
-    ap.add_argument("--route", choices=("default", "single", "batch", "xdirect"), default="default",
+    ap.add_argument("--route", choices=("default", "single", "batch", "xdirect", "xblock"), default="default",
                     help="force a form of the multiply-accumulate stage (default: the library picks)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle leg: its timing and the check of the timed output against it")

@@ -67,10 +67,25 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // generating (the same rule that picks between the two forms of the fully transformed route), provided the y
 // transform has an in-register kernel (only those read the transposed layout).  Measured on 48 -> 48 images of
 // 320^3 with 5^3 kernels: 20.9 ms against 25.0 ms; 40 -> 40 images of 128^3, 3^3 kernels: 0.98 against 1.10 ms.
+static bool pick_untransformed_x(const LayerPlan& L, unsigned flags)
+{
+    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
+    // small images, where one kernel per side does the z and y transforms: the two routes were measured within
+    // a few per cent of each other (lengths 64 and 100), the fully transformed one ahead
+    if (fused_fwd_zy_available(L) && fused_inv_yz_available(L)) return false;
+    return !mac_batch_preferred(L);
+}
+
+// ... and whether it applies the kernel's taps along x through length-8 transforms of overlapping blocks
+// (mac_xb.hip) rather than as shifted reads: wherever that form exists (4 or 5 taps).  Measured, whole layer:
+// 48 -> 48 images of 320^3, 5^3 kernels 18.6 against 20.9 ms; 48 -> 48 of 240^3, 4^3: 7.8 against 8.2 ms;
+// 2 x 32 -> 32 of 128^3, 5^3: 1.49 against 1.55 ms.
 static bool pick_xblock(const LayerPlan& L, unsigned flags)
 {
     if (!mac_xb_available(L) || !fast_pass_available(L.d.Ny)) return false;
-    return (flags & ZNNI_MAC_XBLOCK) != 0;
+    if (flags & ZNNI_MAC_XBLOCK) return true;
+    if (flags & ZNNI_MAC_XDIRECT) return false;
+    return pick_untransformed_x(L, flags);
 }
 
 static bool pick_xdirect(const LayerPlan& L, unsigned flags)
@@ -78,11 +93,8 @@ static bool pick_xdirect(const LayerPlan& L, unsigned flags)
     if (L.xblock) return true;
     if (!mac_xd_available(L) || !fast_pass_available(L.d.Ny)) return false;
     if (flags & ZNNI_MAC_XDIRECT) return true;
-    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XBLOCK)) return false;
-    // small images, where one kernel per side does the z and y transforms: the two routes were measured within
-    // a few per cent of each other (lengths 64 and 100), the fully transformed one ahead
-    if (fused_fwd_zy_available(L) && fused_inv_yz_available(L)) return false;
-    return !mac_batch_preferred(L);
+    if (flags & ZNNI_MAC_XBLOCK) return false;
+    return pick_untransformed_x(L, flags);
 }
 
 // Shape part of a plan: validates, fills every size and the array sizes sz[]; assigns no pointers.

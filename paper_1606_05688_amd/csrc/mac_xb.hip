@@ -152,9 +152,10 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
     const int fb = t % NB, fhk = min(t / NB, 7), fh = fhk >> 2, fkk = fhk & 3;
     const int gb = b0 + fb;                                 // block number along x
     const float2* xrow = g.X2 + (size_t)sI * f * g.ximg + (size_t)poz * g.xpen + (size_t)poy * g.ldx;
-    // inputs beyond the row count as zeros (they reach discarded outputs only): loaded from a clamped position
-    // and multiplied by zero
-    const int x0 = gb * V, nval = gb < g.nblk ? min(g.nx - x0, XB) : 0;
+    // Inputs beyond the image row (last block of a row whose outputs do not fill it, blocks of the padding behind
+    // the last one) are read from the row's last element: they reach discarded outputs only, and any finite
+    // value of the data's magnitude does there.
+    const int x0 = gb * V;
     // LDS: two buffers Ds[buf][p][kk][b][h]
     float2* const Ds = lds;
     constexpr int DS_BUF = 8 * 4 * NB * 2;
@@ -188,11 +189,6 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
         for (int e = 0; e < XB; ++e) xv[e] = xr[min(x0 + e, g.nx - 1)];
     };
     auto transform_x = [&](int buf) {
-#pragma unroll
-        for (int e = 0; e < XB; ++e) {
-            const float mk = e < nval ? 1.f : 0.f;
-            xv[e] = make_float2(xv[e].x * mk, xv[e].y * mk);
-        }
         fft8<false>(xv);
         float2* d = Ds + buf * DS_BUF + ds_w;
 #pragma unroll
@@ -262,13 +258,21 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
             float2* y = g.Yd + (size_t)(sI * g.fo + jrow) * g.yimg + (size_t)poz * g.ypen + (size_t)poy * g.ldxo +
                         blk * V;
             const int nv = min(V, g.nox - blk * V);
+            if (K == 5 && nv == 4 && !g.accumulate) {
+                // the common case: four outputs, 32 contiguous bytes at a 32-byte boundary (Yd's rows start on
+                // 128-byte boundaries)
+                float4* y4 = reinterpret_cast<float4*>(y);
+                y4[0] = make_float4(cv[4].x, cv[4].y, cv[5].x, cv[5].y);
+                y4[1] = make_float4(cv[6].x, cv[6].y, cv[7].x, cv[7].y);
+            } else {
 #pragma unroll
-            for (int m = 0; m < XB; ++m) {
-                const int v = m - (K - 1);
-                if (v >= 0 && v < nv) {
-                    float2 o = cv[m];
-                    if (g.accumulate) o = cadd(o, y[v]);
-                    y[v] = o;
+                for (int m = 0; m < XB; ++m) {
+                    const int v = m - (K - 1);
+                    if (v >= 0 && v < nv) {
+                        float2 o = cv[m];
+                        if (g.accumulate) o = cadd(o, y[v]);
+                        y[v] = o;
+                    }
                 }
             }
         }
