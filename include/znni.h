@@ -61,6 +61,14 @@ enum {
                                     /* length as ZNNI_MAC_SINGLE, no x passes; ignored where it does not exist: */
                                     /* more than 9 taps along x, or a y transform length without an in-register */
                                     /* pass kernel)                                                             */
+    ZNNI_KEEP_KERNELS = 64u,        /* skip the kernel transform: the workspace still holds the stored kernel   */
+                                    /* transforms of an earlier call with the same w, layer shape and           */
+                                    /* multiply-accumulate form, and nothing else has written to it since.      */
+                                    /* For inference, where one set of kernels meets every patch of a volume    */
+                                    /* (Section II), so that the pruned kernel transform of Section III-A is    */
+                                    /* paid once per network and not once per patch.  The caller vouches: the   */
+                                    /* library cannot tell stale transforms from fresh ones.  w is not read.    */
+                                    /* Rejected by znni_conv3d_fft_budget_v (its sub-layers share the space).   */
     ZNNI_MAC_XBLOCK = 32u           /* force the route that transforms the x axis in overlapping blocks of      */
                                     /* eight inside the multiply-accumulate (transforms along z and y as for    */
                                     /* ZNNI_MAC_XDIRECT; 8 / (9 - kx) multiply-adds per output instead of kx;   */
@@ -112,7 +120,7 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
  *   w         [fo][f][k][k][k]         device, read-only
  *   bias      [fo] device, read-only, or NULL for zero bias
  *   out       [S][fo][n-k+1]^3         device, written (every element)
- *   flags     bitwise OR of ZNNI_RELU and at most one of the ZNNI_MAC_* flags, or 0
+ *   flags     bitwise OR of ZNNI_RELU, ZNNI_KEEP_KERNELS and at most one of the ZNNI_MAC_* flags, or 0
  *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
  *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
  *             not overlap in time.
@@ -157,7 +165,8 @@ znni_status znni_conv3d_fft_profile(int S, int f, int fo, int n, int k,
  * and output tensors, unpadded); flops[s] = floating-point operations of the contraction in the
  * multiply-accumulate stage, counting 8 per complex multiply-add: (8 S + 8 (kx - 1)) f f' per bin of the transformed
  * image when the x axis is transformed (the per-bin product of Algorithm 3 plus the kx-term sum that stands in for a
- * stored kernel spectrum), 8 kx S f f' per bin of the image transformed along y and z only when it is not.  Stages a
+ * stored kernel spectrum), 8 kx S f f' per bin of the image transformed along y and z only when it is not, 64 S f f'
+ * per block of 9 - kx outputs where x is transformed in blocks of eight.  Stages a
  * call does not run (the y or z stage where one kernel does both, the x stages where the x axis is not transformed)
  * get 0.  Both arrays have ZNNI_NUM_STAGES elements, indexed like stage_ms above.
  */

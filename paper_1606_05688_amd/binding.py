@@ -18,6 +18,7 @@ MAC_SINGLE = 4
 MAC_BATCH = 8
 MAC_XDIRECT = 16
 MAC_XBLOCK = 32
+KEEP_KERNELS = 64
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
@@ -124,12 +125,12 @@ def alloc_workspace(S, f, fo, n, k, device="cuda"):
     return torch.empty(znni_conv3d_fft_workspace(S, f, fo, n, k), dtype=torch.uint8, device=device)
 
 
-def _flags(relu, mac_reference):
+def _flags(relu, mac_reference, keep_kernels=False):
     """mac_reference: False/True, or one of the strings 'single' / 'batch' / 'xdirect' / 'xblock' to force a
     multiply-accumulate form."""
     m = {False: 0, None: 0, True: MAC_REFERENCE, "reference": MAC_REFERENCE, "single": MAC_SINGLE,
          "batch": MAC_BATCH, "xdirect": MAC_XDIRECT, "xblock": MAC_XBLOCK}[mac_reference]
-    return (RELU if relu else 0) | m
+    return (RELU if relu else 0) | m | (KEEP_KERNELS if keep_kernels else 0)
 
 
 def _marshal(inp, w, bias, out, workspace):
@@ -159,15 +160,17 @@ def _cubic(n, k):
 
 
 def znni_conv3d_fft(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
-                    mac_reference=False):
+                    mac_reference=False, keep_kernels=False):
     """out[S,f',n-k+1 per axis] = act(bias + valid 3D convolution of inp[S,f,nx,ny,nz] with w[f',f,kx,ky,kz]).
 
     Cubic shapes go through znni_conv3d_fft, all others through znni_conv3d_fft_v.
-    Asynchronous on `stream` (a torch.cuda.Stream; default: torch's current stream)."""
+    Asynchronous on `stream` (a torch.cuda.Stream; default: torch's current stream).
+    keep_kernels: the workspace (which must then be passed) still holds this w's stored transforms."""
+    assert not keep_kernels or workspace is not None
     S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
     tail = (inp.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, out.data_ptr(),
-            _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(), st.cuda_stream)
+            _flags(relu, mac_reference, keep_kernels), workspace.data_ptr(), workspace.numel(), st.cuda_stream)
     if _cubic(n, k):
         _check(lib().znni_conv3d_fft(S, f, fo, n[0], k[0], *tail))
     else:
@@ -190,13 +193,13 @@ def znni_conv3d_fft_static(inp, w, bias=None, relu=False, out=None, stream=None,
 
 
 def znni_conv3d_fft_profile(inp, w, bias=None, relu=False, out=None, workspace=None, stream=None,
-                            mac_reference=False):
+                            mac_reference=False, keep_kernels=False):
     """Same call with per-stage HIP-event timing; returns (out, {stage: milliseconds}).  Synchronises."""
     S, f, fo, n, k, out, workspace = _marshal(inp, w, bias, out, workspace)
     st = stream if stream is not None else torch.cuda.current_stream(inp.device)
     ms = (ctypes.c_float * len(STAGES))()
     tail = (inp.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None, out.data_ptr(),
-            _flags(relu, mac_reference), workspace.data_ptr(), workspace.numel(), st.cuda_stream, ms)
+            _flags(relu, mac_reference, keep_kernels), workspace.data_ptr(), workspace.numel(), st.cuda_stream, ms)
     if _cubic(n, k):
         _check(lib().znni_conv3d_fft_profile(S, f, fo, n[0], k[0], *tail))
     else:

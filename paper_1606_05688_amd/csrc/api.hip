@@ -297,7 +297,7 @@ static znni_status choose_division(int S, int f, int fo, const int n[3], const i
 static bool flags_ok(unsigned flags)
 {
     const unsigned all_forms = ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT | ZNNI_MAC_XBLOCK;
-    if (flags & ~(unsigned)(ZNNI_RELU | all_forms)) return false;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_KEEP_KERNELS | all_forms)) return false;
     const unsigned forms = flags & all_forms;
     return (forms & (forms - 1)) == 0;
 }
@@ -333,7 +333,8 @@ static znni_status run(const LayerPlan& L, const float* in, const float* w, cons
     } while (0)
     ZNNI_DO(launch_twiddles(L, st));
     ZNNI_MARK(ZNNI_STAGE_KERNEL_PREP);
-    ZNNI_DO(launch_kernel_prep(L, w, (size_t)L.f * L.d.kx * L.d.ky * L.d.kz, st));
+    // the stored kernel transforms of an earlier call on this workspace may be kept (same w, shape and form)
+    if (!(flags & ZNNI_KEEP_KERNELS)) ZNNI_DO(launch_kernel_prep(L, w, (size_t)L.f * L.d.kx * L.d.ky * L.d.kz, st));
     if (L.xdirect) {
         // x axis not transformed: the x stages do nothing and read about zero
         ZNNI_MARK(ZNNI_STAGE_FWD_Z);
@@ -519,9 +520,10 @@ znni_status znni_conv3d_fft_stage_work_v(int S, int f, int fo, const int n[3], c
     const double vox = (double)d.nx * d.ny * d.nz, ovox = (double)d.nox * d.noy * d.noz;
     const double x1 = c * d.nx * d.ny * zc, x2 = c * d.nx * d.Ny * zc, xt = c * (double)d.Nx * d.Ny * zc;
     const double y2 = c * zc * d.nox * d.Ny, y1 = c * (double)d.nox * d.noy * zc;
-    const double a = c * zc * d.Ny * (double)f * fo * d.kx;              // stored kernel transforms, unpadded
+    // stored kernel transforms, unpadded: kx values per kernel column along x, or 8 where x goes in blocks of eight
+    const double a = c * zc * d.Ny * (double)f * fo * (L.xblock ? 8 : d.kx);
     for (int q = 0; q < ZNNI_NUM_STAGES; ++q) hbm_bytes[q] = flops[q] = 0.0;
-    hbm_bytes[ZNNI_STAGE_KERNEL_PREP] = 4.0 * f * fo * d.kx * d.ky * d.kz + a;
+    if (!(flags & ZNNI_KEEP_KERNELS)) hbm_bytes[ZNNI_STAGE_KERNEL_PREP] = 4.0 * f * fo * d.kx * d.ky * d.kz + a;
     const bool fused_zy = !L.xdirect && fused_fwd_zy_available(L), fused_yz = !L.xdirect && fused_inv_yz_available(L);
     if (fused_zy) hbm_bytes[ZNNI_STAGE_FWD_Z] = ni * (4.0 * vox + x2);
     else {
@@ -538,6 +540,11 @@ znni_status znni_conv3d_fft_stage_work_v(int S, int f, int fo, const int n[3], c
         const double bins = zc * d.Ny * d.nox;
         hbm_bytes[ZNNI_STAGE_MAC] = ni * x2 + a + no * y2;
         flops[ZNNI_STAGE_MAC] = 8.0 * d.kx * S * (double)f * fo * bins;
+        if (L.xblock) {
+            // one length-8 product per block of V = 9 - kx outputs
+            const int V = 9 - d.kx;
+            flops[ZNNI_STAGE_MAC] = 8.0 * 8 * S * (double)f * fo * zc * d.Ny * ((d.nox + V - 1) / V);
+        }
     } else {
         const double bins = zc * d.Ny * d.Nx;
         hbm_bytes[ZNNI_STAGE_FWD_X] = ni * (x2 + xt);
@@ -632,7 +639,8 @@ znni_status znni_conv3d_fft_budget_v(int S, int f, int fo, const int n[3], const
                                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!in || !w || !out || !workspace) return ZNNI_ERR_NULL;
-    if (!flags_ok(flags)) return ZNNI_ERR_FLAGS;
+    // sub-layers take turns in the workspace, so there are no stored kernel transforms to keep between calls
+    if (!flags_ok(flags) || (flags & ZNNI_KEEP_KERNELS)) return ZNNI_ERR_FLAGS;
     Division D;
     znni_status rc = choose_division(S, f, fo, n, k, workspace_bytes, &D);
     if (rc) return rc;

@@ -270,9 +270,10 @@ znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
     const Dims& d = L.d;
     // the multiply-accumulate reads a little past A's last pencil (values multiplied by zero at most): that
     // padding is zeroed here
-    const size_t pad = (size_t)(L.fp + 64) * L.Mp;
+    // (the block-transform route keeps another array in A and reads nothing behind it)
+    const size_t pad = L.xblock ? 0 : (size_t)(L.fp + 64) * L.Mp;
     const size_t per = (size_t)d.kx * L.fp * L.Mp;
-    size_t most = pad;
+    size_t most = pad > 0 ? pad : 1;
     for (int N : {d.Nx, d.Ny, d.Nz})
         if ((size_t)N > most) most = N;
     k_twiddles<<<dim3((unsigned)((most + 255) / 256), 4), dim3(256), 0, st>>>(

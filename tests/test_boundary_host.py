@@ -94,7 +94,8 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
-    assert call(flags=64) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=128) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=64 | 1, wsb=1024) == -4                 # keeping stored kernel transforms is a known flag
     # at most one of the three bits that pick a multiply-accumulate form
     assert call(flags=2 | 4) == -5 and call(flags=4 | 8) == -5 and call(flags=1 | 2 | 8) == -5 and call(flags=8 | 16) == -5 and call(flags=16 | 32) == -5
     assert call(flags=1 | 4, wsb=1024) == -4 and call(flags=8, wsb=1024) == -4     # one of them: validation goes on
@@ -191,7 +192,7 @@ def test_sublayer_division_follows_the_stated_preference():
     p = 0x1000
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 0, 0x100000, 1024, None) == -4
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), None, p, None, p, 0, 0x100000, full, None) == -1
-    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 64, 0x100000, full, None) == -5
+    assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 64, 0x100000, full, None) == -5            # no kernels kept across sub-layers
     assert L.znni_conv3d_fft_budget_v(S, f, fo, _i3(*n), _i3(*k), p, p, None, p, 4 | 8, 0x100000, full, None) == -5
 
 
@@ -247,6 +248,13 @@ def test_stage_work_follows_the_kernels_a_call_would_run():
     assert nb["fwd_x"] == 0 and nb["inv_x"] == 0 and nb["fwd_y"] == f * 2 * img
     assert nb["inv_y"] == fo * (8 * zc * no * n + 8 * no * no * zc)
     assert fl["mac"] == 8 * k * S * f * fo * zc * n * no
+    # ... or with the x axis transformed in blocks of eight, four outputs each: 8 stored values per kernel column and
+    # 8 multiply-adds per block, image and kernel; kept kernel transforms cost nothing
+    nb, fl = B.znni_conv3d_fft_stage_work(S, f, fo, n, k, mac_reference="xblock")
+    assert nb["fwd_x"] == 0 and nb["kernel_prep"] == 4 * f * fo * k ** 3 + 8 * zc * n * f * fo * 8
+    assert fl["mac"] == 8 * 8 * S * f * fo * zc * n * (no // 4)
+    assert nb["mac"] == f * img + 8 * zc * n * f * fo * 8 + fo * 8 * zc * no * n
+    assert B.lib().znni_conv3d_fft_stage_work_v is not None
     # small images: one kernel per side does the z and y transforms, and its stage carries the bytes of both
     nb, _ = B.znni_conv3d_fft_stage_work(8, 32, 32, 64, 7)
     assert nb["fwd_y"] == 0 and nb["inv_z"] == 0
@@ -256,4 +264,4 @@ def test_stage_work_follows_the_kernels_a_call_would_run():
     arr = (ctypes.c_double * 8)()
     assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 0, None, arr) == -1
     assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(9, 3, 3), 0, arr, arr) == -2
-    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 64, arr, arr) == -5
+    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 128, arr, arr) == -5

@@ -402,6 +402,29 @@ def test_untransformed_x_axis_route_matches_oracle_and_transformed_route(oracle,
     assert np.all(np.abs(xb - single) <= 0.1 * tol)
 
 
+@pytest.mark.parametrize("route", [False, "single", "batch", "xdirect", "xblock"], ids=lambda r: str(r or "default"))
+def test_stored_kernel_transforms_can_be_kept_between_calls(oracle, route):
+    """Inference applies one kernel bank to many inputs: a call that keeps the workspace's stored kernel transforms
+    must equal a call that recomputes them, bit for bit, on new inputs; and it really does not read w."""
+    S, f, fo, n, k = (4 if route == "batch" else 1), 16, 20, (36, 20, 24), (5, 3, 4)
+    inp, w, b = _rand_v(321, S, f, fo, n, k)
+    d = torch.device("cuda:0")
+    ti, tw, tb = (torch.from_numpy(t).to(d) for t in (inp, w, b))
+    ws = B.alloc_workspace(S, f, fo, n, k, d)
+    first = B.znni_conv3d_fft(ti, tw, tb, relu=True, workspace=ws, mac_reference=route)
+    exp = oracle.conv3d(inp, w, b, relu=True)
+    tol = oracle.tolerance(inp, w)[None, :, None, None, None]
+    assert np.all(np.abs(first.cpu().numpy() - exp) <= tol)
+    inp2 = np.random.default_rng(322).uniform(-1, 1, inp.shape).astype(np.float32)
+    ti2 = torch.from_numpy(inp2).to(d)
+    fresh = B.znni_conv3d_fft(ti2, tw, tb, relu=True, mac_reference=route)
+    junk = torch.full_like(tw, float("nan"))                    # would poison everything if it were read
+    kept = B.znni_conv3d_fft(ti2, junk, tb, relu=True, workspace=ws, mac_reference=route, keep_kernels=True)
+    torch.cuda.synchronize()
+    assert torch.equal(kept, fresh)
+    assert np.all(np.abs(kept.cpu().numpy() - oracle.conv3d(inp2, w, b, relu=True)) <= tol)
+
+
 def test_relu_flag_and_null_bias(oracle):
     S, f, fo, n, k = 1, 2, 2, 16, 3
     inp, w, b = _rand(11, S, f, fo, n, k)
