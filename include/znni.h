@@ -93,8 +93,8 @@ enum {
 /* Library version, major*10000 + minor*100 + patch. */
 int znni_version(void);
 
-/* Static string for a status code (never NULL). */
-const char* znni_status_string(znni_status st);
+/* Static string for a status code (never NULL; any integer may be passed, unknown ones give "unknown status"). */
+const char* znni_status_string(int st);
 
 /*
  * Transform size n~ used for an image edge n.  Supported sizes are the products 2^a 3^b 5^c 7^d (the family

@@ -39,5 +39,31 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+LIB_HOST_SANITIZED = os.path.join(OBJDIR, "libznni_hostsan.so")
+
+
+def build_host_sanitized() -> str:
+    """The library with its HOST code (argument validation, workspace and sub-layer planning, cost model, launch
+    set-up) under AddressSanitizer and UndefinedBehaviorSanitizer; device code as usual.  For host-only checks
+    (tests/test_host_sanitizers.py): no GPU sanitizer is involved."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+    def one(src):
+        obj = os.path.join(OBJDIR, os.path.basename(src) + ".san.o")
+        extra = EXTRA_FLAGS.get(os.path.basename(src), [])
+        subprocess.run([HIPCC, *FLAGS, *extra, *san, "-c", src, "-o", obj], check=True)
+        return obj
+
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        objs = list(ex.map(one, srcs))
+    # (link: host sanitizer runtimes only, never the GPU one)
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize", "-fsanitize=address",
+                    "-fsanitize=undefined", "-o", LIB_HOST_SANITIZED, *objs], check=True)
+    return LIB_HOST_SANITIZED
+
+
 if __name__ == "__main__":
     build(verbose=True)

@@ -170,7 +170,8 @@ static void place_plan(LayerPlan* L, void* base, const size_t sz[5], bool own_yt
     const Dims& d = L->d;
     const size_t c = sizeof(float2);
     size_t off = 0;
-    char* p = (char*)base;
+    // addresses as integers: a size query carves from a null base
+    const uintptr_t p = (uintptr_t)base;
     L->twx = (float2*)(p + off); off += align_up((size_t)d.Nx * c, 256);
     L->twy = (float2*)(p + off); off += align_up((size_t)d.Ny * c, 256);
     L->twz = (float2*)(p + off); off += align_up((size_t)d.Nz * c, 256);
@@ -470,7 +471,7 @@ extern "C" {
 
 int znni_version(void) { return 200; }
 
-const char* znni_status_string(znni_status st)
+const char* znni_status_string(int st)
 {
     switch (st) {
         case ZNNI_OK: return "ok";

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
             for (int m = 0; m < R1; ++m) {
                 const int e = ja + R2 * m;
                 const float mk = e < lin ? ml : 0.f;
-                const float2 x = ldg<STREAM && !LT>(ls + (size_t)min(e, lin - 1) * epitch);
+                const float2 x = ldg<STREAM && (!LT || KIND == P_INV_YT)>(ls + (size_t)min(e, lin - 1) * epitch);
                 v[m] = make_float2(x.x * mk, (KIND == P_INV_X || KIND == P_INV_Y || KIND == P_INV_YT) ? -(x.y * mk)
                                                                                                       : x.y * mk);
             }

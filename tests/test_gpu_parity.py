@@ -425,6 +425,29 @@ def test_stored_kernel_transforms_can_be_kept_between_calls(oracle, route):
     assert np.all(np.abs(kept.cpu().numpy() - oracle.conv3d(inp2, w, b, relu=True)) <= tol)
 
 
+def test_calls_on_two_streams_with_two_workspaces_do_not_disturb_each_other():
+    """The library keeps no device state of its own: calls on different streams with different workspaces may overlap
+    in time.  Two layers of different shapes are enqueued alternately on two streams, several times, without any
+    synchronisation in between; every result must equal the one computed alone, bit for bit."""
+    d = torch.device("cuda:0")
+    shapes = [(1, 16, 16, (72, 64, 64), (5, 5, 5)), (2, 12, 20, (40, 36, 48), (3, 3, 3))]
+    layers = []
+    for q, (S, f, fo, n, k) in enumerate(shapes):
+        inp, w, b = (torch.from_numpy(t).to(d) for t in _rand_v(700 + q, S, f, fo, n, k))
+        alone = B.znni_conv3d_fft(inp, w, b, relu=True)
+        layers.append(dict(inp=inp, w=w, b=b, alone=alone, ws=B.alloc_workspace(S, f, fo, n, k, d),
+                           outs=[torch.empty_like(alone) for _ in range(4)], st=torch.cuda.Stream(device=d)))
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for L in layers:
+            with torch.cuda.stream(L["st"]):
+                B.znni_conv3d_fft(L["inp"], L["w"], L["b"], relu=True, out=L["outs"][rep], workspace=L["ws"], stream=L["st"])
+    torch.cuda.synchronize()
+    for L in layers:
+        for o in L["outs"]:
+            assert torch.equal(o, L["alone"])
+
+
 def test_relu_flag_and_null_bias(oracle):
     S, f, fo, n, k = 1, 2, 2, 16, 3
     inp, w, b = _rand(11, S, f, fo, n, k)
