@@ -10,8 +10,24 @@
  * Section IV-B-2 (Algorithm 3): forward transforms of the S*f images, a multiply-accumulate over the input
  * images in every frequency bin, inverse transforms of the S*f' accumulated spectra.  Kernel transforms are
  * pruned as in Section III-A (k^2, then k*n~, then n~^2 one-dimensional transforms) and their last stage is
- * evaluated inside the multiply-accumulate kernel, so no full-size kernel spectrum is ever stored.  Bias and
- * transfer function are applied where the inverse transform finishes an output image (Section IV-A-3).
+ * evaluated inside the multiply-accumulate kernel, so no full-size kernel spectrum is ever stored.  Along x
+ * (the slowest axis, transformed last) the common transform size of images and kernels is the library's choice
+ * per layer shape: the full n~ for batches; blocks of eight or no transform at all (the kx-tap sum written out)
+ * where a full-length kernel spectrum value would serve one input only.  The valid outputs are the same numbers
+ * up to fp32 rounding whichever is taken.  Bias and transfer function are applied where the inverse transform
+ * finishes an output image (Section IV-A-3).
+ *
+ * Limits (every call validates them on the host and returns the status named)
+ *   - transform size per axis at most ZNNI_MAX_FFT = 1024, i.e. image edges up to 1024 (ZNNI_ERR_UNSUPPORTED_SIZE);
+ *   - S*f and S*f' at most 65535 (launch grid), (f'+15)*(f+3)*kmax^2 and S*max(f,f')*nmax at most 2^30
+ *     (32-bit index products inside the kernels) (ZNNI_ERR_SHAPE);
+ *   - direct primitive: kernels whose staged image tile fits the 160 KB of LDS, about 6^3 taps and below
+ *     (ZNNI_ERR_UNSUPPORTED_SIZE); pooling: window at most 4 and image edge at most 4096 per axis;
+ *   - znni_conv3d_fft_static_v: layers whose workspace fits ZNNI_STATIC_SCRATCH_BYTES (ZNNI_ERR_WORKSPACE);
+ *   - the workspace size reported by the *_workspace calls includes (f~ + 64) * f'~ zeroed complex elements
+ *     (f~ = f rounded up to 4, f'~ = f' to 16) after the stored kernel transforms, which two multiply-accumulate kernels
+ *     read (and discard) one iteration past the last frequency bin; nothing is read or written outside the
+ *     workspace and the tensors for any shape within these limits.
  *
  * Conventions for every function below
  *   - Returns a znni_status; never throws, aborts or prints.
@@ -73,8 +89,8 @@ enum {
                                     /* eight inside the multiply-accumulate (transforms along z and y as for    */
                                     /* ZNNI_MAC_XDIRECT; 8 / (9 - kx) multiply-adds per output instead of kx;   */
                                     /* ignored where it does not exist: other than 4 or 5 taps along x, fewer   */
-                                    /* than 16 input images, more than 48 output images per row block, or no    */
-                                    /* in-register y pass kernel); without any of these flags the library picks */
+                                    /* than 16 input images, or no in-register y pass kernel); without any of   */
+                                    /* these flags the library picks                                            */
 };
 
 /* Stages reported by znni_conv3d_fft_profile, in execution order (Algorithm 3 of Section IV-B-2). */
@@ -237,9 +253,10 @@ znni_status znni_conv3d_direct_v(int S, int f, int fo, const int n[3], const int
  * were measured on MI355X and writes the pick to *primitive; est_ms, if not NULL, receives the two estimates in
  * milliseconds (index = primitive; negative = that primitive does not take this shape).
  * znni_conv3d_workspace_v / znni_conv3d_v are the workspace query and the layer call of the picked primitive;
- * arguments as for znni_conv3d_fft_v.  When the direct route is picked, ZNNI_MAC_SINGLE and ZNNI_MAC_BATCH are
- * accepted and ignored (they choose between forms of the transform route only) and ZNNI_MAC_REFERENCE is rejected
- * with ZNNI_ERR_FLAGS.
+ * arguments as for znni_conv3d_fft_v.  When the direct route is picked, ZNNI_MAC_SINGLE, _BATCH, _XDIRECT and
+ * _XBLOCK are accepted (at most one) and ignored: they choose between forms of the transform route only.
+ * ZNNI_KEEP_KERNELS is ignored there too (that route keeps nothing a later call could reuse and rearranges the bank
+ * on every call), and ZNNI_MAC_REFERENCE is rejected with ZNNI_ERR_FLAGS.
  */
 enum { ZNNI_PRIMITIVE_FFT = 0, ZNNI_PRIMITIVE_DIRECT = 1 };
 

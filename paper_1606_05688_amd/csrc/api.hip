@@ -79,13 +79,20 @@ static bool pick_untransformed_x(const LayerPlan& L, unsigned flags)
 // ... and whether it applies the kernel's taps along x through length-8 transforms of overlapping blocks
 // (mac_xb.hip) rather than as shifted reads: wherever that form exists (4 or 5 taps).  Measured, whole layer:
 // 48 -> 48 images of 320^3, 5^3 kernels 18.6 against 20.9 ms; 48 -> 48 of 240^3, 4^3: 7.8 against 8.2 ms;
-// 2 x 32 -> 32 of 128^3, 5^3: 1.49 against 1.55 ms.
+// 2 x 32 -> 32 of 128^3, 5^3: 1.49 against 1.55 ms; 80 -> 80 of 200^3, 5^3 (row blocks of three and two tiles):
+// 12.0 against 14.4 ms, with 4^3 kernels 11.2 against 12.4 ms.
 static bool pick_xblock(const LayerPlan& L, unsigned flags)
 {
     if (!mac_xb_available(L) || !fast_pass_available(L.d.Ny)) return false;
     if (flags & ZNNI_MAC_XBLOCK) return true;
     if (flags & ZNNI_MAC_XDIRECT) return false;
-    return pick_untransformed_x(L, flags);
+    if (pick_untransformed_x(L, flags)) return true;
+    // small images (one kernel per side for the z and y transforms of the fully transformed route): ahead only with
+    // five taps and at least 24 blocks along x.  Measured, blocks against full length: 80 -> 80 images of 100^3, 5^3
+    // kernels 1.81 against 2.08 ms; 4 x 48 -> 48 of 100^3 2.57 against 2.91; 48 -> 48 of 120^3 1.31 against 1.39;
+    // but 80 -> 80 of 120^3 with 4^3 kernels 2.75 against 2.69, 80 -> 80 of 60^3 with 5^3 0.67 against 0.52.
+    if (flags & (ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH)) return false;
+    return L.d.kx == 5 && L.d.nox >= 96 && !mac_batch_preferred(L);
 }
 
 static bool pick_xdirect(const LayerPlan& L, unsigned flags)

@@ -132,6 +132,7 @@ struct XbArgs {
     int nch;                          // chunks of eight input images
     int nblk;                         // blocks along x: ceil(nox / V)
     int n2, n1, blk1, nmblk, npencils, accumulate;
+    int m_base;                       // first output-image row of this launch (row blocks of another height before it)
 };
 
 template <int RTW, int CTW>
@@ -141,7 +142,7 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
     const int colblk = sub % ncolblk, mblk = sub / ncolblk;
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int l16 = lane & 15, kk = lane >> 4;
-    const int m0 = mblk * RTW * 16;
+    const int m0 = g.m_base + mblk * RTW * 16;
     const int b0 = blk0 + colblk * NB;          // first block of the workgroup
     const int sI = blockIdx.y;
     const int f = g.f, Mp = g.Mp, K = g.K, V = XB - K + 1;
@@ -296,12 +297,12 @@ __global__ __launch_bounds__(256, 2) void k_mac_xb(XbArgs g)
 
 // ---------------------------------------------------------------------------------------- host side
 // Four or five taps along x (four or five outputs per block of eight: with fewer taps the stored transforms grow by
-// more than the products shrink), at least 16 input images (they go through in groups of eight), row blocks of at
-// most three tiles (the accumulators of two frequencies per wave must fit the registers), a batch index that fits
-// the launch grid.
+// more than the products shrink), at least 16 input images (they go through in groups of eight), a batch index that
+// fits the launch grid.  Output images go in row blocks of three or two tiles of 16 (the accumulators of two
+// frequencies per wave must fit the registers); each row block transforms the image blocks again.
 bool mac_xb_available(const LayerPlan& L)
 {
-    return L.d.kx >= 4 && L.d.kx <= 5 && L.f >= 16 && L.mac_RTW <= 3 && L.S <= 65535;
+    return L.d.kx >= 4 && L.d.kx <= 5 && L.f >= 16 && L.S <= 65535;
 }
 
 size_t mac_xb_kernel_bytes(const LayerPlan& L)
@@ -338,7 +339,7 @@ znni_status launch_kprep_yb(const LayerPlan& L, hipStream_t st)
 }
 
 template <int RTW, bool WIDE>
-static znni_status launch_xb(const LayerPlan& L, int accumulate, hipStream_t st)
+static znni_status launch_xb(const LayerPlan& L, int accumulate, int m_base, int nmblk, hipStream_t st)
 {
     const Dims& d = L.d;
     XbArgs g;
@@ -353,7 +354,8 @@ static znni_status launch_xb(const LayerPlan& L, int accumulate, hipStream_t st)
     g.n2 = WIDE ? g.nblk / 32 : 0;
     g.n1 = (g.nblk - g.n2 * 32 + 15) / 16;
     g.blk1 = g.n2 * 32;
-    g.nmblk = L.mac_nmblk;
+    g.nmblk = nmblk;
+    g.m_base = m_base;
     g.npencils = d.zc * d.Ny;
     g.accumulate = accumulate;
     const int per_pencil = (g.n2 + g.n1) * g.nmblk;
@@ -364,24 +366,25 @@ static znni_status launch_xb(const LayerPlan& L, int accumulate, hipStream_t st)
     return ZNNI_OK;
 }
 
+template <bool WIDE>
+static znni_status launch_xb_rows(const LayerPlan& L, int accumulate, hipStream_t st)
+{
+    // the 16-row tiles that hold output images, dealt to row blocks of three tiles, then of two (one tile: one block)
+    const int q = (L.fo + 15) / 16;
+    if (q == 1) return launch_xb<1, WIDE>(L, accumulate, 0, 1, st);
+    const int n2 = q % 3 == 0 ? 0 : (q % 3 == 1 ? 2 : 1), n3 = (q - 2 * n2) / 3;
+    znni_status rc = ZNNI_OK;
+    if (n3) rc = launch_xb<3, WIDE>(L, accumulate, 0, n3, st);
+    if (rc == ZNNI_OK && n2) rc = launch_xb<2, WIDE>(L, accumulate, 48 * n3, n2, st);
+    return rc;
+}
+
 znni_status launch_mac_xb(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     if (!mac_xb_available(L)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const int V = XB - L.d.kx + 1;
-    const bool wide = (L.d.nox + V - 1) / V >= 32;
-    if (wide) {
-        switch (L.mac_RTW) {
-            case 1: return launch_xb<1, true>(L, accumulate, st);
-            case 2: return launch_xb<2, true>(L, accumulate, st);
-            case 3: return launch_xb<3, true>(L, accumulate, st);
-        }
-    }
-    switch (L.mac_RTW) {
-        case 1: return launch_xb<1, false>(L, accumulate, st);
-        case 2: return launch_xb<2, false>(L, accumulate, st);
-        case 3: return launch_xb<3, false>(L, accumulate, st);
-    }
-    return ZNNI_ERR_SHAPE;
+    return (L.d.nox + V - 1) / V >= 32 ? launch_xb_rows<true>(L, accumulate, st)
+                                       : launch_xb_rows<false>(L, accumulate, st);
 }
 
 }  // namespace znni

@@ -127,7 +127,7 @@ __global__ void k_fwd_x(const float2* __restrict__ X2, float2* __restrict__ Xt, 
     const int N = P.N;
     Lds L = carve(lds, N, TL, twg);
     const int oy0 = blockIdx.x * TL, oz = blockIdx.y, img = blockIdx.z;
-    const int nx = d.nx, Ny = d.Ny, zc = d.zc;
+    const int nx = d.nx, Ny = d.Ny;
     const int nvalid = min(TL, Ny - oy0);
     const float2* src = X2 + ((size_t)img * d.x2i + (size_t)oz * d.x2o + oy0) * d.ldx;
     for (int e = threadIdx.x; e < TL * N; e += blockDim.x) {

@@ -65,7 +65,7 @@ def test_workspace_holds_both_spectra_and_partial_kernel_transforms():
         fp, Mp = (f + 3) // 4 * 4, (fo + 15) // 16 * 16     # kernel transforms are stored padded to matrix-core tiles
         # ... with k values per kernel column along x, or 8 (and input images in groups of 8) where the route that
         # transforms x in blocks of eight exists: the workspace does not depend on the flags of a call
-        blocks = k in (4, 5) and f >= 16 and Mp <= 48
+        blocks = k in (4, 5) and f >= 16
         need = 8 * zc * N * N * S * (f + fo) + 8 * zc * N * Mp * ((f + 7) // 8 * 8 * 8 if blocks else fp * k)
         got = B.znni_conv3d_fft_workspace(S, f, fo, n, k)
         assert need <= got <= 1.1 * need + (1 << 20)

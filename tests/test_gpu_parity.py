@@ -380,7 +380,10 @@ XDIRECT = [(1, 3, 2, (9, 16, 16), (1, 3, 3)), (1, 5, 17, (37, 12, 20), (2, 3, 2)
            # blocks of eight along x: ragged last block, more than 32 blocks (wide and narrow column blocks), a number
            # of input images that is no multiple of 8 or 4, several inputs per batch, two row blocks, one block only
            (1, 19, 40, (141, 8, 10), (5, 2, 2)), (2, 20, 48, (70, 10, 8), (4, 3, 2)), (1, 16, 7, (203, 8, 8), (4, 2, 2)),
-           (1, 33, 96, (77, 8, 12), (5, 2, 3)), (3, 24, 4, (8, 12, 10), (5, 3, 2)), (1, 17, 3, (300, 8, 8), (4, 2, 2))]
+           (1, 33, 96, (77, 8, 12), (5, 2, 3)), (3, 24, 4, (8, 12, 10), (5, 3, 2)), (1, 17, 3, (300, 8, 8), (4, 2, 2)),
+           # ... output images in row blocks of different heights (five tiles = 3 + 2, four = 2 + 2, seven = 3 + 2 + 2)
+           (1, 16, 80, (50, 8, 10), (5, 2, 2)), (1, 24, 64, (37, 10, 8), (4, 3, 2)), (2, 17, 112, (30, 8, 8), (5, 2, 2)),
+           (1, 16, 70, (170, 8, 8), (4, 2, 2))]
 
 
 @pytest.mark.parametrize("shape", XDIRECT, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
