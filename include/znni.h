@@ -85,6 +85,10 @@ enum {
                                     /* paid once per network and not once per patch.  The caller vouches: the   */
                                     /* library cannot tell stale transforms from fresh ones.  w is not read.    */
                                     /* Rejected by znni_conv3d_fft_budget_v (its sub-layers share the space).   */
+    ZNNI_PASSES_REFERENCE = 128u,   /* diagnostic: run every transform pass with the generic kernels (lines staged in  */
+                                    /* LDS, radix-2/3/4/5/7/8 stages) instead of the in-register ones, which serve all */
+                                    /* transform sizes from 8 up: an independent implementation of the same passes,    */
+                                    /* about half as fast.  Excludes the routes that do not transform x at full length */
     ZNNI_MAC_XBLOCK = 32u           /* force the route that transforms the x axis in overlapping blocks of      */
                                     /* eight inside the multiply-accumulate (transforms along z and y as for    */
                                     /* ZNNI_MAC_XDIRECT; 8 / (9 - kx) multiply-adds per output instead of kx;   */
@@ -113,12 +117,12 @@ int znni_version(void);
 const char* znni_status_string(int st);
 
 /*
- * Transform size n~ used for an image edge n.  Supported sizes are the products 2^a 3^b 5^c 7^d (the family
- * Section III-D names for GPU transforms) up to ZNNI_MAX_FFT.  The valid outputs of a circular convolution of
- * any length n~ >= n never wrap, so the choice is one of speed only: the smallest supported size m0 >= n is
- * taken unless a size at most one sixth larger is served by the faster in-register pass kernels and m0 is not
- * (e.g. 125 -> 128 rather than 126).  The result is always in [n, m0 + m0/6]; n itself whenever n is one of
- * the in-register sizes (16, 64, 128, 256, 320, ...).  Returns 0 if there is no supported size.  Host only.
+ * Transform size n~ used for an image edge n.  Members of the family 2^a 3^b 5^c 7^d that Section III-D names for
+ * GPU transforms, up to ZNNI_MAX_FFT.  The valid outputs of a circular convolution of any length n~ >= n never wrap,
+ * so the choice is one of speed only: the smallest of the 46 lengths that the in-register pass kernels serve (8, 10,
+ * 12, 14, 16, 20, 24, 28, 32, 36, 40, 48, 56, 64, 72, 80, 84, 96, 100, 112, 120, 128, 144, 160, 168, 192, 200, 224,
+ * 240, 256, 288, 320, 336, 384, 400, 448, 480, 512, 576, 640, 720, 768, 840, 896, 960, 1024) that is >= n, at most
+ * 20 % above n; n itself for n < 7.  Returns 0 if there is no supported size (n < 1 or n > ZNNI_MAX_FFT).  Host only.
  */
 #define ZNNI_MAX_FFT 1024
 int znni_fft_size(int n);
@@ -136,7 +140,8 @@ znni_status znni_conv3d_fft_workspace(int S, int f, int fo, int n, int k, size_t
  *   w         [fo][f][k][k][k]         device, read-only
  *   bias      [fo] device, read-only, or NULL for zero bias
  *   out       [S][fo][n-k+1]^3         device, written (every element)
- *   flags     bitwise OR of ZNNI_RELU, ZNNI_KEEP_KERNELS and at most one of the ZNNI_MAC_* flags, or 0
+ *   flags     bitwise OR of ZNNI_RELU, ZNNI_KEEP_KERNELS, ZNNI_PASSES_REFERENCE and at most one of the ZNNI_MAC_*
+ *             flags, or 0
  *   workspace device scratch of at least znni_conv3d_fft_workspace() bytes, 256-byte aligned; contents on
  *             entry are ignored, contents on return are unspecified.  Calls that share a workspace must
  *             not overlap in time.

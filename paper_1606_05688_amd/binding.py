@@ -19,6 +19,7 @@ MAC_BATCH = 8
 MAC_XDIRECT = 16
 MAC_XBLOCK = 32
 KEEP_KERNELS = 64
+PASSES_REFERENCE = 128
 STAGES = ("kernel_prep", "fwd_z", "fwd_y", "fwd_x", "mac", "inv_x", "inv_y", "inv_z")
 EXPORTS = ("znni_version", "znni_status_string", "znni_fft_size", "znni_conv3d_fft_workspace",
            "znni_conv3d_fft", "znni_conv3d_fft_profile", "znni_conv3d_fft_workspace_v", "znni_conv3d_fft_v",
@@ -127,9 +128,10 @@ def alloc_workspace(S, f, fo, n, k, device="cuda"):
 
 def _flags(relu, mac_reference, keep_kernels=False):
     """mac_reference: False/True, or one of the strings 'single' / 'batch' / 'xdirect' / 'xblock' to force a
-    multiply-accumulate form."""
+    multiply-accumulate form, or 'generic_passes' for the diagnostic that runs the generic transform passes."""
     m = {False: 0, None: 0, True: MAC_REFERENCE, "reference": MAC_REFERENCE, "single": MAC_SINGLE,
-         "batch": MAC_BATCH, "xdirect": MAC_XDIRECT, "xblock": MAC_XBLOCK}[mac_reference]
+         "batch": MAC_BATCH, "xdirect": MAC_XDIRECT, "xblock": MAC_XBLOCK,
+         "generic_passes": PASSES_REFERENCE}[mac_reference]
     return (RELU if relu else 0) | m | (KEEP_KERNELS if keep_kernels else 0)
 
 

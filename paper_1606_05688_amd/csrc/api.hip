@@ -15,33 +15,17 @@ static __device__ __align__(256) unsigned char scratch[ZNNI_STATIC_SCRATCH_BYTES
 
 namespace znni {
 
-static bool smooth7(int m)
-{
-    for (int p : {2, 3, 5, 7})
-        while (m % p == 0) m /= p;
-    return m == 1;
-}
-
-// Transform size for an image edge n: a 7-smooth length >= n.  The smallest one, m0, unless a length up to
-// one sixth longer is cheaper: the pass kernels (about half of a layer's time) run 2.2 times faster per element
-// for the lengths served by the in-register kernels, and everything grows in proportion to the length, so a
-// layer costs about 1.66 units per element of a generic length against 1 of an in-register one.
+// Transform size for an image edge n: the smallest length >= n that the in-register pass kernels serve (46
+// members of the 2^a 3^b 5^c 7^d family from 8 to 1024, never more than 20 % above n); below 7 the edge itself (all
+// of 1..6 are members), transformed by the generic pass kernels.  A layer's cost grows in proportion to the length,
+// and the generic kernels run at well under half the speed per element, so a nearer generic length never pays.
 static int fft_size(int n)
 {
     if (n < 1) return 0;
-    int m0 = 0;
+    if (n < 7) return n;
     for (int m = n; m <= ZNNI_MAX_FFT; ++m)
-        if (smooth7(m)) { m0 = m; break; }
-    if (m0 == 0) return 0;
-    int best = m0;
-    double best_cost = m0 * (fast_pass_available(m0) ? 1.0 : 1.66);
-    const int hi = m0 + m0 / 6 < ZNNI_MAX_FFT ? m0 + m0 / 6 : ZNNI_MAX_FFT;
-    for (int m = m0 + 1; m <= hi; ++m) {
-        if (!smooth7(m)) continue;
-        const double cost = m * (fast_pass_available(m) ? 1.0 : 1.66);
-        if (cost < best_cost) { best = m; best_cost = cost; }
-    }
-    return best;
+        if (fast_pass_available(m)) return m;
+    return 0;
 }
 
 // Radix schedule: odd primes first, then the power of two as 8s with a 4,4 / 4 / 2 tail.
@@ -83,7 +67,7 @@ static bool pick_untransformed_x(const LayerPlan& L, unsigned flags)
 // 12.0 against 14.4 ms, with 4^3 kernels 11.2 against 12.4 ms.
 static bool pick_xblock(const LayerPlan& L, unsigned flags)
 {
-    if (!mac_xb_available(L) || !fast_pass_available(L.d.Ny)) return false;
+    if (L.generic_passes || !mac_xb_available(L) || !fast_pass_available(L.d.Ny)) return false;
     if (flags & ZNNI_MAC_XBLOCK) return true;
     if (flags & ZNNI_MAC_XDIRECT) return false;
     if (pick_untransformed_x(L, flags)) return true;
@@ -98,7 +82,7 @@ static bool pick_xblock(const LayerPlan& L, unsigned flags)
 static bool pick_xdirect(const LayerPlan& L, unsigned flags)
 {
     if (L.xblock) return true;
-    if (!mac_xd_available(L) || !fast_pass_available(L.d.Ny)) return false;
+    if (L.generic_passes || !mac_xd_available(L) || !fast_pass_available(L.d.Ny)) return false;
     if (flags & ZNNI_MAC_XDIRECT) return true;
     if (flags & ZNNI_MAC_XBLOCK) return false;
     return pick_untransformed_x(L, flags);
@@ -137,6 +121,7 @@ static znni_status shape_plan(int S, int f, int fo, const int n[3], const int k[
     L->nimgo = S * fo;
     L->fp = (f + 3) & ~3;
     plan_mac(L);        // also sets Mp
+    L->generic_passes = (flags & ZNNI_PASSES_REFERENCE) != 0;
     L->xblock = pick_xblock(*L, flags);
     L->xdirect = pick_xdirect(*L, flags);
     // X2 and Yd are ordered [image][oz][oy]; the order [oz][image][oy] was measured too: 2 % faster for the
@@ -305,7 +290,7 @@ static znni_status choose_division(int S, int f, int fo, const int n[3], const i
 static bool flags_ok(unsigned flags)
 {
     const unsigned all_forms = ZNNI_MAC_REFERENCE | ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT | ZNNI_MAC_XBLOCK;
-    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_KEEP_KERNELS | all_forms)) return false;
+    if (flags & ~(unsigned)(ZNNI_RELU | ZNNI_KEEP_KERNELS | ZNNI_PASSES_REFERENCE | all_forms)) return false;
     const unsigned forms = flags & all_forms;
     return (forms & (forms - 1)) == 0;
 }

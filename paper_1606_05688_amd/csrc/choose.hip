@@ -110,11 +110,13 @@ znni_status znni_conv3d_v(int S, int f, int fo, const int n[3], const int k[3], 
         if (in && w && out && (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 15u)) return ZNNI_ERR_ALIGN;
         // the hints that pick a multiply-accumulate form mean nothing to the direct route: validated, then dropped
         // (at most one, as on the transform route); the direct route stores no kernel transforms a later call
-        // could reuse, so ZNNI_KEEP_KERNELS is dropped as well: the bank is rearranged again, which is always right
+        // could reuse, so ZNNI_KEEP_KERNELS is dropped as well: the bank is rearranged again, which is always right; it
+        // has no transform passes either
         const unsigned forms = flags & (unsigned)(ZNNI_MAC_SINGLE | ZNNI_MAC_BATCH | ZNNI_MAC_XDIRECT | ZNNI_MAC_XBLOCK);
         if (forms & (forms - 1)) return ZNNI_ERR_FLAGS;
         return znni_conv3d_direct_v(S, f, fo, n, k, in, w, bias, out,
-                                    flags & ~(forms | (unsigned)ZNNI_KEEP_KERNELS), workspace, workspace_bytes, stream);
+                                    flags & ~(forms | (unsigned)(ZNNI_KEEP_KERNELS | ZNNI_PASSES_REFERENCE)), workspace,
+                                    workspace_bytes, stream);
     }
     return znni_conv3d_fft_v(S, f, fo, n, k, in, w, bias, out, flags, workspace, workspace_bytes, stream);
 }

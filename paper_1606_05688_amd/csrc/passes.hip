@@ -285,7 +285,7 @@ znni_status launch_twiddles(const LayerPlan& L, hipStream_t st)
 znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Nz)) return launch_fast_fwd_z(L, in, st);
+    if (!L.generic_passes && fast_pass_available(d.Nz)) return launch_fast_fwd_z(L, in, st);
     const int TL = lines_per_tile(d.Nz);
     const size_t lds = pass_lds_bytes(d.Nz, TL / 2);
     znni_status rc = allow_lds((const void*)k_fwd_z, lds);
@@ -299,7 +299,7 @@ znni_status launch_fwd_z(const LayerPlan& L, const float* in, hipStream_t st)
 znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Ny)) return launch_fast_fwd_y(L, st);
+    if (!L.generic_passes && fast_pass_available(d.Ny)) return launch_fast_fwd_y(L, st);
     const int TL = lines_per_tile(d.Ny);
     const size_t lds = pass_lds_bytes(d.Ny, TL);
     znni_status rc = allow_lds((const void*)k_fwd_y, lds);
@@ -313,7 +313,7 @@ znni_status launch_fwd_y(const LayerPlan& L, hipStream_t st)
 znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Nx)) return launch_fast_fwd_x(L, st);
+    if (!L.generic_passes && fast_pass_available(d.Nx)) return launch_fast_fwd_x(L, st);
     const int TL = lines_per_tile(d.Nx);
     const size_t lds = pass_lds_bytes(d.Nx, TL);
     znni_status rc = allow_lds((const void*)k_fwd_x, lds);
@@ -327,7 +327,7 @@ znni_status launch_fwd_x(const LayerPlan& L, hipStream_t st)
 znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Nx)) return launch_fast_inv_x(L, st);
+    if (!L.generic_passes && fast_pass_available(d.Nx)) return launch_fast_inv_x(L, st);
     const int TL = lines_per_tile(d.Nx);
     const size_t lds = pass_lds_bytes(d.Nx, TL);
     znni_status rc = allow_lds((const void*)k_inv_x, lds);
@@ -341,7 +341,7 @@ znni_status launch_inv_x(const LayerPlan& L, hipStream_t st)
 znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Ny)) return launch_fast_inv_y(L, st);
+    if (!L.generic_passes && fast_pass_available(d.Ny)) return launch_fast_inv_y(L, st);
     const int TL = lines_per_tile(d.Ny);
     const size_t lds = pass_lds_bytes(d.Ny, TL);
     znni_status rc = allow_lds((const void*)k_inv_y, lds);
@@ -355,7 +355,7 @@ znni_status launch_inv_y(const LayerPlan& L, hipStream_t st)
 znni_status launch_inv_z(const LayerPlan& L, const float* bias, float* out, unsigned flags, hipStream_t st)
 {
     const Dims& d = L.d;
-    if (fast_pass_available(d.Nz)) return launch_fast_inv_z(L, bias, out, flags, st);
+    if (!L.generic_passes && fast_pass_available(d.Nz)) return launch_fast_inv_z(L, bias, out, flags, st);
     const int TL = lines_per_tile(d.Nz);
     const size_t lds = pass_lds_bytes(d.Nz, TL / 2);
     znni_status rc = allow_lds((const void*)k_inv_z, lds);

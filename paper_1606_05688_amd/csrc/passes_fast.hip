@@ -1,5 +1,5 @@
 // passes_fast.hip -- the six transform passes for transform lengths N = R1*R2 with both factors small enough
-// for an in-register DFT (35 lengths from 8 to 512, listed in launch_kind).  Same layouts, pruning and results
+// for an in-register DFT (46 lengths from 8 to 1024, listed in launch_kind).  Same layouts, pruning and results
 // as passes.hip.
 //
 // One workgroup transforms a tile of 16 lines (passes along z: 16 pairs of real lines).  Each line is done in
@@ -39,11 +39,10 @@ struct PassArgs {
 __host__ __device__ inline bool inv_x_flat(const Dims& d) { return d.ldn == d.Ny && d.Ny > 16 && (d.Ny & 15) != 0; }
 
 template <int R1, int R2, int KIND>
-__global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
+__device__ __forceinline__ void pass_body(const PassArgs& a, float2* lds)
 {
     using TS = TwoStep<R1, R2>;
     constexpr int N = TS::N, P = TS::P, NTH = TS::NTH;
-    extern __shared__ float2 lds[];
     float2* tws = lds;
     float2* buf = lds + N;
     // Streaming accesses only where a lane group moves whole 128-byte lines per instruction (R2 = 16 samples of a
@@ -262,16 +261,38 @@ __global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
     }
 }
 
+template <int R1, int R2, int KIND>
+__global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) void k_pass(PassArgs a)
+{
+    extern __shared__ float2 lds[];
+    pass_body<R1, R2, KIND>(a, lds);
+}
+
+// Lengths from 640 on: the tile's LDS leaves room for one workgroup of 512 threads per CU, two waves per SIMD, and
+// the compiler is told so.  (Left to assume more resident waves it holds the kernel to about 90 registers, and from
+// 28 samples per thread on it then waits for each pair of loads of the real-to-complex pass before issuing the
+// next: 1.6 to 2 TB/s instead of over 4.)
+template <int R1, int R2, int KIND>
+__global__ __launch_bounds__(16 * (R1 > R2 ? R1 : R2)) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_pass_long(PassArgs a)
+{
+    extern __shared__ float2 lds[];
+    pass_body<R1, R2, KIND>(a, lds);
+}
+
 // ------------------------------------------------------------------------------------------- host side
 template <int R1, int R2, int KIND>
 static znni_status launch_one(const PassArgs& a, dim3 grid, hipStream_t st)
 {
     using TS = TwoStep<R1, R2>;
-    const void* fn = (const void*)k_pass<R1, R2, KIND>;
+    constexpr bool LONG = TS::LDS_BYTES > 80 * 1024;      // from length 640 on; two tiles of length 576 share a CU
+    const void* fn = LONG ? (const void*)k_pass_long<R1, R2, KIND> : (const void*)k_pass<R1, R2, KIND>;
     if (TS::LDS_BYTES > 48 * 1024 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TS::LDS_BYTES) != hipSuccess)
         return ZNNI_ERR_HIP;
-    k_pass<R1, R2, KIND><<<grid, dim3(TS::NTH), TS::LDS_BYTES, st>>>(a);
+    if constexpr (LONG)
+        k_pass_long<R1, R2, KIND><<<grid, dim3(TS::NTH), TS::LDS_BYTES, st>>>(a);
+    else
+        k_pass<R1, R2, KIND><<<grid, dim3(TS::NTH), TS::LDS_BYTES, st>>>(a);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }
@@ -285,6 +306,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
         // the real-to-complex pass loads two rows per thread in step A, 2*R1 values: with R1 above 20 that is more
         // than a wave keeps in flight, so the long lengths are split the other way round
         switch (N) {
+            case 336: return launch_one<12, 28, KIND>(a, grid, st);
             case 384: return launch_one<16, 24, KIND>(a, grid, st);
             case 448: return launch_one<16, 28, KIND>(a, grid, st);
             case 480: return launch_one<16, 30, KIND>(a, grid, st);
@@ -341,6 +363,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
         case 64: return launch_one<8, 8, KIND>(a, grid, st);
         case 72: return launch_one<9, 8, KIND>(a, grid, st);
         case 80: return launch_one<5, 16, KIND>(a, grid, st);
+        case 84: return launch_one<6, 14, KIND>(a, grid, st);
         case 96: return launch_one<6, 16, KIND>(a, grid, st);
         case 100: return launch_one<10, 10, KIND>(a, grid, st);
         case 112: return launch_one<7, 16, KIND>(a, grid, st);
@@ -348,6 +371,7 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
         case 128: return launch_one<8, 16, KIND>(a, grid, st);
         case 144: return launch_one<9, 16, KIND>(a, grid, st);
         case 160: return launch_one<10, 16, KIND>(a, grid, st);
+        case 168: return launch_one<12, 14, KIND>(a, grid, st);
         case 192: return launch_one<12, 16, KIND>(a, grid, st);
         case 200: return launch_one<20, 10, KIND>(a, grid, st);
         case 224: return launch_one<14, 16, KIND>(a, grid, st);
@@ -355,11 +379,21 @@ static znni_status launch_kind(int N, const PassArgs& a, dim3 grid, hipStream_t 
         case 256: return launch_one<16, 16, KIND>(a, grid, st);
         case 288: return launch_one<18, 16, KIND>(a, grid, st);
         case 320: return launch_one<20, 16, KIND>(a, grid, st);
+        case 336: return launch_one<24, 14, KIND>(a, grid, st);
         case 384: return launch_one<24, 16, KIND>(a, grid, st);
         case 400: return launch_one<20, 20, KIND>(a, grid, st);
         case 448: return launch_one<28, 16, KIND>(a, grid, st);
         case 480: return launch_one<30, 16, KIND>(a, grid, st);
         case 512: return launch_one<32, 16, KIND>(a, grid, st);
+        // above 512 a tile of 16 lines takes 74 to 139 KB of LDS: from 640 on one workgroup of 512 threads per CU
+        case 576: return launch_one<18, 32, KIND>(a, grid, st);
+        case 640: return launch_one<20, 32, KIND>(a, grid, st);
+        case 720: return launch_one<24, 30, KIND>(a, grid, st);
+        case 768: return launch_one<24, 32, KIND>(a, grid, st);
+        case 840: return launch_one<28, 30, KIND>(a, grid, st);
+        case 896: return launch_one<28, 32, KIND>(a, grid, st);
+        case 960: return launch_one<30, 32, KIND>(a, grid, st);
+        case 1024: return launch_one<32, 32, KIND>(a, grid, st);
     }
     return ZNNI_ERR_UNSUPPORTED_SIZE;
 }
@@ -369,8 +403,9 @@ bool fast_pass_available(int N)
     switch (N) {
         case 8: case 10: case 12: case 14:
         case 16: case 20: case 24: case 28: case 32: case 36: case 40: case 48: case 56: case 64: case 72: case 80:
-        case 96: case 100: case 112: case 120: case 128: case 144: case 160: case 192: case 200: case 224: case 240:
-        case 256: case 288: case 320: case 384: case 400: case 448: case 480: case 512:
+        case 84: case 96: case 100: case 112: case 120: case 128: case 144: case 160: case 168: case 192: case 200:
+        case 224: case 240: case 256: case 288: case 320: case 336: case 384: case 400: case 448: case 480: case 512:
+        case 576: case 640: case 720: case 768: case 840: case 896: case 960: case 1024:
             return true;
     }
     return false;

@@ -365,7 +365,7 @@ static bool fused_split(int N, bool forward, int* R1, int* R2)
 static bool fused_shape(const LayerPlan& L, FusedShape* F, bool forward = false)
 {
     const Dims& d = L.d;
-    if (d.Ny != d.Nz) return false;
+    if (L.generic_passes || d.Ny != d.Nz) return false;
     int R1, R2;
     if (!fused_split(d.Ny, forward, &R1, &R2)) return false;
     F->R1 = R1; F->R2 = R2;

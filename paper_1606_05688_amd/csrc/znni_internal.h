@@ -36,6 +36,9 @@ struct LayerPlan {
     // ... and the kx taps are applied through length-8 transforms of overlapping blocks of X2 rows (mac_xb.hip)
     // instead of shifted reads; A then holds the length-8 transforms of the taps.  Implies xdirect.
     bool xblock;
+    // Diagnostic (ZNNI_PASSES_REFERENCE): every transform pass by the generic kernels of passes.hip, no fused z+y
+    // kernels, x axis transformed at full length.
+    bool generic_passes;
     int nimg;     // S * f
     int nimgo;    // S * fo
     int fp;       // f rounded up to a multiple of 4   (matrix-core k-step)

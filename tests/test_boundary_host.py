@@ -36,23 +36,25 @@ def test_status_strings():
     assert L.znni_status_string(-99) == b"unknown status"
 
 
-def test_fft_size_is_7_smooth_and_close_to_the_smallest():
+def test_fft_size_is_the_nearest_in_register_length():
     def smooth(m):
         for p in (2, 3, 5, 7):
             while m % p == 0:
                 m //= p
         return m == 1
-    picked_larger = 0
+    sizes = set()
     for n in range(1, 1025):
         m = B.znni_fft_size(n)
-        m0 = next(t for t in range(n, 1025) if smooth(t))
-        assert smooth(m) and m0 <= m <= m0 + m0 // 6
-        picked_larger += m > m0
-    assert 0 < picked_larger < 700      # the preference for in-register sizes is used, and not everywhere
+        assert smooth(m) and n <= m <= 1024 and 5 * m <= 6 * n + 5      # at most 20 % above n (rounded)
+        assert B.znni_fft_size(m) == m                                   # a size maps to itself
+        if n > 1:
+            assert m >= B.znni_fft_size(n - 1)                           # monotone
+        sizes.add(m)
+    assert len([m for m in sizes if m >= 8]) == 46 and {1, 2, 3, 4, 5, 6} <= sizes and 7 not in sizes
     assert B.znni_fft_size(125) == 128 and B.znni_fft_size(126) == 128 and B.znni_fft_size(243) == 256
-    assert B.znni_fft_size(17) == 20 and B.znni_fft_size(21) == 24
-    for n in (8, 12, 540, 700, 1000):         # no in-register size within reach: the smallest size itself
-        assert B.znni_fft_size(n) == n
+    assert B.znni_fft_size(17) == 20 and B.znni_fft_size(21) == 24 and B.znni_fft_size(7) == 8
+    assert B.znni_fft_size(81) == 84 and B.znni_fft_size(162) == 168 and B.znni_fft_size(324) == 336
+    assert B.znni_fft_size(540) == 576 and B.znni_fft_size(700) == 720 and B.znni_fft_size(1000) == 1024
     for n in (16, 64, 128, 320):
         assert B.znni_fft_size(n) == n          # the benchmark layers transform at their own size
     assert B.znni_fft_size(0) == 0 and B.znni_fft_size(-3) == 0 and B.znni_fft_size(1025) == 0
@@ -94,7 +96,7 @@ def test_layer_call_validates_before_any_gpu_work():
     assert call(inp=None) == -1 and call(w=None) == -1 and call(out=None) == -1 and call(wsp=None) == -1
     assert call(k=9) == -2 and call(S=0) == -2
     assert call(n=1025, k=1) == -3
-    assert call(flags=128) == -5 and call(flags=0x80000001) == -5
+    assert call(flags=256) == -5 and call(flags=0x80000001) == -5
     assert call(flags=64 | 1, wsb=1024) == -4                 # keeping stored kernel transforms is a known flag
     # at most one of the three bits that pick a multiply-accumulate form
     assert call(flags=2 | 4) == -5 and call(flags=4 | 8) == -5 and call(flags=1 | 2 | 8) == -5 and call(flags=8 | 16) == -5 and call(flags=16 | 32) == -5
@@ -264,4 +266,4 @@ def test_stage_work_follows_the_kernels_a_call_would_run():
     arr = (ctypes.c_double * 8)()
     assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 0, None, arr) == -1
     assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(9, 3, 3), 0, arr, arr) == -2
-    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 128, arr, arr) == -5
+    assert L.znni_conv3d_fft_stage_work_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), 256, arr, arr) == -5

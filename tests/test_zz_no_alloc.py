@@ -71,5 +71,5 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     p = inp.data_ptr()
     assert L.znni_conv3d_fft_static_v(1, 1, 1, i3((8, 8, 8)), i3((3, 3, 3)), None, p, None, p, 0, None) == -1
     assert L.znni_conv3d_fft_static_v(1, 1, 1, i3((8, 8, 8)), i3((9, 3, 3)), p, p, None, p, 0, None) == -2
-    assert L.znni_conv3d_fft_static_v(1, 1, 1, i3((8, 8, 8)), i3((3, 3, 3)), p, p, None, p, 128, None) == -5
+    assert L.znni_conv3d_fft_static_v(1, 1, 1, i3((8, 8, 8)), i3((3, 3, 3)), p, p, None, p, 256, None) == -5
     assert L.znni_conv3d_fft_static_v(1, 1, 1, i3((8, 8, 8)), i3((3, 3, 3)), p, p + 4, None, p, 0, None) == -7
