@@ -23,6 +23,8 @@
 // while the waves multiply the current chunk; one barrier per chunk.  At the end the accumulated block spectra
 // change hands through LDS once more (wave = frequency becomes thread = (output image, block)), are transformed
 // back, and the valid outputs of each block are stored as one contiguous run.
+#include <type_traits>
+
 #include "mac_common.h"
 
 namespace znni {
@@ -54,7 +56,7 @@ __device__ __forceinline__ void fft8(float2* v)
 // Ah[pencil][ch][p<8][kk<4][j<Mp][h<2] = scale * sum_{a<K} exp(-2 pi i a p / 8) sum_{b<ky} A1[oz][b][a][i][j] exp(-2 pi i oy b / Ny),
 // i = 8 ch + 4 h + kk; zero where i >= f or j >= fo (A1 holds zeros there, images beyond A1's fp rows are skipped).
 // One thread: one (ch, kk, j), both h, KB_OY consecutive oy, all K taps in registers; the two h are stored together.
-constexpr int KB_OY = 4;
+constexpr int KB_OY = 8;
 constexpr int KPREP_TAPS_XB = 64;
 template <int K>
 __global__ __launch_bounds__(256) void k_kprep_yb(const float2* __restrict__ A1, float2* __restrict__ Ah,
@@ -102,23 +104,83 @@ __global__ __launch_bounds__(256) void k_kprep_yb(const float2* __restrict__ A1,
         }
     }
     if (!live) return;
-    // exp(-2 pi i q / 8)
-    const float2 w8[8] = {{1.f, 0.f}, {kR8, -kR8}, {0.f, -1.f}, {-kR8, -kR8}, {-1.f, 0.f}, {-kR8, kR8}, {0.f, 1.f}, {kR8, kR8}};
+    // length-8 transform of the K taps (the other 8 - K inputs are zero and fold away)
 #pragma unroll
     for (int o = 0; o < KB_OY; ++o) {
         if (oy0 + o >= N) break;
         const size_t pencil = (size_t)oz * N + oy0 + o;
         float4* d = reinterpret_cast<float4*>(Ah) + ((pencil * nch + ch) * 8 * 4 + kk) * Mp + j;
+        float2 s0[XB], s1[XB];
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            float2 s0 = make_float2(0.f, 0.f), s1 = s0;
+        for (int a = 0; a < XB; ++a) {
+            s0[a] = a < K ? acc[0][a][o] : make_float2(0.f, 0.f);
+            s1[a] = a < K ? acc[1][a][o] : make_float2(0.f, 0.f);
+        }
+        fft8<false>(s0);
+        fft8<false>(s1);
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            d[(size_t)p * 4 * Mp] = make_float4(s0[p].x * scale, s0[p].y * scale, s1[p].x * scale, s1[p].y * scale);
+    }
+}
+
+// The same transform for kernels of up to 5 taps along y (KY a template parameter): a thread keeps the K * KY values
+// of A1 of both its images in registers and walks KR_OY consecutive oy with them, so that A1 (460 KB per oz on the
+// 48 -> 48 layer with 5^3 kernels) is read from the caches Ny / KR_OY times per call instead of Ny / KB_OY times: with
+// 4 oy per thread those reads were as many bytes as the kernel writes (1.74 ms), with 8 1.57 ms.
+constexpr int KR_OY = 32;
+template <int K, int KY>
+__global__ __launch_bounds__(256) void k_kprep_yb_r(const float2* __restrict__ A1, float2* __restrict__ Ah,
+                                                    const float2* __restrict__ tw, int N, int fp, int Mp, int nch,
+                                                    float scale)
+{
+    __shared__ float2 tw2[KR_OY][KY];
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (ch, kk, j)
+    const int oy0 = blockIdx.y * KR_OY, oz = blockIdx.z;
+    const int items = nch * 4 * Mp;
+    for (int e = threadIdx.x; e < KR_OY * KY; e += 256) {
+        const int o = e / KY, b = e - o * KY;
+        tw2[o][b] = tw[(unsigned)((oy0 + o) * b) % (unsigned)N];
+    }
+    __syncthreads();
+    if (idx >= items) return;
+    const int j = idx % Mp, kk = (idx / Mp) & 3, ch = idx / (4 * Mp);
+    const int per = K * fp * Mp;
+    float2 a1v[2][KY][K];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = min(8 * ch + 4 * h + kk, fp - 1);
+        const float m = 8 * ch + 4 * h + kk < fp ? 1.f : 0.f;          // images beyond A1's rows count as zero
+        const float2* a1 = A1 + (size_t)oz * KY * per + (size_t)i * Mp + j;
+#pragma unroll
+        for (int b = 0; b < KY; ++b)
 #pragma unroll
             for (int a = 0; a < K; ++a) {
-                s0 = cfma(s0, acc[0][a][o], w8[(a * p) & 7]);
-                s1 = cfma(s1, acc[1][a][o], w8[(a * p) & 7]);
+                const float2 v = a1[(size_t)b * per + (size_t)a * fp * Mp];
+                a1v[h][b][a] = make_float2(v.x * m, v.y * m);
             }
-            d[(size_t)p * 4 * Mp] = make_float4(s0.x * scale, s0.y * scale, s1.x * scale, s1.y * scale);
-        }
+    }
+    const int no = min(KR_OY, N - oy0);
+    float4* d = reinterpret_cast<float4*>(Ah) + ((((size_t)oz * N + oy0) * nch + ch) * 8 * 4 + kk) * Mp + j;
+    const size_t d_oy = (size_t)nch * 8 * 4 * Mp;
+    for (int o = 0; o < no; ++o, d += d_oy) {
+        float2 s[2][XB];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int a = 0; a < XB; ++a) {
+                float2 acc = make_float2(0.f, 0.f);
+                if (a < K) {
+#pragma unroll
+                    for (int b = 0; b < KY; ++b) acc = cfma(acc, a1v[h][b][a < K ? a : 0], tw2[o][b]);
+                }
+                s[h][a] = acc;
+            }
+        fft8<false>(s[0]);
+        fft8<false>(s[1]);
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            d[(size_t)p * 4 * Mp] = make_float4(s[0][p].x * scale, s[0][p].y * scale, s[1][p].x * scale, s[1][p].y * scale);
     }
 }
 
@@ -149,7 +211,8 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
     const int poz = pencil / g.Ny, poy = pencil - poz * g.Ny;
 
     // ---- this thread's share of the block transforms: block fb of image 4*fh + fkk of each chunk
-    const bool fft_on = t < 8 * NB;
+    // (a compile-time `true` for 32 blocks: all 256 threads transform)
+    const bool fft_on = (8 * NB >= 256) ? true : t < 8 * NB;
     const int fb = t % NB, fhk = min(t / NB, 7), fh = fhk >> 2, fkk = fhk & 3;
     const int gb = b0 + fb;                                 // block number along x
     const float2* xrow = g.X2 + (size_t)sI * f * g.ximg + (size_t)poz * g.xpen + (size_t)poy * g.ldx;
@@ -164,14 +227,6 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
 
     // ---- this wave's share of the products: frequencies 2*wave, 2*wave+1
     floatx4 p1[2][RTW][CTW], p2[2][RTW][CTW], p3[2][RTW][CTW];
-#pragma unroll
-    for (int pp = 0; pp < 2; ++pp)
-#pragma unroll
-        for (int r = 0; r < RTW; ++r)
-#pragma unroll
-            for (int c = 0; c < CTW; ++c) {
-                p1[pp][r][c] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[pp][r][c] = p1[pp][r][c]; p3[pp][r][c] = p1[pp][r][c];
-            }
     // A operands: float4 = (h = 0, h = 1) of Ah[pencil][ch][p][kk][j]
     const float4* Ab = reinterpret_cast<const float4*>(g.Ah) +
                        (((size_t)pencil * g.nch * 8 + 2 * wave) * 4 + kk) * Mp + m0 + l16;
@@ -196,12 +251,24 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
         for (int p = 0; p < XB; ++p) d[p * 4 * NB * 2] = xv[p];
     };
 
-    if (fft_on) { load_x(0); transform_x(0); }
+    load_x(0);
+    if (fft_on) transform_x(0);
     __syncthreads();
 
-    for (int ch = 0; ch < g.nch; ++ch) {
+    // One chunk of eight input images.  The first chunk's products start from zero through the instruction's own
+    // addend, which spares every wave 288 register moves for clearing the accumulators (1.4 % of the kernel's time).
+    auto chunk = [&](int ch, auto first_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
         const int chn = min(ch + 1, g.nch - 1);
-        if (fft_on) load_x(chn);                                  // travels during the products below
+        // The next chunk's image values travel during the products below.  Every thread requests them, also those
+        // without a transform to do (16 blocks: the upper half repeats the last image's requests), and nothing may
+        // move across the fence: inside a branch, the wait for the kernel operands (requested earlier, but counted
+        // in order) has to assume the image loads were never issued and ends up waiting for them too; and without
+        // the fence the scheduler sinks the loads below the products, right in front of their use.  Either way the
+        // loads did not overlap with the products: 7.2 against 6.8 ms on the 320-wide workload.
+        load_x(chn);
+        __builtin_amdgcn_sched_barrier(0);
         const float4* an = Ab + (size_t)chn * a_ch;
         const float4* Bs = reinterpret_cast<const float4*>(Ds + (ch & 1) * DS_BUF) + ((2 * wave) * 4 + kk) * NB + l16;
 #pragma unroll
@@ -218,9 +285,9 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
                 const float as0 = a.x + a.y, as1 = a.z + a.w;
 #pragma unroll
                 for (int c = 0; c < CTW; ++c) {
-                    p1[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, bv[c].x, p1[pp][r][c], 0, 0, 0);
-                    p2[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, bv[c].y, p2[pp][r][c], 0, 0, 0);
-                    p3[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as0, bs0[c], p3[pp][r][c], 0, 0, 0);
+                    p1[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, bv[c].x, FIRST ? zero : p1[pp][r][c], 0, 0, 0);
+                    p2[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, bv[c].y, FIRST ? zero : p2[pp][r][c], 0, 0, 0);
+                    p3[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as0, bs0[c], FIRST ? zero : p3[pp][r][c], 0, 0, 0);
                     p1[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, bv[c].z, p1[pp][r][c], 0, 0, 0);
                     p2[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, bv[c].w, p2[pp][r][c], 0, 0, 0);
                     p3[pp][r][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(as1, bs1[c], p3[pp][r][c], 0, 0, 0);
@@ -230,7 +297,9 @@ __device__ __forceinline__ void mac_xb_body(float2* lds, const XbArgs& g, int bl
         }
         if (fft_on && ch + 1 < g.nch) transform_x((ch + 1) & 1);
         __syncthreads();
-    }
+    };
+    chunk(0, std::true_type{});
+    for (int ch = 1; ch < g.nch; ++ch) chunk(ch, std::false_type{});
 
     // ---- block spectra change hands: Ex[p][jl<16][b<NB], one tile of 16 output images at a time
     float2* const Ex = lds;
@@ -311,10 +380,30 @@ size_t mac_xb_kernel_bytes(const LayerPlan& L)
     return (size_t)L.d.zc * L.d.Ny * nch * 8 * 4 * L.Mp * 2 * sizeof(float2);
 }
 
+template <int K, int KY>
+static znni_status launch_kprep_yb_r(const LayerPlan& L, hipStream_t st)
+{
+    const Dims& d = L.d;
+    const int nch = (L.f + 7) / 8;
+    const int items = nch * 4 * L.Mp;
+    const float scale = (float)(1.0 / ((double)d.Ny * d.Nz * XB));
+    k_kprep_yb_r<K, KY><<<dim3((items + 255) / 256, (d.Ny + KR_OY - 1) / KR_OY, d.zc), dim3(256), 0, st>>>(
+        L.A1, L.A, L.twy, d.Ny, L.fp, L.Mp, nch, scale);
+    if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
+    return ZNNI_OK;
+}
+
 template <int K>
 static znni_status launch_kprep_yb_k(const LayerPlan& L, hipStream_t st)
 {
     const Dims& d = L.d;
+    switch (d.ky) {                    // up to 5 taps along y: A1 values in registers; more: the general kernel
+        case 1: return launch_kprep_yb_r<K, 1>(L, st);
+        case 2: return launch_kprep_yb_r<K, 2>(L, st);
+        case 3: return launch_kprep_yb_r<K, 3>(L, st);
+        case 4: return launch_kprep_yb_r<K, 4>(L, st);
+        case 5: return launch_kprep_yb_r<K, 5>(L, st);
+    }
     const int nch = (L.f + 7) / 8;
     const int items = nch * 4 * L.Mp;
     const float scale = (float)(1.0 / ((double)d.Ny * d.Nz * XB));
@@ -329,9 +418,6 @@ static znni_status launch_kprep_yb_k(const LayerPlan& L, hipStream_t st)
 znni_status launch_kprep_yb(const LayerPlan& L, hipStream_t st)
 {
     switch (L.d.kx) {
-        case 1: return launch_kprep_yb_k<1>(L, st);
-        case 2: return launch_kprep_yb_k<2>(L, st);
-        case 3: return launch_kprep_yb_k<3>(L, st);
         case 4: return launch_kprep_yb_k<4>(L, st);
         case 5: return launch_kprep_yb_k<5>(L, st);
     }

@@ -383,7 +383,10 @@ XDIRECT = [(1, 3, 2, (9, 16, 16), (1, 3, 3)), (1, 5, 17, (37, 12, 20), (2, 3, 2)
            (1, 33, 96, (77, 8, 12), (5, 2, 3)), (3, 24, 4, (8, 12, 10), (5, 3, 2)), (1, 17, 3, (300, 8, 8), (4, 2, 2)),
            # ... output images in row blocks of different heights (five tiles = 3 + 2, four = 2 + 2, seven = 3 + 2 + 2)
            (1, 16, 80, (50, 8, 10), (5, 2, 2)), (1, 24, 64, (37, 10, 8), (4, 3, 2)), (2, 17, 112, (30, 8, 8), (5, 2, 2)),
-           (1, 16, 70, (170, 8, 8), (4, 2, 2))]
+           (1, 16, 70, (170, 8, 8), (4, 2, 2)),
+           # ... kernels of one and of more than five taps along y (the kernel transform of this route has a form for up
+           # to five and a general one), more than 32 transform bins along y
+           (1, 16, 16, (30, 12, 8), (4, 1, 3)), (1, 17, 20, (40, 16, 8), (5, 7, 2)), (1, 16, 5, (20, 45, 8), (5, 4, 3))]
 
 
 @pytest.mark.parametrize("shape", XDIRECT, ids=lambda s: "S%d_f%dx%d_n%s_k%s" % (s[0], s[1], s[2], "x".join(map(str, s[3])), "x".join(map(str, s[4]))))
