@@ -97,19 +97,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
         xmask[r] = (gs < S && gox < N) ? 1.f : 0.f;
         xoff[r] = (size_t)min(gs, S - 1) * f * N + min(gox, N - 1);
     }
-    const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
+    // step-1 left operands of this wave's two images, ic0 + 2*wave + h: A[(i/4)][a][i%4][j] of the pencil, so a chunk
+    // of eight images later is 2 * k * 4 * Mp elements further (32-bit offsets: the shape limits of the layer call
+    // see to it).  Images in [fp, fp + 4) of a last half chunk are read where they would lie (the next pencil's
+    // first rows, or the zeroed padding behind the last pencil) and masked below.
+    int a_off[2], a_tap[KS];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) a_off[h] = (((2 * wave + h) >> 2) * k * 4 + ((2 * wave + h) & 3)) * Mp + j0 + l16;
+#pragma unroll
+    for (int st = 0; st < KS; ++st) a_tap[st] = min(4 * st + kk, k - 1) * 4 * Mp;      // surplus taps meet a zero twiddle
+    const int a_chunk = 2 * k * 4 * Mp;
     float2 xreg[XR], areg[2][KS];
     auto request = [&](int ic0) {
 #pragma unroll
         for (int r = 0; r < XR; ++r) xreg[r] = Xp[xoff[r] + (size_t)min(ic0 + xi[r], f - 1) * N];
+        const float2* ac = Ap + (ic0 >> 3) * a_chunk;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ic = min(ic0 + 2 * wave + h, fp - 1);
-            const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int st = 0; st < KS; ++st)           // surplus taps meet a zero twiddle
-                areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
-        }
+            for (int st = 0; st < KS; ++st) areg[h][st] = ac[a_off[h] + a_tap[st]];
     };
     request(0);
 
@@ -256,26 +262,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
     const bool lowcol = l16 < 8;
     const float2* xs = Xp + (size_t)min(s0 + (l16 & 7), S - 1) * f * N;
     const int oxa = min(ox0 + 4 * wave, N - 2), oxb = min(ox0 + 4 * wave + 2, N - 2);     // N is even
+    // (offsets inside an input's images and inside a pencil's kernel transforms fit 32 bits: the shape limits of the
+    // layer call see to it)
+    const int x_last = (f - 1) * N;
     auto request_x = [&](float4 (&x)[MB_IC / 4][2], int ic0) {
 #pragma unroll
         for (int st = 0; st < MB_IC / 4; ++st) {
-            const float2* row = xs + (size_t)min(ic0 + 4 * st + kk, f - 1) * N;
+            const float2* row = xs + min((ic0 + 4 * st + kk) * N, x_last);
             x[st][0] = *reinterpret_cast<const float4*>(row + oxa);
             x[st][1] = *reinterpret_cast<const float4*>(row + oxb);
         }
     };
-    // step-1 left operands of this wave's two images
-    const size_t astep = (size_t)4 * Mp;             // from tap a to tap a+1 in A
+    // step-1 left operands of this wave's two images, ic0 + 2*wave + h: A[(i/4)][a][i%4][j] of the pencil, so a chunk
+    // of eight images later is 2 * k * 4 * Mp elements further.  Images in [fp, fp + 4) of a last half chunk are
+    // read where they would lie (the next pencil's first rows, or the zeroed padding behind the last pencil) and
+    // masked below.
+    int a_off[2], a_tap[KS];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) a_off[h] = (((2 * wave + h) >> 2) * k * 4 + ((2 * wave + h) & 3)) * Mp + j0 + l16;
+#pragma unroll
+    for (int st = 0; st < KS; ++st) a_tap[st] = min(4 * st + kk, k - 1) * 4 * Mp;      // surplus taps meet a zero twiddle
+    const int a_chunk = 2 * k * 4 * Mp;
     float2 areg[2][KS];
     auto request_a = [&](int ic0) {
+        const float2* ac = Ap + (ic0 >> 3) * a_chunk;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ic = min(ic0 + 2 * wave + h, fp - 1);
-            const float2* arow = Ap + ((size_t)(ic >> 2) * k * 4 + (ic & 3)) * Mp + j0 + l16;
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int st = 0; st < KS; ++st)           // surplus taps meet a zero twiddle
-                areg[h][st] = arow[(size_t)min(4 * st + kk, k - 1) * astep];
-        }
+            for (int st = 0; st < KS; ++st) areg[h][st] = ac[a_off[h] + a_tap[st]];
     };
 
     floatx4 p1[4], p2[4];                            // step-2 accumulators, ox = ox0 + 4*wave + q: p1 collects the
