@@ -85,17 +85,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
     // what this thread stages per chunk: eight image values (element e = t + 256 r of [i][s][ox]) and the step-1
     // left operands of its wave's two images; both are requested one chunk ahead and wait in registers
     constexpr int XR = MB_IC * 16 * 16 / 256;
+    // Inputs, bins and images beyond the tensor are read from clamped (valid, finite) places and need no mask: their
+    // products land in tile columns or bins that are never stored, or meet kernel-spectrum values that are zero
+    // (the kernel transforms of images in [f, fp) are zero, those beyond are masked in step 1).
     size_t xoff[XR];                                 // offset of (s, ox) inside the pencil, image index excluded
-    float xmask[XR];
     int xi[XR];
 #pragma unroll
     for (int r = 0; r < XR; ++r) {
         const int e = t + 256 * r;
         const int oxl = e & 15, s = (e >> 4) & 15;
         xi[r] = e >> 8;
-        const int gs = s0 + s, gox = ox0 + oxl;
-        xmask[r] = (gs < S && gox < N) ? 1.f : 0.f;
-        xoff[r] = (size_t)min(gs, S - 1) * f * N + min(gox, N - 1);
+        xoff[r] = (size_t)min(s0 + s, S - 1) * f * N + min(ox0 + oxl, N - 1);
     }
     // step-1 left operands of this wave's two images, ic0 + 2*wave + h: A[(i/4)][a][i%4][j] of the pencil, so a chunk
     // of eight images later is 2 * k * 4 * Mp elements further (32-bit offsets: the shape limits of the layer call
@@ -125,12 +125,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
 
     for (int ic0 = 0; ic0 < f; ic0 += MB_IC) {
         __syncthreads();                             // the previous chunk has been consumed
-        // ---- image values of the chunk: Xl[ox][i][s], zero outside the tensor
+        // ---- image values of the chunk: Xl[ox][i][s]
 #pragma unroll
         for (int r = 0; r < XR; ++r) {
             const int e = t + 256 * r;
-            const float mk = ic0 + xi[r] < f ? xmask[r] : 0.f;
-            Xl[(e & 15) * MB_XP + (e >> 4)] = make_float2(xreg[r].x * mk, xreg[r].y * mk);
+            Xl[(e & 15) * MB_XP + (e >> 4)] = xreg[r];
         }
         // ---- step 1 for images ic0 + 2*wave, ic0 + 2*wave + 1
 #pragma unroll
@@ -197,18 +196,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
                     make_float2(p1[q][e] - p2[q][e], p3[q][e] - p1[q][e] - p2[q][e]);
     }
     __syncthreads();
-    for (int e = t; e < 16 * 16 * 16; e += 256) {
-        const int oxl = e & 15, s = (e >> 4) & 15, j = e >> 8;
-        const int gs = s0 + s, gj = j0 + j, gox = ox0 + oxl;
-        if (gs >= S || gj >= fo || gox >= N) continue;
-        float2 v = Ol[(j * 16 + s) * MB_OP + oxl];
-        float2* dst = Yp + ((size_t)gs * fo + gj) * N + gox;
-        if (accumulate) {
-            const float2 old = *dst;
-            v.x += old.x;
-            v.y += old.y;
+    // thread = (input s, bin oxl) of the tile, walking the tile's output images: one address, then a constant stride
+    {
+        const int oxl = t & 15, s = t >> 4;
+        const int gs = s0 + s, gox = ox0 + oxl;
+        if (gs < S && gox < N) {
+            float2* dst = Yp + ((size_t)gs * fo + j0) * N + gox;
+            const float2* src = Ol + s * MB_OP + oxl;
+            const int nj = min(16, fo - j0);
+            for (int j = 0; j < nj; ++j) {
+                float2 v = src[j * 16 * MB_OP];
+                if (accumulate) {
+                    const float2 old = dst[(size_t)j * N];
+                    v.x += old.x;
+                    v.y += old.y;
+                }
+                dst[(size_t)j * N] = v;
+            }
         }
-        *dst = v;
     }
 }
 
@@ -376,18 +381,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
                     p1[q][e] + p2[q][e];
     }
     __syncthreads();
-    for (int e = t; e < 16 * 16 * 16; e += 256) {
-        const int oxl = e & 15, s = (e >> 4) & 15, j = e >> 8;
-        const int gs = s0 + s, gj = j0 + j, gox = ox0 + oxl;
-        if (gs >= S || gj >= fo || gox >= N) continue;
-        float2 v = Ol[(j * 16 + s) * MB_OP + oxl];
-        float2* dst = Yp + ((size_t)gs * fo + gj) * N + gox;
-        if (accumulate) {
-            const float2 old = *dst;
-            v.x += old.x;
-            v.y += old.y;
+    // thread = (input s, bin oxl) of the tile, walking the tile's output images: one address, then a constant stride
+    {
+        const int oxl = t & 15, s = t >> 4;
+        const int gs = s0 + s, gox = ox0 + oxl;
+        if (gs < S && gox < N) {
+            float2* dst = Yp + ((size_t)gs * fo + j0) * N + gox;
+            const float2* src = Ol + s * MB_OP + oxl;
+            const int nj = min(16, fo - j0);
+            for (int j = 0; j < nj; ++j) {
+                float2 v = src[j * 16 * MB_OP];
+                if (accumulate) {
+                    const float2 old = dst[(size_t)j * N];
+                    v.x += old.x;
+                    v.y += old.y;
+                }
+                dst[(size_t)j * N] = v;
+            }
         }
-        *dst = v;
     }
 }
 
