@@ -227,9 +227,11 @@ def test_primitive_choice_follows_kernel_size_and_image_count():
     assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 0, 0x100000, 16, None) == -4
     # the form hints of the transform route do not change what a call does when the direct route is picked: they
     # pass validation (the call goes on to the workspace check) unless both are given
-    for hint in (4, 8, 1 | 4):
+    for hint in (4, 8, 1 | 4, 16, 32, 64, 128, 64 | 128 | 8):
         assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, hint, 0x100000, 16, None) == -4
     assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 4 | 8, 0x100000, 16, None) == -5
+    assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 16 | 32, 0x100000, 16, None) == -5
+    assert L.znni_conv3d_v(1, 1, 48, _i3(128, 128, 128), _i3(3, 3, 3), p, p, None, p, 256, 0x100000, 16, None) == -5
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), None, p, None, p, 0, 0x100000, 1 << 20, None) == -1
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p, 2, 0x100000, 1 << 20, None) == -5
     assert L.znni_conv3d_direct_v(1, 1, 1, _i3(8, 8, 8), _i3(3, 3, 3), p, p, None, p + 1, 0, 0x100000, 1 << 20, None) == -7
