@@ -18,7 +18,9 @@
 // P3 = (ar+ai)(br+bi)).  The result leaves through LDS so that stores run along ox.
 //
 // Two kernels, by batch size:
-//  * k_mac_batch (more than 8 inputs): the image values of a chunk are staged in LDS ([ox][i][s]) with coalesced
+//  * k_mac_batch (more than 8 inputs; with more than 16, eight waves take two tiles of 16 inputs per workgroup, so that
+//    a generated kernel-spectrum tile serves 32 inputs: a third of the matrix instructions of the 16-input form
+//    regenerate spectra, a fifth of this one's; 64 x 80 -> 80 images of 55^3, 7^3 kernels: 4.96 -> 4.46 ms): the image values of a chunk are staged in LDS ([ox][i][s]) with coalesced
 //    loads; step 2 uses three real products per complex one.
 //  * k_mac_batch8 (at most 8 inputs): real and imaginary parts sit side by side in the 16 columns of the step-2
 //    tile, [Yr | Yi] += Wr [Xr | Xi] + Wi [-Xi | Xr]: two full products instead of three half-empty ones and no
@@ -33,19 +35,24 @@ namespace znni {
 
 constexpr int MB_IC = 8;              // input images per chunk
 constexpr int MB_WP = 132;            // floats between consecutive ox in the Wt arrays (8*16 + padding)
-constexpr int MB_XP = 129;            // float2 between consecutive ox in the image array (8*16 + padding)
 constexpr int MB_OP = 17;             // float2 between consecutive (j, s) rows of the output tile (16 ox + padding)
 constexpr int MB_WB = 2 * 16 * MB_WP; // floats per Wt buffer (real array, then imaginary array)
 
 // (one and two steps are held to 128 registers, four waves per SIMD: 3-7 % faster for 5^3 to 8^3 kernels)
-template <int KS>      // KS = steps of four taps: (k + 3) / 4, 1 to 3
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
+// NS = tiles of 16 inputs per workgroup: 1 (four waves), or 2 (eight waves: waves 0-3 take the first tile, 4-7 the
+// second; each generated kernel-spectrum tile then serves 32 inputs and each wave generates one image's share of it
+// instead of two)
+template <int KS, int NS>      // KS = steps of four taps: (k + 3) / 4, 1 to 3
+__global__ __launch_bounds__(256 * NS) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 4 : 3)))) void k_mac_batch(const float2* __restrict__ Xt, const float2* __restrict__ A,
                                                    float2* __restrict__ Yt, const float2* __restrict__ twg, int N,
                                                    int S, int f, int fo, int k, int fp, int Mp, int noxt, int njt,
                                                    int nsc, int npencils, int accumulate)
 {
-    // LDS: Wt as two float arrays (real, imaginary) [16 ox][MB_WP], image values float2 [16 ox][MB_XP]; the
-    // output tile (float2 [16 j][16 s][MB_OP]) reuses the same memory after the last chunk.
+    // LDS: Wt as two float arrays (real, imaginary) [16 ox][MB_WP], image values float2 [16 ox][XP]; the
+    // output tile (float2 [16 j][16 NS s][MB_OP]) reuses the same memory after the last chunk.
+    constexpr int NT = 256 * NS, SW = 16 * NS;           // threads, inputs of the workgroup
+    constexpr int XP = MB_IC * SW + 1;                   // float2 between consecutive ox in the image array
+    constexpr int HPW = 2 / NS;                          // images a wave generates the spectrum tile of, per chunk
     extern __shared__ float lds[];
     float* Wr = lds;
     float* Wi = Wr + 16 * MB_WP;
@@ -55,7 +62,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
     if (!mac_block(noxt * njt * nsc, npencils, pencil, sub)) return;
     const int oxt = sub % noxt, jt = (sub / noxt) % njt, sc = sub / (noxt * njt);
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63, l16 = lane & 15, kk = lane >> 4;
-    const int ox0 = oxt * 16, j0 = jt * 16, s0 = sc * 16;
+    const int w4 = wave & 3, sw = wave >> 2;             // group of four bins, tile of 16 inputs
+    const int ox0 = oxt * 16, j0 = jt * 16, s0 = sc * SW;
     const float2* Xp = Xt + (size_t)pencil * S * f * N;
     const float2* Ap = A + (size_t)pencil * k * fp * Mp;
     float2* Yp = Yt + (size_t)pencil * S * fo * N;
@@ -84,7 +92,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
 
     // what this thread stages per chunk: eight image values (element e = t + 256 r of [i][s][ox]) and the step-1
     // left operands of its wave's two images; both are requested one chunk ahead and wait in registers
-    constexpr int XR = MB_IC * 16 * 16 / 256;
+    constexpr int XR = MB_IC * 16 * SW / NT;
     // Inputs, bins and images beyond the tensor are read from clamped (valid, finite) places and need no mask: their
     // products land in tile columns or bins that are never stored, or meet kernel-spectrum values that are zero
     // (the kernel transforms of images in [f, fp) are zero, those beyond are masked in step 1).
@@ -92,34 +100,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
     int xi[XR];
 #pragma unroll
     for (int r = 0; r < XR; ++r) {
-        const int e = t + 256 * r;
-        const int oxl = e & 15, s = (e >> 4) & 15;
-        xi[r] = e >> 8;
+        const int e = t + NT * r;
+        const int oxl = e & 15, s = (e >> 4) % SW;
+        xi[r] = e / (16 * SW);
         xoff[r] = (size_t)min(s0 + s, S - 1) * f * N + min(ox0 + oxl, N - 1);
     }
     // step-1 left operands of this wave's two images, ic0 + 2*wave + h: A[(i/4)][a][i%4][j] of the pencil, so a chunk
     // of eight images later is 2 * k * 4 * Mp elements further (32-bit offsets: the shape limits of the layer call
     // see to it).  Images in [fp, fp + 4) of a last half chunk are read where they would lie (the next pencil's
     // first rows, or the zeroed padding behind the last pencil) and masked below.
-    int a_off[2], a_tap[KS];
+    int a_off[HPW], a_tap[KS];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) a_off[h] = (((2 * wave + h) >> 2) * k * 4 + ((2 * wave + h) & 3)) * Mp + j0 + l16;
+    for (int h = 0; h < HPW; ++h)
+        a_off[h] = (((HPW * wave + h) >> 2) * k * 4 + ((HPW * wave + h) & 3)) * Mp + j0 + l16;
 #pragma unroll
     for (int st = 0; st < KS; ++st) a_tap[st] = min(4 * st + kk, k - 1) * 4 * Mp;      // surplus taps meet a zero twiddle
     const int a_chunk = 2 * k * 4 * Mp;
-    float2 xreg[XR], areg[2][KS];
+    float2 xreg[XR], areg[HPW][KS];
     auto request = [&](int ic0) {
 #pragma unroll
         for (int r = 0; r < XR; ++r) xreg[r] = Xp[xoff[r] + (size_t)min(ic0 + xi[r], f - 1) * N];
         const float2* ac = Ap + (ic0 >> 3) * a_chunk;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < HPW; ++h)
 #pragma unroll
             for (int st = 0; st < KS; ++st) areg[h][st] = ac[a_off[h] + a_tap[st]];
     };
     request(0);
 
-    floatx4 p1[4], p2[4], p3[4];                     // step-2 accumulators: ox = ox0 + 4*wave + q
+    floatx4 p1[4], p2[4], p3[4];                     // step-2 accumulators: ox = ox0 + 4*w4 + q
 #pragma unroll
     for (int q = 0; q < 4; ++q) { p1[q] = floatx4{0.f, 0.f, 0.f, 0.f}; p2[q] = p1[q]; p3[q] = p1[q]; }
 
@@ -128,13 +137,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
         // ---- image values of the chunk: Xl[ox][i][s]
 #pragma unroll
         for (int r = 0; r < XR; ++r) {
-            const int e = t + 256 * r;
-            Xl[(e & 15) * MB_XP + (e >> 4)] = xreg[r];
+            const int e = t + NT * r;
+            Xl[(e & 15) * XP + (e >> 4)] = xreg[r];
         }
-        // ---- step 1 for images ic0 + 2*wave, ic0 + 2*wave + 1
+        // ---- step 1 for this wave's images of the chunk
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int il = 2 * wave + h;
+        for (int h = 0; h < HPW; ++h) {
+            const int il = HPW * wave + h;
             const float mi = ic0 + il < fp ? 1.f : 0.f;
             floatx4 q1 = floatx4{0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
 #pragma unroll
@@ -166,11 +175,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
             float2 x_[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int oxl = 4 * wave + q;
+                const int oxl = 4 * w4 + q;
                 const int o = st * 64 + lane;
                 wr_[q] = Wr[oxl * MB_WP + o];
                 wi_[q] = Wi[oxl * MB_WP + o];
-                x_[q] = Xl[oxl * MB_XP + o];
+                x_[q] = Xl[oxl * XP + (4 * st + kk) * SW + 16 * sw + l16];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -192,7 +201,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                Ol[((4 * kk + e) * 16 + l16) * MB_OP + 4 * wave + q] =
+                Ol[((4 * kk + e) * SW + 16 * sw + l16) * MB_OP + 4 * w4 + q] =
                     make_float2(p1[q][e] - p2[q][e], p3[q][e] - p1[q][e] - p2[q][e]);
     }
     __syncthreads();
@@ -202,10 +211,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((KS <= 2 ? 
         const int gs = s0 + s, gox = ox0 + oxl;
         if (gs < S && gox < N) {
             float2* dst = Yp + ((size_t)gs * fo + j0) * N + gox;
-            const float2* src = Ol + s * MB_OP + oxl;
+            const float2* src = Ol + s * MB_OP + oxl;        // s < 16 NS
             const int nj = min(16, fo - j0);
             for (int j = 0; j < nj; ++j) {
-                float2 v = src[j * 16 * MB_OP];
+                float2 v = src[j * SW * MB_OP];
                 if (accumulate) {
                     const float2 old = dst[(size_t)j * N];
                     v.x += old.x;
@@ -413,20 +422,27 @@ znni_status launch_mac_batch(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     if (!mac_batch_available(L)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const int N = L.d.Nx;
+    // more than 16 inputs: two tiles of 16 inputs per workgroup share each generated kernel-spectrum tile
+    const int NS = L.S > 16 ? 2 : 1;
     const size_t lds_main = L.S <= 8 ? sizeof(float) * 2 * MB_WB
-                                     : sizeof(float) * MB_WB + sizeof(float2) * 16 * MB_XP;
-    const size_t lds_out = sizeof(float2) * 16 * 16 * MB_OP;
+                                     : sizeof(float) * MB_WB + sizeof(float2) * 16 * (MB_IC * 16 * NS + 1);
+    const size_t lds_out = sizeof(float2) * 16 * 16 * (L.S <= 8 ? 1 : NS) * MB_OP;
     const size_t lds = lds_main > lds_out ? lds_main : lds_out;
-    const int noxt = (N + 15) / 16, njt = (L.fo + 15) / 16, nsc = (L.S + 15) / 16;
+    const int noxt = (N + 15) / 16, njt = (L.fo + 15) / 16, nsc = (L.S + 16 * NS - 1) / (16 * NS);
     const int npencils = L.d.zc * L.d.Ny;
     const long long blocks = (long long)((npencils + 7) / 8) * noxt * njt * nsc * 8;
     if (blocks > 0x7fffffffll) return ZNNI_ERR_SHAPE;
     // one instantiation per number of tap steps: the loops over them are straight-line code
     const int ks = (L.d.kx + 3) / 4;
     auto* kernel = L.S <= 8 ? (ks == 1 ? k_mac_batch8<1> : ks == 2 ? k_mac_batch8<2> : k_mac_batch8<3>)
-                            : (ks == 1 ? k_mac_batch<1> : ks == 2 ? k_mac_batch<2> : k_mac_batch<3>);
-    kernel<<<dim3((unsigned)blocks), dim3(256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo, L.d.kx, L.fp,
-                                                           L.Mp, noxt, njt, nsc, npencils, accumulate);
+                   : NS == 1 ? (ks == 1 ? k_mac_batch<1, 1> : ks == 2 ? k_mac_batch<2, 1> : k_mac_batch<3, 1>)
+                             : (ks == 1 ? k_mac_batch<1, 2> : ks == 2 ? k_mac_batch<2, 2> : k_mac_batch<3, 2>);
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return ZNNI_ERR_HIP;
+    kernel<<<dim3((unsigned)blocks), dim3(L.S > 16 ? 512 : 256), lds, st>>>(L.buf0, L.A, L.Yt, L.twx, N, L.S, L.f, L.fo,
+                                                                          L.d.kx, L.fp, L.Mp, noxt, njt, nsc, npencils,
+                                                                          accumulate);
     if (hipGetLastError() != hipSuccess) return ZNNI_ERR_HIP;
     return ZNNI_OK;
 }

@@ -351,7 +351,10 @@ def test_matrix_core_mac_agrees_with_plain_mac(oracle, shape):
 # partial second chunk of input images.
 BATCH = [(2, 3, 5, 16, 3), (4, 4, 4, 20, 5), (5, 2, 3, 24, 2), (8, 32, 32, 16, 7), (9, 6, 40, 18, 4), (20, 3, 7, 16, 3),
          (3, 70, 9, 16, 1), (8, 5, 70, 32, 6), (4, 3, 3, 5, 2), (12, 3, 3, 5, 2), (8, 9, 5, 22, 5), (7, 12, 4, 10, 3),
-         (4, 3, 5, 14, 9), (10, 2, 3, 13, 11), (9, 5, 3, 12, 12)]      # 9 to 12 taps: three steps of four
+         (4, 3, 5, 14, 9), (10, 2, 3, 13, 11), (9, 5, 3, 12, 12),      # 9 to 12 taps: three steps of four
+         # more than 16 inputs: workgroups of two tiles of 16 inputs; a second tile with one input, several workgroups
+         # along the batch with a ragged last one, a partial chunk of input images
+         (33, 9, 17, 16, 7), (40, 5, 20, 12, 5), (70, 12, 4, 10, 3)]
 
 
 @pytest.mark.parametrize("shape", BATCH, ids=lambda s: "S%d_f%dx%d_n%d_k%d" % s)
