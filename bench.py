@@ -158,6 +158,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="benchmark layer 1..5 (default: the largest)")
+    ap.add_argument("--shape", default=None, metavar="S,f,fo,n,k",
+                    help="a layer of the same kind that is not one of the five (cubic images and kernels, bias and "
+                         "transfer function on), e.g. 8,80,80,107,5; overrides --config")
     ap.add_argument("--route", choices=("default", "single", "batch", "xdirect", "xblock"), default="default",
                     help="force a form of the multiply-accumulate stage (default: the library picks)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
@@ -173,6 +176,9 @@ def main():
     from paper_1606_05688_amd import workloads as W
 
     layer = W.CONFIGS[args.config - 1]
+    if args.shape:
+        S_, f_, fo_, n_, k_ = (int(v) for v in args.shape.split(","))
+        layer = W.Layer(f"S{S_}_{n_}c_f{f_}x{fo_}_k{k_}", S=S_, f=f_, fo=fo_, n=n_, k=k_)
     route = None if args.route == "default" else args.route
     dev = torch.device("cuda:0")
     S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
