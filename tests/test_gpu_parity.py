@@ -411,6 +411,29 @@ def test_untransformed_x_axis_route_matches_oracle_and_transformed_route(oracle,
     assert np.all(np.abs(xb - single) <= 0.1 * tol)
 
 
+ALL_FORMS = (False, "single", "batch", "xdirect", "xblock", "generic_passes")
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_random_shapes_match_oracle_in_every_form(oracle, seed):
+    """Seeded random layers (batches of 1 to 40, 1 to 40 input and 1 to 100 output images, per-axis image sizes up to
+    72 and kernels of 1 to 9 taps, drawn until the oracle's work stays below about a billion multiply-adds): every
+    form of the multiply-accumulate and both sets of pass kernels against the oracle, on every voxel."""
+    r = np.random.default_rng(7000 + seed)
+    while True:
+        S = int(r.choice([1, 1, 1, 2, 3, 5, 8, 9, 17, 24, 40]))
+        f, fo = int(r.integers(1, 41)), int(r.integers(1, 101))
+        k = tuple(int(v) for v in r.integers(1, 10, 3))
+        n = tuple(int(k[a] + r.integers(0, 72 - k[a] + 1)) for a in range(3))
+        macs = S * f * fo * k[0] * k[1] * k[2] * np.prod([n[a] - k[a] + 1 for a in range(3)], dtype=np.float64)
+        vox = S * max(f, fo) * np.prod(n, dtype=np.float64)
+        if macs <= 1.2e9 and vox <= 3e7:
+            break
+    inp, w, b = _rand_v(7100 + seed, S, f, fo, n, k)
+    relu, bias = bool(seed & 1), (b if seed % 3 else None)
+    _check_full(oracle, inp, w, bias, relu, f"random seed {seed}: S={S} f={f} fo={fo} n={n} k={k}", routes=ALL_FORMS)
+
+
 @pytest.mark.parametrize("route", [False, "single", "batch", "xdirect", "xblock"], ids=lambda r: str(r or "default"))
 def test_stored_kernel_transforms_can_be_kept_between_calls(oracle, route):
     """Inference applies one kernel bank to many inputs: a call that keeps the workspace's stored kernel transforms
