@@ -235,8 +235,10 @@ static znni_status launch_xd(const LayerPlan& L, int accumulate, hipStream_t st)
     g.nox = d.nox; g.ldx = d.ldx; g.ldxo = d.ldxo;
     // columns (input of the batch, xo): blocks of 128 where the row block leaves room, a 64-wide remainder
     const int Ct = L.S * d.nox;
-    g.n2 = (WIDE && Ct >= 128) ? Ct / 128 : 0;
-    g.n1 = (Ct - g.n2 * 128 + 63) / 64;
+    // (a remainder of more than 64 columns goes to one more 128-wide block, ragged, rather than to two 64-wide ones:
+    // the same column slots, half the reads of the kernel transforms)
+    g.n2 = WIDE ? (Ct + 63) / 128 : 0;
+    g.n1 = Ct > g.n2 * 128 ? (Ct - g.n2 * 128 + 63) / 64 : 0;
     g.col1 = g.n2 * 128;
     g.nmblk = L.mac_nmblk;
     g.npencils = d.zc * d.Ny;
@@ -251,7 +253,7 @@ static znni_status launch_xd(const LayerPlan& L, int accumulate, hipStream_t st)
 template <int K>
 static znni_status launch_xd_tiles(const LayerPlan& L, int accumulate, hipStream_t st)
 {
-    const bool wide = L.mac_RTW <= 3 && L.S * L.d.nox >= 128;
+    const bool wide = L.mac_RTW <= 3 && L.S * L.d.nox > 64;
     if (wide) {
         switch (L.mac_RTW) {
             case 1: return launch_xd<1, K, true>(L, accumulate, st);
