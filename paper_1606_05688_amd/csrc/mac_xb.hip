@@ -437,8 +437,9 @@ static znni_status launch_xb(const LayerPlan& L, int accumulate, int m_base, int
     g.nch = (L.f + 7) / 8;
     const int V = XB - d.kx + 1;
     g.nblk = (d.nox + V - 1) / V;
-    g.n2 = WIDE ? g.nblk / 32 : 0;
-    g.n1 = (g.nblk - g.n2 * 32 + 15) / 16;
+    // (a remainder of more than 16 blocks goes to one more 32-block tile, ragged, rather than to two 16-block ones)
+    g.n2 = WIDE ? (g.nblk + 15) / 32 : 0;
+    g.n1 = g.nblk > g.n2 * 32 ? (g.nblk - g.n2 * 32 + 15) / 16 : 0;
     g.blk1 = g.n2 * 32;
     g.nmblk = nmblk;
     g.m_base = m_base;
@@ -469,7 +470,7 @@ znni_status launch_mac_xb(const LayerPlan& L, int accumulate, hipStream_t st)
 {
     if (!mac_xb_available(L)) return ZNNI_ERR_UNSUPPORTED_SIZE;
     const int V = XB - L.d.kx + 1;
-    return (L.d.nox + V - 1) / V >= 32 ? launch_xb_rows<true>(L, accumulate, st)
+    return (L.d.nox + V - 1) / V > 16 ? launch_xb_rows<true>(L, accumulate, st)
                                        : launch_xb_rows<false>(L, accumulate, st);
 }
 
