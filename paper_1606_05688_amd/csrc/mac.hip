@@ -353,8 +353,10 @@ void plan_mac(LayerPlan* L)
     L->mac_nmblk = nmblk;
     L->Mp = nmblk * RTW * 16;
     const int Ct = L->S * L->d.Nx;
-    L->mac_n2 = (RTW <= 3 && Ct >= 128) ? Ct / 128 : 0;  // room for 2 x RTW accumulator tiles per wave
-    L->mac_n1 = (Ct - L->mac_n2 * 128 + 63) / 64;
+    // 128-wide column blocks where there is room for 2 x RTW accumulator tiles per wave; a remainder of more than 64
+    // columns goes to one more of them, ragged, rather than to two 64-wide blocks
+    L->mac_n2 = (RTW <= 3 && Ct > 64) ? (Ct + 63) / 128 : 0;
+    L->mac_n1 = Ct > L->mac_n2 * 128 ? (Ct - L->mac_n2 * 128 + 63) / 64 : 0;
     // image-spectrum block kept in LDS: about 48 KB at most, so that three workgroups share a CU
     const int nwmax = L->mac_n2 ? 128 : 64;
     int FC = (48 * 1024) / (nwmax * (int)sizeof(float2));
